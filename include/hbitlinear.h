@@ -1,0 +1,155 @@
+/*
+ * libhbitlinear - the H-BitLinear forward pass of BitNet v2 (Section 2.1) for
+ * AMD MI355X (gfx950), as a C-ABI library of hand-written HIP kernels.
+ *
+ *   Y = Qw(W) . Q_INT8/4(X_r),   X_r = Hadamard(X)                     (Eq. 7)
+ *
+ * Conventions shared by every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller (the library
+ *     never allocates, frees or keeps them); scalars and sizes are by value.
+ *   - X is [T, K] row-major (token-major, K features contiguous).  W is
+ *     [N, K] row-major (out x in), so Y[T, N] = Xq . Wq^T - the row form of
+ *     Eq. 7 - and the Hadamard transform (Eq. 3-4) runs along K, n = K = 2^m.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without synchronising.
+ *   - Every call returns a status: HBL_OK or a negative HBL_E_* code.  On an
+ *     error nothing has been launched.  No exception crosses this boundary.
+ *   - bf16 tensors are 16-bit patterns (the upper half of an IEEE fp32).
+ *   - `eps` is the epsilon of Eq. 1, 5 and 6 (the paper gives no value; the
+ *     tests and the benchmark use 1e-5).  It is added exactly as printed:
+ *     inside the quantiser gain, not in the outer dequantisation factor.
+ *   - round() of Eq. 2 is round-half-to-even.
+ *   - Inputs containing NaN or Inf are not checked and give undefined output.
+ *
+ * Shape limits (HBL_E_SHAPE otherwise): T >= 0 (T == 0 is a no-op);
+ * K a multiple of 128, 128 <= K <= 16384, and a power of two when the
+ * Hadamard transform is applied; N a positive multiple of 32.
+ */
+#ifndef HBITLINEAR_H
+#define HBITLINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define HBL_OK 0
+#define HBL_E_NULL (-1)      /* a required pointer is NULL                              */
+#define HBL_E_SHAPE (-2)     /* a size violates the limits above                        */
+#define HBL_E_BITS (-3)      /* bits is neither 4 nor 8                                 */
+#define HBL_E_DTYPE (-4)     /* x_dtype is neither HBL_F32 nor HBL_BF16                 */
+#define HBL_E_WORKSPACE (-5) /* workspace smaller than the matching *_workspace_bytes() */
+#define HBL_E_HIP (-6)       /* a HIP call failed; see hbl_last_hip_error()             */
+#define HBL_E_ALIGN (-7)     /* a pointer is not aligned to 16 bytes                    */
+
+/* activation storage types */
+#define HBL_F32 0
+#define HBL_BF16 1
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* hbl_strerror(int status);
+/* The hipError_t value behind the most recent HBL_E_HIP on this thread (0 if none). */
+int hbl_last_hip_error(void);
+
+/* ---------------------------------------------------------------------------
+ * Weight set-up (offline, once per weight tensor)
+ * ------------------------------------------------------------------------- */
+
+/* Scratch needed by hbl_ternarize_weights_absmean for an [N, K] tensor. */
+size_t hbl_ternarize_workspace_bytes(int64_t N, int64_t K);
+
+/*
+ * Per-tensor absmean ternary weight quantiser (Eq. 1-2):
+ *   alpha = mean(|W|),  codes = RoundClip(W / (alpha + eps), -1, 1).
+ *   W      [N, K] fp32, read only
+ *   codes  [N, K] int8 out, each -1, 0 or +1; dequantised weight = alpha * codes
+ *   alpha  1 fp32 out (device).  The mean is accumulated in fp64 in a fixed
+ *          order (deterministic) and rounded to fp32 once.
+ *   workspace  device scratch of at least hbl_ternarize_workspace_bytes(N, K)
+ * Any N >= 1, K >= 1 is accepted here (the GEMM limits apply at pack time).
+ */
+int hbl_ternarize_weights_absmean(const float* W, int64_t N, int64_t K, float eps, int8_t* codes,
+                                  float* alpha, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of the packed form of an [N, K] ternary tensor: N*K/4 (2 bits per weight). */
+size_t hbl_packed_bytes(int64_t N, int64_t K);
+
+/*
+ * Pack ternary codes 4 per byte into the library's streaming layout (not in
+ * the paper, which describes no storage format).  The layout is opaque to the
+ * caller: 1 KiB tiles of 32 output rows x 128 input features, ordered so that
+ * one 16-byte load per lane yields matrix-core operands; each weight is
+ * stored as code+1 in {0,1,2}.  hbl_unpack_ternary_2bit is the exact inverse.
+ *   codes  [N, K] int8 in {-1,0,1};   packed  hbl_packed_bytes(N, K) bytes, 16-byte aligned
+ */
+int hbl_pack_ternary_2bit(const int8_t* codes, int64_t N, int64_t K, void* packed, void* stream);
+int hbl_unpack_ternary_2bit(const void* packed, int64_t N, int64_t K, int8_t* codes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Forward pass (the hot path)
+ * ------------------------------------------------------------------------- */
+
+/* Device scratch needed by the two forward calls (activation codes, per-token
+ * dequantisation scale and per-token code sum). */
+size_t hbl_workspace_bytes(int64_t T, int64_t K, int64_t N, int bits);
+
+/*
+ * H-BitLinear forward (Eq. 7 with Eq. 3-6): for every token row
+ *   x_r = H_m x                       fast Walsh-Hadamard transform, fp32,
+ *                                     butterflies with ascending stride then
+ *                                     one multiply by (float)(1/sqrt(K))
+ *   bits == 8:  gamma = max|x_r|,  q = RoundClip(127/(gamma+eps) x_r, -128, 127), s = gamma/127
+ *   bits == 4:  beta  = mean|x_r|, q = RoundClip(sqrt7/(beta+eps) x_r, -8, 7),    s = beta/sqrt7
+ *   y[o] = bf16( (float)(sum_k q[k] c[o][k]) * s * alpha_g(o) )
+ * with int32 accumulation (exact) and round-to-nearest-even to bf16.
+ *   x          [T, K] x_dtype (HBL_F32 or HBL_BF16), read only, 16-byte aligned
+ *   Wq_packed  from hbl_pack_ternary_2bit for an [N, K] tensor
+ *   w_scales   [n_scale_groups] fp32 (device): alpha of each group of
+ *              N/n_scale_groups consecutive output rows (1 = the paper's
+ *              per-tensor scale; 3 for a fused QKV, 2 for up|gate).
+ *              N/n_scale_groups must be a multiple of 32.
+ *   y          [T, N] bf16 out; must not overlap x or the workspace
+ *   workspace  at least hbl_workspace_bytes(T, K, N, bits), 256-byte aligned
+ */
+int hbl_hbitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed,
+                           int64_t N, const float* w_scales, int64_t n_scale_groups, int bits,
+                           float eps, void* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Plain BitLinear forward for the projections that keep their input
+ * distribution (W_qkv, W_up/gate; Section 2, first paragraph): identical to
+ * the call above with x_r = x (no Hadamard transform).  K need not be a power
+ * of two.
+ */
+int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K,
+                                const void* Wq_packed, int64_t N, const float* w_scales,
+                                int64_t n_scale_groups, int bits, float eps, void* y,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Stage-level entry points (parity checks and profiling; same kernels)
+ * ------------------------------------------------------------------------- */
+
+/*
+ * Activation front end only (Eq. 3-6): transform (if hadamard != 0) and quantise.
+ *   codes      [T, K] int8 out in natural feature order
+ *   s_dequant  [T] fp32 out: gamma/127 or beta/sqrt7
+ *   code_sum   [T] int32 out or NULL: sum_k codes[t][k]
+ */
+int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps,
+                   int hadamard, int8_t* codes, float* s_dequant, int32_t* code_sum, void* stream);
+
+/*
+ * Integer contraction only: acc[t][o] = sum_k codes[t][k] * c[o][k] (int32, exact).
+ *   codes [T, K] int8 (any values in [-128,127]);  acc [T, N] int32 out
+ */
+int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+                 int32_t* acc, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HBITLINEAR_H */

@@ -1,0 +1,149 @@
+// C-ABI entry points of libhbitlinear: argument validation and kernel sequencing only.
+#include "hbl_internal.h"
+
+namespace hbl {
+
+static thread_local int g_last_hip_error = 0;
+
+int note_hip_error(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return HBL_E_HIP;
+}
+
+namespace {
+
+int check_gemm_shape(int64_t T, int64_t K, int64_t N, bool hadamard) {
+    if (T < 0 || T > (1 << 24)) return HBL_E_SHAPE;
+    if (K < 128 || K > 16384 || (K % 128) != 0) return HBL_E_SHAPE;
+    if (hadamard && !is_pow2(K)) return HBL_E_SHAPE;
+    if (N < 32 || (N % 32) != 0 || N > (1 << 24)) return HBL_E_SHAPE;
+    if (T * N >= ((int64_t)1 << 40)) return HBL_E_SHAPE;
+    return HBL_OK;
+}
+
+int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+            const float* w_scales, int64_t groups, int bits, float eps, void* y, void* workspace,
+            size_t workspace_bytes, void* stream, bool hadamard) {
+    if (bits != 4 && bits != 8) return HBL_E_BITS;
+    if (x_dtype != HBL_F32 && x_dtype != HBL_BF16) return HBL_E_DTYPE;
+    int rc = check_gemm_shape(T, K, N, hadamard);
+    if (rc != HBL_OK) return rc;
+    if (groups < 1 || (N % groups) != 0 || ((N / groups) % 32) != 0) return HBL_E_SHAPE;
+    if (T == 0) return HBL_OK;
+    if (!x || !Wq_packed || !w_scales || !y || !workspace) return HBL_E_NULL;
+    if (!aligned16(x) || !aligned16(Wq_packed) || !aligned16(y) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return HBL_E_ALIGN;
+    if (workspace_bytes < hbl_workspace_bytes(T, K, N, bits)) return HBL_E_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Workspace ws = carve_workspace(workspace, T, K);
+    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, s);
+    if (rc != HBL_OK) return rc;
+    return launch_ternary_gemm(ws.codes, T, K, Wq_packed, N, ws.s_dequant, ws.code_sum, w_scales, groups, y,
+                               nullptr, s);
+}
+
+}  // namespace
+}  // namespace hbl
+
+using namespace hbl;
+
+extern "C" {
+
+const char* hbl_strerror(int status) {
+    switch (status) {
+        case HBL_OK: return "ok";
+        case HBL_E_NULL: return "a required pointer is NULL";
+        case HBL_E_SHAPE: return "unsupported shape (K: multiple of 128 in [128,16384], power of two with Hadamard; N: multiple of 32; T >= 0)";
+        case HBL_E_BITS: return "bits must be 4 or 8";
+        case HBL_E_DTYPE: return "x_dtype must be HBL_F32 or HBL_BF16";
+        case HBL_E_WORKSPACE: return "workspace too small";
+        case HBL_E_HIP: return "a HIP call failed (see hbl_last_hip_error)";
+        case HBL_E_ALIGN: return "pointer not sufficiently aligned";
+        default: return "unknown status";
+    }
+}
+
+int hbl_last_hip_error(void) { return g_last_hip_error; }
+
+size_t hbl_ternarize_workspace_bytes(int64_t N, int64_t K) {
+    if (N <= 0 || K <= 0) return 0;
+    return ternarize_workspace_bytes(N * K);
+}
+
+int hbl_ternarize_weights_absmean(const float* W, int64_t N, int64_t K, float eps, int8_t* codes, float* alpha,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+    if (!W || !codes || !alpha || !workspace) return HBL_E_NULL;
+    if (N <= 0 || K <= 0 || N > ((int64_t)1 << 40) / K) return HBL_E_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 7u) != 0) return HBL_E_ALIGN;
+    if (workspace_bytes < hbl_ternarize_workspace_bytes(N, K)) return HBL_E_WORKSPACE;
+    return launch_ternarize(W, N * K, eps, codes, alpha, workspace, static_cast<hipStream_t>(stream));
+}
+
+size_t hbl_packed_bytes(int64_t N, int64_t K) {
+    if (N <= 0 || K <= 0) return 0;
+    return (size_t)N * (size_t)K / 4;
+}
+
+int hbl_pack_ternary_2bit(const int8_t* codes, int64_t N, int64_t K, void* packed, void* stream) {
+    if (!codes || !packed) return HBL_E_NULL;
+    int rc = check_gemm_shape(0, K, N, false);
+    if (rc != HBL_OK) return rc;
+    if (!aligned16(codes) || !aligned16(packed)) return HBL_E_ALIGN;
+    return launch_pack(codes, N, K, packed, static_cast<hipStream_t>(stream));
+}
+
+int hbl_unpack_ternary_2bit(const void* packed, int64_t N, int64_t K, int8_t* codes, void* stream) {
+    if (!codes || !packed) return HBL_E_NULL;
+    int rc = check_gemm_shape(0, K, N, false);
+    if (rc != HBL_OK) return rc;
+    if (!aligned16(codes) || !aligned16(packed)) return HBL_E_ALIGN;
+    return launch_unpack(packed, N, K, codes, static_cast<hipStream_t>(stream));
+}
+
+size_t hbl_workspace_bytes(int64_t T, int64_t K, int64_t N, int bits) {
+    (void)N;
+    (void)bits;
+    if (T <= 0 || K <= 0) return 256;
+    return carve_workspace(nullptr, T, K).bytes;
+}
+
+int hbl_hbitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+                           const float* w_scales, int64_t n_scale_groups, int bits, float eps, void* y,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    return forward(x, x_dtype, T, K, Wq_packed, N, w_scales, n_scale_groups, bits, eps, y, workspace,
+                   workspace_bytes, stream, true);
+}
+
+int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+                                const float* w_scales, int64_t n_scale_groups, int bits, float eps, void* y,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    return forward(x, x_dtype, T, K, Wq_packed, N, w_scales, n_scale_groups, bits, eps, y, workspace,
+                   workspace_bytes, stream, false);
+}
+
+int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int hadamard,
+                   int8_t* codes, float* s_dequant, int32_t* code_sum, void* stream) {
+    if (bits != 4 && bits != 8) return HBL_E_BITS;
+    if (x_dtype != HBL_F32 && x_dtype != HBL_BF16) return HBL_E_DTYPE;
+    int rc = check_gemm_shape(T, K, 32, hadamard != 0);
+    if (rc != HBL_OK) return rc;
+    if (T == 0) return HBL_OK;
+    if (!x || !codes || !s_dequant) return HBL_E_NULL;
+    if (!aligned16(x) || !aligned16(codes)) return HBL_E_ALIGN;
+    return launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard != 0, codes, s_dequant, code_sum,
+                             static_cast<hipStream_t>(stream));
+}
+
+int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packed, int64_t N, int32_t* acc,
+                 void* stream) {
+    int rc = check_gemm_shape(T, K, N, false);
+    if (rc != HBL_OK) return rc;
+    if (T == 0) return HBL_OK;
+    if (!codes || !Wq_packed || !acc) return HBL_E_NULL;
+    if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(acc)) return HBL_E_ALIGN;
+    return launch_ternary_gemm(codes, T, K, Wq_packed, N, nullptr, nullptr, nullptr, 1, nullptr, acc,
+                               static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,436 @@
+// Activation front end of H-BitLinear (Section 2.1): online Hadamard transform
+// (Eq. 3-4) fused with the per-token INT8 absmax / INT4 absmean quantiser
+// (Eq. 5-6).  One workgroup owns one token row; the row never leaves registers
+// / LDS between the load of x and the store of the int8 codes.
+//
+// Arithmetic contract (what makes the codes reproducible bit for bit):
+//   - butterflies are single fp32 adds / subtracts, stages in ascending stride
+//     order 1,2,4,...,K/2 - which stage runs in registers, across lanes or
+//     through LDS does not change any value;
+//   - one multiply by c_n = (float)(1/sqrt(K)) after the last stage;
+//   - gamma = max|x_r| (exact); beta = (float)(sum|x_r| in fp64 / K);
+//   - gain = 127/(gamma+eps) or sqrt7/(beta+eps) with IEEE fp32 division,
+//     code = RoundClip(gain * x_r) with round-half-to-even.
+//
+// Index bits of a row of K = CH*64*R*W elements, low to high:
+//   [e: log2 CH in-thread][lane: 6][r: log2 R in-thread chunks][wave: log2 W]
+// so that every global access is one contiguous CH-element piece per lane and
+// the stage order e -> lane -> r -> wave is ascending.  The wave stages swap
+// the wave bits with the low r bits through LDS once, then run in registers.
+#include "hbl_internal.h"
+
+namespace hbl {
+namespace {
+
+constexpr float kRoot7 = 2.6457513110645907f;  // (float)sqrt(7.0), bit pattern 0x402953FD
+constexpr float kMagic = 12582912.0f;          // 1.5 * 2^23: adding it rounds to an integer (nearest-even)
+
+__device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// Value held by lane (lane ^ MASK).
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v) {
+    const int iv = (int)as_u(v);
+    if constexpr (MASK == 1) {
+        return as_f((uint32_t)__builtin_amdgcn_mov_dpp(iv, 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+    } else if constexpr (MASK == 2) {
+        return as_f((uint32_t)__builtin_amdgcn_mov_dpp(iv, 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+    } else if constexpr (MASK == 8) {
+        return as_f((uint32_t)__builtin_amdgcn_mov_dpp(iv, 0x128, 0xF, 0xF, false));  // row_ror:8
+    } else if constexpr (MASK == 4) {
+        return as_f((uint32_t)__builtin_amdgcn_ds_swizzle(iv, 0x101F));  // xor 4 inside 32 lanes
+    } else if constexpr (MASK == 16) {
+        return as_f((uint32_t)__builtin_amdgcn_ds_swizzle(iv, 0x401F));  // xor 16 inside 32 lanes
+    } else {
+        return __shfl_xor(v, MASK, 64);
+    }
+}
+
+template <int MASK, int R, int CH>
+__device__ __forceinline__ void lane_stage(float (&v)[R][CH], int lane) {
+    // lanes with the bit clear compute a + b, lanes with it set compute a - b = partner - own
+    const uint32_t sign = (lane & MASK) ? 0x80000000u : 0u;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < CH; ++e) {
+            const float own = v[r][e];
+            const float partner = lane_xor<MASK>(own);
+            v[r][e] = partner + as_f(as_u(own) ^ sign);
+        }
+}
+
+template <int BYTES>
+struct Raw;
+template <>
+struct Raw<2> { using type = uint16_t; };
+template <>
+struct Raw<4> { using type = uint32_t; };
+template <>
+struct Raw<8> { using type = uint2; };
+template <>
+struct Raw<16> { using type = uint4; };
+template <>
+struct Raw<32> { struct type { uint4 a, b; }; };
+
+// Load CH consecutive elements starting at element offset `off` and widen to fp32.
+template <int CH, bool BF16>
+__device__ __forceinline__ void load_chunk(const void* x, int64_t off, float (&dst)[CH]) {
+    if constexpr (BF16) {
+        using V = typename Raw<CH * 2>::type;
+        V raw = *reinterpret_cast<const V*>(static_cast<const uint16_t*>(x) + off);
+        const uint16_t* h = reinterpret_cast<const uint16_t*>(&raw);
+#pragma unroll
+        for (int e = 0; e < CH; ++e) dst[e] = as_f((uint32_t)h[e] << 16);
+    } else {
+        using V = typename Raw<CH * 4>::type;
+        V raw = *reinterpret_cast<const V*>(static_cast<const float*>(x) + off);
+        const float* f = reinterpret_cast<const float*>(&raw);
+#pragma unroll
+        for (int e = 0; e < CH; ++e) dst[e] = f[e];
+    }
+}
+
+template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
+__global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restrict__ x, int8_t* __restrict__ codes,
+                                                            float* __restrict__ s_dequant,
+                                                            int32_t* __restrict__ code_sum, float eps) {
+    constexpr int K = 1 << LOG2K;
+    constexpr int NT = 64 * W;
+    constexpr int E = K / NT;            // elements per thread
+    constexpr int CH = E < 8 ? E : 8;    // contiguous elements per chunk
+    constexpr int R = E / CH;            // chunks per thread
+    static_assert(E >= 1 && R >= 1 && (W == 1 || R >= W), "unsupported split");
+
+    __shared__ double red_d[W];
+    __shared__ float red_f[W];
+    __shared__ int red_i[W];
+    extern __shared__ float exch[];      // K floats when HADAMARD && W > 1
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const int64_t row_off = row * (int64_t)K;
+
+    float v[R][CH];
+#pragma unroll
+    for (int r = 0; r < R; ++r) load_chunk<CH, BF16>(x, row_off + (int64_t)((wave * R + r) * 64 + lane) * CH, v[r]);
+
+    bool exchanged = false;  // register slot r holds chunk g = wave*R + r until the LDS exchange
+
+    if constexpr (HADAMARD) {
+        // e bits
+#pragma unroll
+        for (int h = 1; h < CH; h <<= 1)
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int e = 0; e < CH; ++e)
+                    if ((e & h) == 0) {
+                        const float a = v[r][e], b = v[r][e + h];
+                        v[r][e] = a + b;
+                        v[r][e + h] = a - b;
+                    }
+        // lane bits
+        lane_stage<1>(v, lane);
+        lane_stage<2>(v, lane);
+        lane_stage<4>(v, lane);
+        lane_stage<8>(v, lane);
+        lane_stage<16>(v, lane);
+        lane_stage<32>(v, lane);
+        // r bits
+#pragma unroll
+        for (int h = 1; h < R; h <<= 1)
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if ((r & h) == 0) {
+#pragma unroll
+                    for (int e = 0; e < CH; ++e) {
+                        const float a = v[r][e], b = v[r + h][e];
+                        v[r][e] = a + b;
+                        v[r + h][e] = a - b;
+                    }
+                }
+        // wave bits: trade them for the low log2(W) bits of r through LDS
+        if constexpr (W > 1) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                float* dst = exch + ((wave * R + r) * 64 + lane) * CH;
+#pragma unroll
+                for (int e = 0; e < CH; e += 4)
+                    *reinterpret_cast<float4*>(dst + e) = make_float4(v[r][e], v[r][e + 1], v[r][e + 2], v[r][e + 3]);
+            }
+            __syncthreads();
+            // slot j = r_hi*W + w2 now holds chunk g = w2*R + r_hi*W + wave
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const int w2 = j % W, r_hi = j / W;
+                const float* src = exch + ((w2 * R + r_hi * W + wave) * 64 + lane) * CH;
+#pragma unroll
+                for (int e = 0; e < CH; e += 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(src + e);
+                    v[j][e] = t.x; v[j][e + 1] = t.y; v[j][e + 2] = t.z; v[j][e + 3] = t.w;
+                }
+            }
+            exchanged = true;
+#pragma unroll
+            for (int h = 1; h < W; h <<= 1)
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+                    if ((j & h) == 0) {
+#pragma unroll
+                        for (int e = 0; e < CH; ++e) {
+                            const float a = v[j][e], b = v[j + h][e];
+                            v[j][e] = a + b;
+                            v[j + h][e] = a - b;
+                        }
+                    }
+        }
+        const float c_n = (float)(1.0 / sqrt((double)K));
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < CH; ++e) v[r][e] = v[r][e] * c_n;
+    }
+
+    // per-token scale
+    float gain, s_d;
+    if constexpr (BITS == 8) {
+        float m = 0.0f;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < CH; ++e) m = fmaxf(m, fabsf(v[r][e]));
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+        if constexpr (W > 1) {
+            if (lane == 0) red_f[wave] = m;
+            __syncthreads();
+            m = red_f[0];
+#pragma unroll
+            for (int w = 1; w < W; ++w) m = fmaxf(m, red_f[w]);
+        }
+        gain = 127.0f / (m + eps);
+        s_d = m / 127.0f;
+    } else {
+        double s = 0.0;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < CH; ++e) s += (double)fabsf(v[r][e]);
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+        if constexpr (W > 1) {
+            if (lane == 0) red_d[wave] = s;
+            __syncthreads();
+            s = red_d[0];
+#pragma unroll
+            for (int w = 1; w < W; ++w) s += red_d[w];
+        }
+        const float beta = (float)(s / (double)K);
+        gain = kRoot7 / (beta + eps);
+        s_d = beta / kRoot7;
+    }
+
+    // codes: clamp, then add 1.5*2^23 so that the fp32 adder rounds to the nearest (even) integer and
+    // leaves its two's complement in the low mantissa bits
+    constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
+    constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
+    int isum = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        uint32_t packed[(CH + 3) / 4];
+#pragma unroll
+        for (int p = 0; p < (CH + 3) / 4; ++p) packed[p] = 0;
+#pragma unroll
+        for (int e = 0; e < CH; ++e) {
+            const float y = v[r][e] * gain;
+            const float t = __builtin_amdgcn_fmed3f(y, lo, hi);
+            const uint32_t bits = as_u(t + kMagic);
+            isum += (int)bits;
+            packed[e / 4] |= (bits & 0xFFu) << (8 * (e % 4));
+        }
+        int g;
+        if (exchanged) {
+            const int w2 = r % W, r_hi = r / W;
+            g = w2 * R + r_hi * W + wave;
+        } else {
+            g = wave * R + r;
+        }
+        int8_t* dst = codes + row_off + (int64_t)(g * 64 + lane) * CH;
+        if constexpr (CH == 8) {
+            *reinterpret_cast<uint2*>(dst) = make_uint2(packed[0], packed[1]);
+        } else if constexpr (CH == 4) {
+            *reinterpret_cast<uint32_t*>(dst) = packed[0];
+        } else if constexpr (CH == 2) {
+            *reinterpret_cast<uint16_t*>(dst) = (uint16_t)packed[0];
+        } else {
+            *reinterpret_cast<uint8_t*>(dst) = (uint8_t)packed[0];
+        }
+    }
+    isum = (int)((uint32_t)isum - (uint32_t)E * 0x4B400000u);  // remove the magic constant's bit pattern (mod 2^32)
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
+    if constexpr (W > 1) {
+        if (lane == 0) red_i[wave] = isum;
+        __syncthreads();
+        isum = 0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) isum += red_i[w];
+    }
+    if (tid == 0) {
+        s_dequant[row] = s_d;
+        if (code_sum) code_sum[row] = isum;
+    }
+}
+
+template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
+int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, float eps,
+               hipStream_t stream) {
+    constexpr int K = 1 << LOG2K;
+    const size_t lds = (HADAMARD && W > 1) ? sizeof(float) * K : 0;
+    auto kern = fwht_quant_kernel<LOG2K, W, BITS, BF16, HADAMARD>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return note_hip_error(e);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, eps);
+    return after_launch();
+}
+
+
+// Plain BitLinear front end for K that is not a power of two (K % 128 == 0, K <= 16384): the same
+// quantiser with the row held as up to 8 chunks of 8 elements per thread of a 256-thread workgroup.
+template <int BITS, bool BF16>
+__global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restrict__ x, int K,
+                                                            int8_t* __restrict__ codes,
+                                                            float* __restrict__ s_dequant,
+                                                            int32_t* __restrict__ code_sum, float eps) {
+    constexpr int MAXC = 8;
+    __shared__ double red_d[4];
+    __shared__ float red_f[4];
+    __shared__ int red_i[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t row_off = (int64_t)blockIdx.x * K;
+    const int nchunks = K / 8;
+    float v[MAXC][8];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ch = c * 256 + tid;
+        if (ch < nchunks) {
+            load_chunk<8, BF16>(x, row_off + (int64_t)ch * 8, v[c]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[c][e] = 0.0f;
+        }
+    }
+    float gain, s_d;
+    if constexpr (BITS == 8) {
+        float m = 0.0f;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(v[c][e]));
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+        if (lane == 0) red_f[wave] = m;
+        __syncthreads();
+        m = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
+        gain = 127.0f / (m + eps);
+        s_d = m / 127.0f;
+    } else {
+        double s = 0.0;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += (double)fabsf(v[c][e]);
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+        if (lane == 0) red_d[wave] = s;
+        __syncthreads();
+        s = ((red_d[0] + red_d[1]) + red_d[2]) + red_d[3];
+        const float beta = (float)(s / (double)K);
+        gain = kRoot7 / (beta + eps);
+        s_d = beta / kRoot7;
+    }
+    constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
+    constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
+    int isum = 0;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
+        const int ch = c * 256 + tid;
+        if (ch < nchunks) {
+            uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float t = __builtin_amdgcn_fmed3f(v[c][e] * gain, lo, hi);
+                const uint32_t bits = as_u(t + kMagic);
+                isum += (int)bits - (int)0x4B400000;
+                packed[e / 4] |= (bits & 0xFFu) << (8 * (e % 4));
+            }
+            *reinterpret_cast<uint2*>(codes + row_off + (int64_t)ch * 8) = make_uint2(packed[0], packed[1]);
+        }
+    }
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
+    if (lane == 0) red_i[wave] = isum;
+    __syncthreads();
+    if (tid == 0) {
+        s_dequant[blockIdx.x] = s_d;
+        if (code_sum) code_sum[blockIdx.x] = red_i[0] + red_i[1] + red_i[2] + red_i[3];
+    }
+}
+
+int launch_generic(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int8_t* codes,
+                   float* s_dequant, int32_t* code_sum, hipStream_t stream) {
+    const dim3 grid((unsigned)T), block(256);
+    const bool bf = x_dtype == HBL_BF16;
+    if (bits == 8) {
+        if (bf) hipLaunchKernelGGL((quant_generic_kernel<8, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps);
+        else    hipLaunchKernelGGL((quant_generic_kernel<8, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps);
+    } else {
+        if (bf) hipLaunchKernelGGL((quant_generic_kernel<4, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps);
+        else    hipLaunchKernelGGL((quant_generic_kernel<4, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps);
+    }
+    return after_launch();
+}
+
+template <int LOG2K, int W>
+int dispatch(const void* x, int x_dtype, int64_t T, int bits, float eps, bool hadamard, int8_t* codes,
+             float* s_dequant, int32_t* code_sum, hipStream_t stream) {
+    const bool bf = x_dtype == HBL_BF16;
+    if (hadamard) {
+        if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, true>(x, T, codes, s_dequant, code_sum, eps, stream)
+                                 : launch_one<LOG2K, W, 8, false, true>(x, T, codes, s_dequant, code_sum, eps, stream);
+        return bf ? launch_one<LOG2K, W, 4, true, true>(x, T, codes, s_dequant, code_sum, eps, stream)
+                  : launch_one<LOG2K, W, 4, false, true>(x, T, codes, s_dequant, code_sum, eps, stream);
+    }
+    if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, false>(x, T, codes, s_dequant, code_sum, eps, stream)
+                             : launch_one<LOG2K, W, 8, false, false>(x, T, codes, s_dequant, code_sum, eps, stream);
+    return bf ? launch_one<LOG2K, W, 4, true, false>(x, T, codes, s_dequant, code_sum, eps, stream)
+              : launch_one<LOG2K, W, 4, false, false>(x, T, codes, s_dequant, code_sum, eps, stream);
+}
+
+}  // namespace
+
+int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
+                      int8_t* codes, float* s_dequant, int32_t* code_sum, hipStream_t stream) {
+    if (T == 0) return HBL_OK;
+    if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, eps, codes, s_dequant, code_sum, stream);
+    switch (K) {
+        case 128:   return dispatch<7, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        case 256:   return dispatch<8, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        case 512:   return dispatch<9, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        case 1024:  return dispatch<10, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        case 2048:  return dispatch<11, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        case 4096:  return dispatch<12, 2>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        case 8192:  return dispatch<13, 4>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        case 16384: return dispatch<14, 4>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        default:    return HBL_E_SHAPE;
+    }
+}
+
+}  // namespace hbl

@@ -1,0 +1,60 @@
+// Internal declarations shared by the HIP translation units of libhbitlinear.
+// Nothing here is part of the public ABI (see include/hbitlinear.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "hbitlinear.h"
+
+namespace hbl {
+
+// Records a failed HIP call for hbl_last_hip_error() and yields HBL_E_HIP.
+int note_hip_error(hipError_t e);
+
+inline int after_launch() {
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? HBL_OK : note_hip_error(e);
+}
+
+inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Layout of the forward workspace: int8 codes [T,K] | float s_dequant [T] | int32 code_sum [T].
+struct Workspace {
+    int8_t* codes;
+    float* s_dequant;
+    int32_t* code_sum;
+    size_t bytes;
+};
+inline Workspace carve_workspace(void* base, int64_t T, int64_t K) {
+    Workspace w;
+    size_t off = 0;
+    w.codes = reinterpret_cast<int8_t*>(static_cast<char*>(base) + off);
+    off += round_up(static_cast<size_t>(T) * static_cast<size_t>(K), 256);
+    w.s_dequant = reinterpret_cast<float*>(static_cast<char*>(base) + off);
+    off += round_up(static_cast<size_t>(T) * sizeof(float), 256);
+    w.code_sum = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
+    off += round_up(static_cast<size_t>(T) * sizeof(int32_t), 256);
+    w.bytes = off;
+    return w;
+}
+
+// Launchers (defined in the .hip files). All validate nothing: callers in api.hip do.
+int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
+                      int8_t* codes, float* s_dequant, int32_t* code_sum, hipStream_t stream);
+
+// GEMM + epilogue. If acc_out != nullptr the raw int32 accumulators are written
+// (no scales, no code_sum needed); otherwise y (bf16) is written.
+int launch_ternary_gemm(const int8_t* codes, int64_t T, int64_t K, const void* packed, int64_t N,
+                        const float* s_dequant, const int32_t* code_sum, const float* w_scales,
+                        int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, hipStream_t stream);
+
+int launch_ternarize(const float* W, int64_t count, float eps, int8_t* codes, float* alpha, void* workspace,
+                     hipStream_t stream);
+size_t ternarize_workspace_bytes(int64_t count);
+int launch_pack(const int8_t* codes, int64_t N, int64_t K, void* packed, hipStream_t stream);
+int launch_unpack(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream);
+
+}  // namespace hbl

@@ -1,0 +1,154 @@
+// Weight set-up kernels: the per-tensor absmean ternary quantiser (Eq. 1-2) and the
+// 2-bit packing of its codes into the streaming layout the GEMM kernels read.
+//
+// Packed layout.  The [N, K] code matrix is cut into tiles of 32 output rows x 128
+// input features, stored tile after tile with the K direction fastest:
+//   tile(nt, kb) at byte ((nt * (K/128) + kb) * 1024), nt = o / 32, kb = k / 128.
+// A tile is 64 lanes x 4 dwords (lane-major, 16 bytes per lane).  Lane l, dword s
+// holds the 16 weights of row 32*nt + (l & 31) at features
+//   k = 128*kb + 32*s + 16*(l >> 5) + i,  i = 0..15,
+// i.e. exactly one lane's share of a 32x32x32 int8 matrix-core operand for K-step s.
+// Weight i = 4*j + b of that group sits at bits [8*b + 2*j, 8*b + 2*j + 1] as code+1,
+// so that (dword >> 2*j) & 0x03030303 is operand register j (bytes b = 0..3).
+#include "hbl_internal.h"
+
+namespace hbl {
+namespace {
+
+constexpr int kSumBlock = 256;
+constexpr int kSumItems = 16;  // floats per thread per block
+
+// Eq. 1: partial sums of |W| in fp64, one per workgroup, fixed order inside the workgroup.
+__global__ __launch_bounds__(kSumBlock) void abs_sum_partial_kernel(const float* __restrict__ W, int64_t count,
+                                                                    double* __restrict__ partial) {
+    __shared__ double red[kSumBlock / 64];
+    const int64_t base = (int64_t)blockIdx.x * (kSumBlock * kSumItems);
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < kSumItems; ++i) {
+        const int64_t idx = base + (int64_t)i * kSumBlock + threadIdx.x;
+        if (idx < count) s += (double)fabsf(W[idx]);
+    }
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = red[0];
+        for (int w = 1; w < kSumBlock / 64; ++w) t += red[w];
+        partial[blockIdx.x] = t;
+    }
+}
+
+// Final reduction by one workgroup (fixed order), alpha = (float)(sum / count).
+__global__ __launch_bounds__(256) void abs_mean_final_kernel(const double* __restrict__ partial, int64_t nparts,
+                                                             int64_t count, float* __restrict__ alpha) {
+    __shared__ double red[4];
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < nparts; i += 256) s += partial[i];
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const double t = ((red[0] + red[1]) + red[2]) + red[3];
+        *alpha = (float)(t / (double)count);
+    }
+}
+
+// Eq. 1-2: codes = RoundClip(W / (alpha + eps), -1, 1).
+__global__ __launch_bounds__(256) void ternarize_kernel(const float* __restrict__ W, int64_t count,
+                                                        const float* __restrict__ alpha, float eps,
+                                                        int8_t* __restrict__ codes) {
+    const float denom = *alpha + eps;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += stride) {
+        float r = rintf(W[i] / denom);
+        r = fminf(fmaxf(r, -1.0f), 1.0f);
+        codes[i] = (int8_t)(int)r;
+    }
+}
+
+__global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ codes, int64_t N, int64_t K,
+                                                   uint32_t* __restrict__ packed) {
+    const int64_t kblocks = K / 128;
+    const int64_t total = (N / 32) * kblocks * 256;  // dwords
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d >= total) return;
+    const int s = (int)(d & 3);
+    const int lane = (int)((d >> 2) & 63);
+    const int64_t tile = d >> 8;
+    const int64_t kb = tile % kblocks, nt = tile / kblocks;
+    const int64_t row = nt * 32 + (lane & 31);
+    const int64_t k0 = kb * 128 + s * 32 + (lane >> 5) * 16;
+    const uint4 raw = *reinterpret_cast<const uint4*>(codes + row * K + k0);
+    const int8_t* c = reinterpret_cast<const int8_t*>(&raw);
+    uint32_t out = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int j = i >> 2, b = i & 3;
+        out |= (uint32_t)((int)c[i] + 1) << (8 * b + 2 * j);
+    }
+    packed[d] = out;
+}
+
+__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict__ packed, int64_t N, int64_t K,
+                                                     int8_t* __restrict__ codes) {
+    const int64_t kblocks = K / 128;
+    const int64_t total = (N / 32) * kblocks * 256;
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d >= total) return;
+    const int s = (int)(d & 3);
+    const int lane = (int)((d >> 2) & 63);
+    const int64_t tile = d >> 8;
+    const int64_t kb = tile % kblocks, nt = tile / kblocks;
+    const int64_t row = nt * 32 + (lane & 31);
+    const int64_t k0 = kb * 128 + s * 32 + (lane >> 5) * 16;
+    const uint32_t p = packed[d];
+    uint4 raw;
+    int8_t* c = reinterpret_cast<int8_t*>(&raw);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int j = i >> 2, b = i & 3;
+        c[i] = (int8_t)((int)((p >> (8 * b + 2 * j)) & 3u) - 1);
+    }
+    *reinterpret_cast<uint4*>(codes + row * K + k0) = raw;
+}
+
+int64_t sum_blocks(int64_t count) { return (count + kSumBlock * kSumItems - 1) / (kSumBlock * kSumItems); }
+
+}  // namespace
+
+size_t ternarize_workspace_bytes(int64_t count) { return round_up((size_t)sum_blocks(count) * sizeof(double), 256); }
+
+int launch_ternarize(const float* W, int64_t count, float eps, int8_t* codes, float* alpha, void* workspace,
+                     hipStream_t stream) {
+    double* partial = static_cast<double*>(workspace);
+    const int64_t nb = sum_blocks(count);
+    hipLaunchKernelGGL(abs_sum_partial_kernel, dim3((unsigned)nb), dim3(kSumBlock), 0, stream, W, count, partial);
+    int rc = after_launch();
+    if (rc != HBL_OK) return rc;
+    hipLaunchKernelGGL(abs_mean_final_kernel, dim3(1), dim3(256), 0, stream, partial, nb, count, alpha);
+    rc = after_launch();
+    if (rc != HBL_OK) return rc;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(ternarize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, W, count, alpha, eps, codes);
+    return after_launch();
+}
+
+int launch_pack(const int8_t* codes, int64_t N, int64_t K, void* packed, hipStream_t stream) {
+    const int64_t total = (N / 32) * (K / 128) * 256;
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
+                       static_cast<uint32_t*>(packed));
+    return after_launch();
+}
+
+int launch_unpack(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream) {
+    const int64_t total = (N / 32) * (K / 128) * 256;
+    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const uint32_t*>(packed), N, K, codes);
+    return after_launch();
+}
+
+}  // namespace hbl

@@ -1,0 +1,189 @@
+"""Thin ctypes binding over libhbitlinear.so (include/hbitlinear.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch provides device memory (``tensor.data_ptr()``) and the
+current stream; nothing here computes.  If the shared library is missing the
+import of any function fails loudly - there is no CPU fallback.
+
+bf16 activations / outputs are ``torch.bfloat16`` tensors; fp32 activations
+``torch.float32``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libhbitlinear.so")
+
+OK = 0
+E_NULL, E_SHAPE, E_BITS, E_DTYPE, E_WORKSPACE, E_HIP, E_ALIGN = -1, -2, -3, -4, -5, -6, -7
+F32, BF16 = 0, 1
+EPS = 1e-5
+
+EXPORTS = [
+    "hbl_strerror", "hbl_last_hip_error", "hbl_ternarize_workspace_bytes", "hbl_ternarize_weights_absmean",
+    "hbl_packed_bytes", "hbl_pack_ternary_2bit", "hbl_unpack_ternary_2bit", "hbl_workspace_bytes",
+    "hbl_hbitlinear_forward", "hbl_plain_bitlinear_forward", "hbl_fwht_quant", "hbl_gemm_i32",
+]
+
+_lib = None
+
+
+class HblError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        msg = lib().hbl_strerror(status).decode()
+        if status == E_HIP:
+            msg += f" (hipError {lib().hbl_last_hip_error()})"
+        super().__init__(f"{what}: {msg} [status {status}]")
+
+
+def lib():
+    """Load the C-ABI library (built by ``__graft_entry__.build()`` / ``paper_2504_18415_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2504_18415_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, ci, f32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+        L.hbl_strerror.restype = ctypes.c_char_p
+        L.hbl_strerror.argtypes = [ci]
+        L.hbl_last_hip_error.restype = ci
+        L.hbl_ternarize_workspace_bytes.restype = sz
+        L.hbl_ternarize_workspace_bytes.argtypes = [i64, i64]
+        L.hbl_ternarize_weights_absmean.argtypes = [vp, i64, i64, f32, vp, vp, vp, sz, vp]
+        L.hbl_packed_bytes.restype = sz
+        L.hbl_packed_bytes.argtypes = [i64, i64]
+        L.hbl_pack_ternary_2bit.argtypes = [vp, i64, i64, vp, vp]
+        L.hbl_unpack_ternary_2bit.argtypes = [vp, i64, i64, vp, vp]
+        L.hbl_workspace_bytes.restype = sz
+        L.hbl_workspace_bytes.argtypes = [i64, i64, i64, ci]
+        fwd = [vp, ci, i64, i64, vp, i64, vp, i64, ci, f32, vp, vp, sz, vp]
+        L.hbl_hbitlinear_forward.argtypes = fwd
+        L.hbl_plain_bitlinear_forward.argtypes = fwd
+        L.hbl_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, vp, vp, vp, vp]
+        L.hbl_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _check(status: int, what: str):
+    if status != OK:
+        raise HblError(status, what)
+
+
+def _x_dtype(x: torch.Tensor) -> int:
+    if x.dtype == torch.bfloat16:
+        return BF16
+    if x.dtype == torch.float32:
+        return F32
+    raise TypeError("activations must be torch.bfloat16 or torch.float32")
+
+
+def _dev_check(*ts):
+    for t in ts:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def ternarize_weights_absmean(W: torch.Tensor, eps: float = EPS) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Eq. 1.  W [N,K] fp32 (device) -> (codes int8 [N,K], alpha fp32 [1]) on the device."""
+    _dev_check(W)
+    N, K = W.shape
+    codes = torch.empty((N, K), dtype=torch.int8, device=W.device)
+    alpha = torch.empty(1, dtype=torch.float32, device=W.device)
+    ws = torch.empty(max(int(lib().hbl_ternarize_workspace_bytes(N, K)), 8), dtype=torch.uint8, device=W.device)
+    _check(lib().hbl_ternarize_weights_absmean(_ptr(W), N, K, eps, _ptr(codes), _ptr(alpha), _ptr(ws), ws.numel(),
+                                               _stream()), "ternarize_weights_absmean")
+    return codes, alpha
+
+
+def packed_bytes(N: int, K: int) -> int:
+    return int(lib().hbl_packed_bytes(N, K))
+
+
+def pack_ternary_2bit(codes: torch.Tensor) -> torch.Tensor:
+    """codes int8 [N,K] in {-1,0,1} -> opaque packed uint8 [N*K/4]."""
+    _dev_check(codes)
+    N, K = codes.shape
+    packed = torch.empty(packed_bytes(N, K), dtype=torch.uint8, device=codes.device)
+    _check(lib().hbl_pack_ternary_2bit(_ptr(codes), N, K, _ptr(packed), _stream()), "pack_ternary_2bit")
+    return packed
+
+
+def unpack_ternary_2bit(packed: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    _dev_check(packed)
+    codes = torch.empty((N, K), dtype=torch.int8, device=packed.device)
+    _check(lib().hbl_unpack_ternary_2bit(_ptr(packed), N, K, _ptr(codes), _stream()), "unpack_ternary_2bit")
+    return codes
+
+
+def workspace_bytes(T: int, K: int, N: int, bits: int) -> int:
+    return int(lib().hbl_workspace_bytes(T, K, N, bits))
+
+
+def alloc_workspace(T: int, K: int, N: int, bits: int, device="cuda") -> torch.Tensor:
+    return torch.empty(workspace_bytes(T, K, N, bits), dtype=torch.uint8, device=device)
+
+
+def _forward(fn, name, x, Wq_packed, N, w_scales, bits, eps, y, workspace):
+    _dev_check(x, Wq_packed, w_scales, y, workspace)
+    T, K = x.shape
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = alloc_workspace(T, K, N, bits, x.device)
+    _check(fn(_ptr(x), _x_dtype(x), T, K, _ptr(Wq_packed), N, _ptr(w_scales), w_scales.numel(), bits, eps,
+              _ptr(y), _ptr(workspace), workspace.numel(), _stream()), name)
+    return y
+
+
+def hbitlinear_forward(x: torch.Tensor, Wq_packed: torch.Tensor, N: int, w_scales: torch.Tensor, bits: int = 4,
+                       eps: float = EPS, y: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 7 with the Hadamard transform: x [T,K] -> y bf16 [T,N]."""
+    return _forward(lib().hbl_hbitlinear_forward, "hbitlinear_forward", x, Wq_packed, N, w_scales, bits, eps, y,
+                    workspace)
+
+
+def plain_bitlinear_forward(x: torch.Tensor, Wq_packed: torch.Tensor, N: int, w_scales: torch.Tensor, bits: int = 4,
+                            eps: float = EPS, y: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 7 without the transform (W_qkv, W_up/gate)."""
+    return _forward(lib().hbl_plain_bitlinear_forward, "plain_bitlinear_forward", x, Wq_packed, N, w_scales, bits,
+                    eps, y, workspace)
+
+
+def fwht_quant(x: torch.Tensor, bits: int, hadamard: bool = True, eps: float = EPS):
+    """Eq. 3-6 only -> (codes int8 [T,K], s_dequant fp32 [T], code_sum int32 [T])."""
+    _dev_check(x)
+    T, K = x.shape
+    codes = torch.empty((T, K), dtype=torch.int8, device=x.device)
+    sd = torch.empty(T, dtype=torch.float32, device=x.device)
+    cs = torch.empty(T, dtype=torch.int32, device=x.device)
+    _check(lib().hbl_fwht_quant(_ptr(x), _x_dtype(x), T, K, bits, eps, int(hadamard), _ptr(codes), _ptr(sd),
+                                _ptr(cs), _stream()), "fwht_quant")
+    return codes, sd, cs
+
+
+def gemm_i32(codes: torch.Tensor, Wq_packed: torch.Tensor, N: int) -> torch.Tensor:
+    """acc int32 [T,N] = codes [T,K] . c^T (exact)."""
+    _dev_check(codes, Wq_packed)
+    T, K = codes.shape
+    acc = torch.empty((T, N), dtype=torch.int32, device=codes.device)
+    _check(lib().hbl_gemm_i32(_ptr(codes), T, K, _ptr(Wq_packed), N, _ptr(acc), _stream()), "gemm_i32")
+    return acc

@@ -1,0 +1,97 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the public header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "hbitlinear.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2504_18415_amd import hbl
+    if not os.path.exists(hbl.LIB_PATH):
+        from paper_2504_18415_amd import build
+        build.build_library()
+    return hbl.lib()
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(hbl_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    from paper_2504_18415_amd import hbl
+    names = declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(hbl.EXPORTS) == names
+
+
+def test_status_text(L):
+    for st in range(0, -8, -1):
+        assert L.hbl_strerror(st) and L.hbl_strerror(st) != b"unknown status"
+    assert L.hbl_strerror(-99) == b"unknown status"
+
+
+def test_size_queries(L):
+    assert L.hbl_packed_bytes(4096, 16384) == 4096 * 16384 // 4
+    assert L.hbl_packed_bytes(256, 256) == 16384
+    ws = L.hbl_workspace_bytes(8192, 16384, 4096, 4)
+    assert ws >= 8192 * 16384 + 8 * 8192 and ws % 256 == 0
+    assert L.hbl_workspace_bytes(17, 256, 256, 8) >= 17 * 256 + 8 * 17
+    assert L.hbl_ternarize_workspace_bytes(4096, 16384) >= 8
+    assert L.hbl_ternarize_workspace_bytes(4096, 16384) <= 4096 * 16384 // 16
+
+
+def test_argument_errors_before_any_launch(L):
+    from paper_2504_18415_amd import hbl
+    P = ctypes.c_void_p(0x10000)       # never dereferenced: every call below fails validation first
+    NUL = ctypes.c_void_p(0)
+    ok_ws = 1 << 30
+
+    def fwd(fn=L.hbl_hbitlinear_forward, x=P, dt=hbl.BF16, T=4, K=256, w=P, N=64, sc=P, g=1, bits=4, y=P, ws=P,
+            wsb=ok_ws):
+        return fn(x, dt, T, K, w, N, sc, g, bits, 1e-5, y, ws, wsb, None)
+
+    assert fwd(bits=5) == hbl.E_BITS
+    assert fwd(dt=7) == hbl.E_DTYPE
+    assert fwd(K=192) == hbl.E_SHAPE                      # Hadamard needs a power of two
+    assert fwd(K=64) == hbl.E_SHAPE
+    assert fwd(K=32768) == hbl.E_SHAPE
+    assert fwd(K=200) == hbl.E_SHAPE
+    assert fwd(N=48) == hbl.E_SHAPE
+    assert fwd(T=-1) == hbl.E_SHAPE
+    assert fwd(g=3) == hbl.E_SHAPE                        # 64 rows do not split into 3 groups
+    assert fwd(N=96, g=3) != hbl.E_SHAPE
+    assert fwd(x=NUL) == hbl.E_NULL
+    assert fwd(w=NUL) == hbl.E_NULL
+    assert fwd(sc=NUL) == hbl.E_NULL
+    assert fwd(y=NUL) == hbl.E_NULL
+    assert fwd(ws=NUL) == hbl.E_NULL
+    assert fwd(x=ctypes.c_void_p(0x10004)) == hbl.E_ALIGN
+    assert fwd(ws=ctypes.c_void_p(0x10010)) == hbl.E_ALIGN
+    assert fwd(wsb=100) == hbl.E_WORKSPACE
+    assert fwd(T=0, x=NUL, y=NUL) == hbl.OK              # empty batch is a no-op
+    assert fwd(fn=L.hbl_plain_bitlinear_forward, K=384, wsb=100) == hbl.E_WORKSPACE   # K=384 is fine without Hadamard
+    assert L.hbl_fwht_quant(P, hbl.BF16, 4, 256, 3, 1e-5, 1, P, P, P, None) == hbl.E_BITS
+    assert L.hbl_fwht_quant(NUL, hbl.BF16, 4, 256, 4, 1e-5, 1, P, P, P, None) == hbl.E_NULL
+    assert L.hbl_gemm_i32(P, 4, 100, P, 64, P, None) == hbl.E_SHAPE
+    assert L.hbl_pack_ternary_2bit(P, 33, 256, P, None) == hbl.E_SHAPE
+    assert L.hbl_pack_ternary_2bit(NUL, 32, 256, P, None) == hbl.E_NULL
+    assert L.hbl_ternarize_weights_absmean(P, 0, 5, 1e-5, P, P, P, 8, None) == hbl.E_SHAPE
+    assert L.hbl_ternarize_weights_absmean(P, 4, 4, 1e-5, P, P, P, 0, None) == hbl.E_WORKSPACE
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    from paper_2504_18415_amd import hbl
+    monkeypatch.setattr(hbl, "_lib", None)
+    monkeypatch.setattr(hbl, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(ImportError):
+        hbl.lib()

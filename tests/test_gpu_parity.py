@@ -1,0 +1,341 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars (from the benchmark spec):
+  * activation codes bit-exact, else mismatch rate <= 1e-5 with off-by-one differences only;
+  * int32 accumulators bit-exact given identical codes;
+  * bf16 outputs: max rel err <= 1e-2 and mean rel err <= 1e-3, with
+    rel = |y - y_ref| / max(|y_ref|, 1e-3 * rms(y_ref row)).
+"""
+import math
+import os
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import hbl_oracle as O
+from paper_2504_18415_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+EPS = 1e-5
+
+
+_CASE_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+
+
+def note(msg):
+    """Name the case before each GPU step (survives a lost box: flushed line by line)."""
+    print(f"[gpu-case] {msg}", flush=True)
+    if os.path.isdir(_CASE_LOG):
+        with open(os.path.join(_CASE_LOG, "gpu_cases.log"), "a") as fh:
+            fh.write(msg + "\n")
+
+
+@pytest.fixture(scope="module")
+def hbl():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2504_18415_amd import hbl as H
+    H.lib()
+    return H
+
+
+def dev_x(x_np):
+    """numpy fp32 array or uint16 bf16 bit patterns -> device tensor of the matching torch dtype."""
+    if x_np.dtype == np.uint16:
+        return torch.from_numpy(x_np.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(x_np).cuda()
+
+
+def host_bf16_bits(y):
+    return y.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def rel_err(y_bits, ref_bits):
+    y = synth.bf16_bits_to_f32(y_bits).astype(np.float64)
+    r = synth.bf16_bits_to_f32(ref_bits).astype(np.float64)
+    rms = np.sqrt((r ** 2).mean(axis=1, keepdims=True))
+    den = np.maximum(np.abs(r), 1e-3 * rms + 1e-30)
+    e = np.abs(y - r) / den
+    return e.max(), e.mean()
+
+
+def check_codes(got, want):
+    diff = got.astype(np.int16) - want.astype(np.int16)
+    bad = diff != 0
+    rate = bad.mean()
+    assert rate <= 1e-5, f"code mismatch rate {rate}"
+    assert np.abs(diff).max(initial=0) <= 1
+    return rate
+
+
+_WEIGHT_CACHE = {}
+
+
+def setup_weights(hbl, site):
+    """Ternarise (oracle and GPU, per scale group) and pack the site's weights; cached per weight recipe."""
+    key = (site.K, site.N, site.seed, site.w_stream, site.groups, site.w_std)
+    if key not in _WEIGHT_CACHE:
+        if len(_WEIGHT_CACHE) > 6:
+            _WEIGHT_CACHE.clear()
+        _WEIGHT_CACHE[key] = _setup_weights(hbl, site)
+    return _WEIGHT_CACHE[key]
+
+
+def _setup_weights(hbl, site):
+    W = synth.make_w(site)
+    wc_ref = np.empty((site.N, site.K), np.int8)
+    alphas_ref = np.empty(site.groups, np.float32)
+    rows = site.N // site.groups
+    wc_dev, al_dev = [], []
+    for g in range(site.groups):
+        blk = np.ascontiguousarray(W[g * rows:(g + 1) * rows])
+        c, a = O.ternarize_weights_absmean(blk, EPS)
+        wc_ref[g * rows:(g + 1) * rows] = c
+        alphas_ref[g] = a
+        cd, ad = hbl.ternarize_weights_absmean(torch.from_numpy(blk).cuda(), EPS)
+        wc_dev.append(cd)
+        al_dev.append(ad)
+    wc_d = torch.cat(wc_dev, 0).contiguous()
+    al_d = torch.cat(al_dev).contiguous()
+    packed = hbl.pack_ternary_2bit(wc_d)
+    torch.cuda.synchronize()
+    return wc_ref, alphas_ref, wc_d, al_d, packed
+
+
+# ------------------------------------------------------------------ set-up kernels
+@pytest.mark.parametrize("N,K", [(32, 128), (96, 384), (256, 256), (320, 2048)])
+def test_ternarize_and_pack_roundtrip(hbl, N, K):
+    note(f"ternarize/pack N={N} K={K}")
+    site = synth.Site("w", 1, K, N, seed=20 + N)
+    W = synth.make_w(site)
+    c_ref, a_ref = O.ternarize_weights_absmean(W, EPS)
+    c_dev, a_dev = hbl.ternarize_weights_absmean(torch.from_numpy(W).cuda(), EPS)
+    assert a_dev.cpu().numpy()[0] == a_ref
+    assert np.array_equal(c_dev.cpu().numpy(), c_ref)
+    packed = hbl.pack_ternary_2bit(c_dev)
+    assert packed.numel() == N * K // 4
+    back = hbl.unpack_ternary_2bit(packed, N, K)
+    assert np.array_equal(back.cpu().numpy(), c_ref)
+
+
+def test_ternarize_odd_sizes_and_scale(hbl):
+    note("ternarize odd sizes")
+    rng = np.random.default_rng(5)
+    for shape, std in [((7, 13), 1.0), ((1, 1), 0.3), ((129, 1000), 1e-3), ((3, 70000), 5.0)]:
+        W = (rng.standard_normal(shape) * std).astype(np.float32)
+        c_ref, a_ref = O.ternarize_weights_absmean(W, EPS)
+        c_dev, a_dev = hbl.ternarize_weights_absmean(torch.from_numpy(W).cuda(), EPS)
+        assert a_dev.cpu().numpy()[0] == a_ref, shape
+        assert np.array_equal(c_dev.cpu().numpy(), c_ref), shape
+
+
+# ------------------------------------------------------------------ activation front end
+ALL_K = [128, 256, 512, 1024, 2048, 4096, 8192, 16384]
+
+
+@pytest.mark.parametrize("K", ALL_K)
+def test_fwht_exact_integers_on_gpu(hbl, K):
+    """Small-integer rows make every butterfly exact, so INT8 codes of H x are fixed by integer
+    arithmetic alone (no dependence on stage order): a pure check of the butterfly network."""
+    note(f"fwht exact integers K={K}")
+    rng = np.random.default_rng(K)
+    x = rng.integers(-3, 4, size=(5, K)).astype(np.float32)
+    codes, sd, cs = hbl.fwht_quant(torch.from_numpy(x).cuda(), 8, True, EPS)
+    c_ref, s_ref, xr = O.fwht_quant(x, 8, hadamard=True, eps=EPS, want_xr=True)
+    assert np.array_equal(codes.cpu().numpy(), c_ref)
+    assert np.array_equal(sd.cpu().numpy(), s_ref)
+    assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
+    # unit vectors: row j of H, all entries +-1/sqrt(K) -> every code is +-127
+    e = np.zeros((2, K), np.float32)
+    e[0, 1] = 1.0
+    e[1, K - 1] = -2.0
+    codes, _, _ = hbl.fwht_quant(torch.from_numpy(e).cuda(), 8, True, EPS)
+    j = np.arange(K)
+    sign0 = np.array([(-1) ** bin(int(v) & 1).count("1") for v in j])
+    sign1 = -np.array([(-1) ** bin(int(v) & (K - 1)).count("1") for v in j])
+    assert np.array_equal(np.sign(codes.cpu().numpy()[0]), sign0)
+    assert np.array_equal(np.sign(codes.cpu().numpy()[1]), sign1)
+
+
+@pytest.mark.parametrize("K", ALL_K)
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("hadamard", [True, False])
+def test_fwht_quant_parity(hbl, K, bits, hadamard):
+    T = 37 if K <= 4096 else 19                       # ragged, several rows per wave-group
+    for dtype in (synth.BF16, synth.F32):
+        note(f"fwht_quant K={K} bits={bits} hadamard={hadamard} dtype={dtype} T={T}")
+        site = synth.Site("a", T, K, 32, x_dtype=dtype, outlier_frac=0.01, outlier_scale=30.0, seed=K + bits)
+        x = synth.make_x(site)
+        c_ref, s_ref = O.fwht_quant(x, bits, hadamard=hadamard, eps=EPS)
+        codes, sd, cs = hbl.fwht_quant(dev_x(x), bits, hadamard, EPS)
+        assert np.array_equal(sd.cpu().numpy(), s_ref)
+        rate = check_codes(codes.cpu().numpy(), c_ref)
+        assert rate == 0.0
+        assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
+
+
+@pytest.mark.parametrize("K", [384, 1536, 11008 // 128 * 128])
+def test_plain_quant_non_power_of_two(hbl, K):
+    note(f"plain quant K={K}")
+    site = synth.Site("a", 9, K, 32, outlier_frac=0.01, outlier_scale=30.0, seed=K)
+    x = synth.make_x(site)
+    for bits in (4, 8):
+        c_ref, s_ref = O.fwht_quant(x, bits, hadamard=False, eps=EPS)
+        codes, sd, cs = hbl.fwht_quant(dev_x(x), bits, False, EPS)
+        assert np.array_equal(codes.cpu().numpy(), c_ref)
+        assert np.array_equal(sd.cpu().numpy(), s_ref)
+        assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
+
+
+def test_zero_rows_and_single_token(hbl):
+    note("zero rows")
+    x = np.zeros((3, 512), np.float32)
+    x[1, 7] = 4.0
+    for bits in (4, 8):
+        codes, sd, cs = hbl.fwht_quant(torch.from_numpy(x).cuda(), bits, True, EPS)
+        c_ref, s_ref = O.fwht_quant(x, bits, hadamard=True, eps=EPS)
+        assert np.array_equal(codes.cpu().numpy(), c_ref) and np.array_equal(sd.cpu().numpy(), s_ref)
+        assert not codes.cpu().numpy()[0].any() and sd.cpu().numpy()[0] == 0
+
+
+# ------------------------------------------------------------------ integer GEMM
+@pytest.mark.parametrize("T,K,N", [
+    (1, 128, 32), (5, 256, 96), (31, 384, 288), (33, 512, 544), (64, 2048, 256), (65, 1024, 320),
+    (130, 640, 416), (257, 2048, 512), (300, 4096, 288), (1000, 256, 1056),
+])
+def test_gemm_i32_bit_exact(hbl, T, K, N):
+    note(f"gemm_i32 T={T} K={K} N={N}")
+    rng = np.random.default_rng(T * 7 + N)
+    q = rng.integers(-128, 128, (T, K)).astype(np.int8)
+    c = rng.integers(-1, 2, (N, K)).astype(np.int8)
+    packed = hbl.pack_ternary_2bit(torch.from_numpy(c).cuda())
+    acc = hbl.gemm_i32(torch.from_numpy(q).cuda(), packed, N)
+    assert np.array_equal(acc.cpu().numpy(), O.gemm_i32(q, c))
+
+
+def test_gemm_i32_one_hot_layout(hbl):
+    """One-hot operands: acc[t][o] = q[t][k0]*c[o][k0]; catches any row/column/K permutation mistake."""
+    note("gemm_i32 one-hot")
+    T, K, N = 70, 512, 96
+    for k0 in (0, 17, 130, 511):
+        q = np.zeros((T, K), np.int8)
+        c = np.zeros((N, K), np.int8)
+        q[:, k0] = (np.arange(T) % 250 - 125).astype(np.int8)
+        c[:, k0] = (np.arange(N) % 3 - 1).astype(np.int8)
+        packed = hbl.pack_ternary_2bit(torch.from_numpy(c).cuda())
+        acc = hbl.gemm_i32(torch.from_numpy(q).cuda(), packed, N).cpu().numpy()
+        assert np.array_equal(acc, np.outer(q[:, k0].astype(np.int32), c[:, k0].astype(np.int32)))
+
+
+# ------------------------------------------------------------------ end to end
+def run_site(hbl, site, bits, sample_rows=None):
+    """Runs one projection on the GPU and the oracle; returns the comparison figures."""
+    x = synth.make_x(site)
+    wc_ref, al_ref, wc_d, al_d, packed = setup_weights(hbl, site)
+    assert np.array_equal(al_d.cpu().numpy(), al_ref)
+    assert np.array_equal(wc_d.cpu().numpy(), wc_ref)
+    xd = dev_x(x)
+    fn = hbl.hbitlinear_forward if site.hadamard else hbl.plain_bitlinear_forward
+    y = fn(xd, packed, site.N, al_d, bits, EPS)
+    codes, sd, cs = hbl.fwht_quant(xd, bits, site.hadamard, EPS)
+    acc = hbl.gemm_i32(codes, packed, site.N)
+    torch.cuda.synchronize()
+    rows = np.arange(site.T) if sample_rows is None else sample_rows
+    xs = np.ascontiguousarray(x[rows])
+    y_ref, c_ref, s_ref, a_ref = O.bitlinear_forward(xs, wc_ref, al_ref, bits, site.hadamard, EPS,
+                                                     want_intermediates=True)
+    rows_t = torch.from_numpy(rows).cuda()
+    c_got = codes[rows_t].cpu().numpy()
+    rate = check_codes(c_got, c_ref)
+    assert np.array_equal(sd[rows_t].cpu().numpy(), s_ref)
+    same = (c_got == c_ref).all(axis=1)
+    a_got = acc[rows_t].cpu().numpy()
+    assert np.array_equal(a_got[same], a_ref[same]), "int32 accumulators differ on rows with identical codes"
+    y_bits = host_bf16_bits(y[rows_t])
+    mx, mean = rel_err(y_bits, y_ref)
+    assert mx <= 1e-2 and mean <= 1e-3, (mx, mean)
+    exact = float((y_bits == y_ref).mean())
+    note(f"   {site.name} bits={bits}: code mismatch {rate:.2e}, y bit-exact {exact:.6f}, max rel {mx:.2e}")
+    return rate, exact
+
+
+def test_config1_tiny(hbl):
+    note("config 1")
+    rate, exact = run_site(hbl, synth.config_sites(1)[0], 4)
+    assert rate == 0 and exact == 1.0
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_config2_wo_1p3b(hbl, bits):
+    note(f"config 2 bits={bits}")
+    run_site(hbl, synth.config_sites(2)[0], bits)
+
+
+@pytest.mark.parametrize("T,K,N", [(96, 8192, 320), (200, 16384, 96), (77, 4096, 544)])
+def test_configs_3_4_reduced_shapes(hbl, T, K, N):
+    """Same recipes as configs 3 and 4 at sizes the oracle finishes in seconds (several tiles, ragged T)."""
+    note(f"reduced cfg3/4 T={T} K={K} N={N}")
+    run_site(hbl, synth.shrink(synth.config_sites(3)[0], T=T, K=K, N=N), 4)
+    run_site(hbl, synth.shrink(synth.config_sites(4)[1], T=T, K=K, N=N), 4)
+
+
+def test_config3_full_size_sampled(hbl):
+    note("config 3 full size, sampled rows")
+    site = synth.config_sites(3)[0]
+    rows = np.sort(np.random.default_rng(3).choice(site.T, 24, replace=False))
+    run_site(hbl, site, 4, sample_rows=rows)
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_config4_full_size_sampled(hbl, idx):
+    """7B prefill sites in the launch configuration the benchmark times; oracle on sampled token rows."""
+    site = synth.config_sites(4)[idx]
+    note(f"config 4 {site.name} full size, sampled rows")
+    rows = np.sort(np.random.default_rng(4 + idx).choice(site.T, 16, replace=False))
+    rows[0], rows[-1] = 0, site.T - 1
+    run_site(hbl, site, 4, sample_rows=rows)
+
+
+@pytest.mark.parametrize("batch", [1, 8, 32, 64])
+def test_config5_decode_layer(hbl, batch):
+    note(f"config 5 batch={batch}")
+    for site in synth.config_sites(5, batch=batch):
+        run_site(hbl, site, 4)
+
+
+def test_forward_reuses_caller_buffers_and_is_deterministic(hbl):
+    note("determinism / caller buffers")
+    site = synth.shrink(synth.config_sites(2)[0], T=300, K=1024, N=288)
+    x = dev_x(synth.make_x(site))
+    _, _, _, al_d, packed = setup_weights(hbl, site)
+    ws = hbl.alloc_workspace(site.T, site.K, site.N, 4)
+    y1 = torch.empty((site.T, site.N), dtype=torch.bfloat16, device="cuda")
+    y2 = torch.empty_like(y1)
+    hbl.hbitlinear_forward(x, packed, site.N, al_d, 4, EPS, y=y1, workspace=ws)
+    hbl.hbitlinear_forward(x, packed, site.N, al_d, 4, EPS, y=y2, workspace=ws)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        y3 = hbl.hbitlinear_forward(x, packed, site.N, al_d, 4, EPS)
+    s.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+    assert torch.equal(y1.view(torch.int16), y3.view(torch.int16))
+
+
+def test_empty_batch_and_errors_on_device(hbl):
+    note("empty batch / errors")
+    x = torch.empty((0, 256), dtype=torch.bfloat16, device="cuda")
+    packed = torch.zeros(256 * 256 // 4, dtype=torch.uint8, device="cuda")
+    al = torch.ones(1, dtype=torch.float32, device="cuda")
+    y = hbl.hbitlinear_forward(x, packed, 256, al, 4)
+    assert y.shape == (0, 256)
+    with pytest.raises(hbl.HblError) as e:
+        hbl.hbitlinear_forward(torch.zeros((4, 192), dtype=torch.bfloat16, device="cuda"), packed, 256, al, 4)
+    assert e.value.status == hbl.E_SHAPE
+    with pytest.raises(hbl.HblError) as e:
+        hbl.hbitlinear_forward(torch.zeros((4, 256), dtype=torch.bfloat16, device="cuda"), packed, 256, al, 6)
+    assert e.value.status == hbl.E_BITS
