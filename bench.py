@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the H-BitLinear forward path on one MI355X.
+
+A step = one pass of the whole hot path over one batch: the FWHT+quantiser launch
+(Eq. 3-6) followed by the ternary-GEMM+dequant launch (Eq. 7) - exactly the two
+launches hbl_hbitlinear_forward() makes - on the 7B-shaped prefill W_down site:
+X bf16 [8192 x 16384] -> 4096, INT4 activations (configuration 4, the shape the
+target "% of INT8 MFMA peak" is quoted on).  Inputs are resident in HBM before
+the timed region.  One JSON line is printed; it also carries the roofline of the
+dominant kernel (the GEMM, timed with events on the launch stream inside the
+timed region), the oracle timed on the host cores on a bounded sample, and the
+batched-decode layer figures (configuration 5).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X published dense int8 (5.0 POP/s)
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--site", default="wdown_7b", choices=["wdown_7b", "wo_7b"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--decode-layers", type=int, default=24)
+    return ap.parse_args()
+
+
+def setup_site(hbl, synth, torch, site, eps):
+    """Weights: draw -> ternarise per scale group -> pack (all on the GPU path)."""
+    W = synth.make_w(site)
+    rows = site.N // site.groups
+    codes, alphas = [], []
+    for g in range(site.groups):
+        c, a = hbl.ternarize_weights_absmean(torch.from_numpy(W[g * rows:(g + 1) * rows]).cuda(), eps)
+        codes.append(c)
+        alphas.append(a)
+    packed = hbl.pack_ternary_2bit(torch.cat(codes, 0).contiguous())
+    return packed, torch.cat(alphas).contiguous(), W
+
+
+def to_dev(torch, np, x):
+    if x.dtype == np.uint16:
+        return torch.from_numpy(x.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(x).cuda()
+
+
+def bench_prefill(args, hbl, synth, torch, np):
+    site = {s.name: s for s in synth.config_sites(4)}[args.site]
+    T, K, N, bits, eps = site.T, site.K, site.N, 4, hbl.EPS
+    x_host = synth.make_x(site)
+    x = to_dev(torch, np, x_host)
+    packed, alphas, W_host = setup_site(hbl, synth, torch, site, eps)
+    codes = torch.empty((T, K), dtype=torch.int8, device="cuda")
+    sd = torch.empty(T, dtype=torch.float32, device="cuda")
+    cs = torch.empty(T, dtype=torch.int32, device="cuda")
+    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    ws = hbl.alloc_workspace(T, K, N, bits)
+
+    def step_split(ev=None):
+        if ev:
+            ev[0].record()
+        hbl.fwht_quant_into(x, bits, site.hadamard, codes, sd, cs, eps)
+        if ev:
+            ev[1].record()
+        hbl.gemm_dequant_bf16(codes, sd, cs, packed, N, alphas, y=y)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step_split()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step_split(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    t_quant = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps     # ms
+    t_gemm = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps      # ms
+
+    # the same work through the single public call, as a cross-check of the split timing
+    for _ in range(3):
+        hbl.hbitlinear_forward(x, packed, N, alphas, bits, eps, y=y, workspace=ws)
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        hbl.hbitlinear_forward(x, packed, N, alphas, bits, eps, y=y, workspace=ws)
+    torch.cuda.synchronize()
+    ms_single = (time.perf_counter() - t2) * 1e3 / args.steps
+
+    ops = 2.0 * T * K * N
+    out = {
+        "T": T, "K": K, "N": N, "ms_per_step": ms_per_step, "ms_single_call": ms_single,
+        "ms_fwht_quant": t_quant, "ms_gemm": t_gemm,
+        "tops_end_to_end": ops / (ms_per_step * 1e-3) / 1e12,
+        "tops_gemm": ops / (t_gemm * 1e-3) / 1e12,
+        "fwht_quant_gbs": (2.0 * T * K + T * K + 8.0 * T) / (t_quant * 1e-3) / 1e9,
+    }
+    return out, site, x_host, W_host
+
+
+def cpu_baseline(site, x_host, W_host, synth, np, budget_s=15.0):
+    """The oracle as it stands, on a bounded sample of token rows of the same workload."""
+    from oracle import hbl_oracle as O
+    wc, alpha = O.ternarize_weights_absmean(W_host, 1e-5)
+    rows = 8
+    t0 = time.perf_counter()
+    O.bitlinear_forward(np.ascontiguousarray(x_host[:rows]), wc, alpha, 4, site.hadamard, 1e-5)
+    dt = time.perf_counter() - t0
+    rows2 = int(max(rows, min(site.T, rows * budget_s / max(dt, 1e-3))))
+    rows2 = max(O.num_threads(), rows2 // O.num_threads() * O.num_threads())
+    t0 = time.perf_counter()
+    O.bitlinear_forward(np.ascontiguousarray(x_host[:rows2]), wc, alpha, 4, site.hadamard, 1e-5)
+    dt = time.perf_counter() - t0
+    return {
+        "value": 2.0 * rows2 * site.K * site.N / dt / 1e12, "unit": "TOPS", "cores": O.num_threads(),
+        "kind": "oracle", "seconds": dt,
+        "sample": f"first {rows2} of {site.T} token rows of the same X, all {site.N} outputs "
+                  f"(FWHT + INT4 quantiser + int32 GEMM + bf16 dequant)",
+    }
+
+
+def bench_decode(args, hbl, synth, torch, np):
+    """Configuration 5: one 7B decoder layer's four projections, weights cycled over `layers`
+    independent copies (1.6 GB at 24) so that they stream from HBM rather than from cache."""
+    eps, bits = hbl.EPS, 4
+    layers = args.decode_layers
+    base = synth.config_sites(5, batch=64)
+    # independent packed weights per layer: drawn once on the GPU (uniform ternary codes are enough
+    # for timing: the kernels' work does not depend on the weight values)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4)
+    packed = []
+    for _ in range(layers):
+        per = []
+        for s in base:
+            c = torch.randint(-1, 2, (s.N, s.K), dtype=torch.int8, device="cuda", generator=g)
+            per.append(hbl.pack_ternary_2bit(c))
+            del c
+        packed.append(per)
+    alphas = [torch.full((s.groups,), 0.016, dtype=torch.float32, device="cuda") for s in base]
+    w_bytes = sum(s.N * s.K // 4 for s in base)
+    res = {}
+    for B in (1, 8, 32, 64):
+        sites = synth.config_sites(5, batch=B)
+        xs = [to_dev(torch, np, synth.make_x(s)) for s in sites]
+        ys = [torch.empty((B, s.N), dtype=torch.bfloat16, device="cuda") for s in sites]
+        wss = [hbl.alloc_workspace(B, s.K, s.N, bits) for s in sites]
+
+        def layer(l):
+            for i, s in enumerate(sites):
+                fn = hbl.hbitlinear_forward if s.hadamard else hbl.plain_bitlinear_forward
+                fn(xs[i], packed[l][i], s.N, alphas[i], bits, eps, y=ys[i], workspace=wss[i])
+
+        for l in range(layers):
+            layer(l)
+        torch.cuda.synchronize()
+        reps = 3
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            for l in range(layers):
+                layer(l)
+        e1.record()
+        torch.cuda.synchronize()
+        us_layer = e0.elapsed_time(e1) * 1e3 / (reps * layers)
+        io_bytes = sum(2 * B * s.K + 2 * B * s.N for s in sites)
+        gbs = (w_bytes + io_bytes) / (us_layer * 1e-6) / 1e9
+        res[str(B)] = {"us_per_layer": us_layer, "GBps": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+    return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes, "launch": "eager, 8 launches per layer",
+            "batch": res}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU only (the hot path is a single-GPU kernel pair; "
+                         "tokens shard trivially across GPUs with no exchange). Use --gpus 1.\n")
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2504_18415_amd import hbl, synth
+    hbl.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    pre, site, x_host, W_host = bench_prefill(args, hbl, synth, torch, np)
+    result = {
+        "metric": "H-BitLinear TOPS (INT4 acts)", "value": pre["tops_end_to_end"], "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": pre["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8",
+        "data": "synthetic",
+        "config": {"workload": f"config 4 (7B prefill) {site.name}: X bf16 [{site.T}x{site.K}] -> {site.N}, "
+                               f"Hadamard n={site.K}, INT4 activations, 2-bit packed ternary W",
+                   "T": site.T, "K": site.K, "N": site.N, "bits": 4},
+        "frac_int8_mfma_peak_end_to_end": pre["tops_end_to_end"] / INT8_MFMA_PEAK_TOPS,
+        "roofline": {"kernel": "ternary_gemm_kernel (GEMM + dequant epilogue)", "bound": "mfma",
+                     "achieved": pre["tops_gemm"], "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": pre["tops_gemm"] / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "avg_kernel_ms": pre["ms_gemm"]},
+        "fwht_quant": {"avg_kernel_ms": pre["ms_fwht_quant"], "bound": "hbm", "achieved": pre["fwht_quant_gbs"],
+                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pre["fwht_quant_gbs"] / HBM_PEAK_GBS},
+        "ms_single_call": pre["ms_single_call"],
+    }
+    if not args.no_decode:
+        torch.cuda.empty_cache()
+        result["decode"] = bench_decode(args, hbl, synth, torch, np)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(site, x_host, W_host, synth, np)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

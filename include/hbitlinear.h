@@ -149,6 +149,18 @@ int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, f
 int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
                  int32_t* acc, void* stream);
 
+/*
+ * GEMM + dequantising epilogue only (Eq. 7 given the quantised activations): the second of the
+ * two launches the forward calls make, on caller-held intermediates.
+ *   codes [T, K] int8, s_dequant [T] fp32, code_sum [T] int32: as written by hbl_fwht_quant
+ *   y [T, N] bf16 out
+ * hbl_hbitlinear_forward(x, ...) == hbl_fwht_quant(x, ..., hadamard=1) into the workspace followed
+ * by this call; hbl_plain_bitlinear_forward likewise with hadamard=0.
+ */
+int hbl_gemm_dequant_bf16(const int8_t* codes, const float* s_dequant, const int32_t* code_sum, int64_t T,
+                          int64_t K, const void* Wq_packed, int64_t N, const float* w_scales,
+                          int64_t n_scale_groups, void* y, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

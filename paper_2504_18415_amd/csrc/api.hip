@@ -146,4 +146,17 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
                                static_cast<hipStream_t>(stream));
 }
 
+int hbl_gemm_dequant_bf16(const int8_t* codes, const float* s_dequant, const int32_t* code_sum, int64_t T,
+                          int64_t K, const void* Wq_packed, int64_t N, const float* w_scales,
+                          int64_t n_scale_groups, void* y, void* stream) {
+    int rc = check_gemm_shape(T, K, N, false);
+    if (rc != HBL_OK) return rc;
+    if (n_scale_groups < 1 || (N % n_scale_groups) != 0 || ((N / n_scale_groups) % 32) != 0) return HBL_E_SHAPE;
+    if (T == 0) return HBL_OK;
+    if (!codes || !s_dequant || !code_sum || !Wq_packed || !w_scales || !y) return HBL_E_NULL;
+    if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(y)) return HBL_E_ALIGN;
+    return launch_ternary_gemm(codes, T, K, Wq_packed, N, s_dequant, code_sum, w_scales, n_scale_groups, y,
+                               nullptr, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

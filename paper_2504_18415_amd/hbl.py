@@ -28,6 +28,7 @@ EXPORTS = [
     "hbl_strerror", "hbl_last_hip_error", "hbl_ternarize_workspace_bytes", "hbl_ternarize_weights_absmean",
     "hbl_packed_bytes", "hbl_pack_ternary_2bit", "hbl_unpack_ternary_2bit", "hbl_workspace_bytes",
     "hbl_hbitlinear_forward", "hbl_plain_bitlinear_forward", "hbl_fwht_quant", "hbl_gemm_i32",
+    "hbl_gemm_dequant_bf16",
 ]
 
 _lib = None
@@ -69,6 +70,7 @@ def lib():
         L.hbl_plain_bitlinear_forward.argtypes = fwd
         L.hbl_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, vp, vp, vp, vp]
         L.hbl_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp, vp]
+        L.hbl_gemm_dequant_bf16.argtypes = [vp, vp, vp, i64, i64, vp, i64, vp, i64, vp, vp]
         _lib = L
     return _lib
 
@@ -187,3 +189,23 @@ def gemm_i32(codes: torch.Tensor, Wq_packed: torch.Tensor, N: int) -> torch.Tens
     acc = torch.empty((T, N), dtype=torch.int32, device=codes.device)
     _check(lib().hbl_gemm_i32(_ptr(codes), T, K, _ptr(Wq_packed), N, _ptr(acc), _stream()), "gemm_i32")
     return acc
+
+
+def gemm_dequant_bf16(codes: torch.Tensor, s_dequant: torch.Tensor, code_sum: torch.Tensor, Wq_packed: torch.Tensor,
+                      N: int, w_scales: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Second launch of the forward on caller-held intermediates: y bf16 [T,N]."""
+    _dev_check(codes, s_dequant, code_sum, Wq_packed, w_scales, y)
+    T, K = codes.shape
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=codes.device)
+    _check(lib().hbl_gemm_dequant_bf16(_ptr(codes), _ptr(s_dequant), _ptr(code_sum), T, K, _ptr(Wq_packed), N,
+                                       _ptr(w_scales), w_scales.numel(), _ptr(y), _stream()), "gemm_dequant_bf16")
+    return y
+
+
+def fwht_quant_into(x: torch.Tensor, bits: int, hadamard: bool, codes: torch.Tensor, s_dequant: torch.Tensor,
+                    code_sum: torch.Tensor, eps: float = EPS) -> None:
+    """hbl_fwht_quant into caller-held buffers (no allocation)."""
+    T, K = x.shape
+    _check(lib().hbl_fwht_quant(_ptr(x), _x_dtype(x), T, K, bits, eps, int(hadamard), _ptr(codes), _ptr(s_dequant),
+                                _ptr(code_sum), _stream()), "fwht_quant")
