@@ -71,10 +71,10 @@ def bench_prefill(args, hbl, synth, torch, np):
     def step_split(ev=None):
         if ev:
             ev[0].record()
-        hbl.fwht_quant_into(x, bits, site.hadamard, codes, sd, cs, eps)
+        hbl.fwht_quant_into(x, bits, site.hadamard, codes, sd, cs, eps, code_offset=8)
         if ev:
             ev[1].record()
-        hbl.gemm_dequant_bf16(codes, sd, cs, packed, N, alphas, y=y)
+        hbl.gemm_dequant_bf16(codes, sd, cs, packed, N, alphas, y=y, code_offset=8)
         if ev:
             ev[2].record()
 
@@ -153,7 +153,7 @@ def bench_decode(args, hbl, synth, torch, np):
             del c
         packed.append(per)
     alphas = [torch.full((s.groups,), 0.016, dtype=torch.float32, device="cuda") for s in base]
-    w_bytes = sum(s.N * s.K // 4 for s in base)
+    w_bytes = sum(s.N * s.K // 4 + 4 * s.N for s in base)
     res = {}
     for B in (1, 8, 32, 64):
         sites = synth.config_sites(5, batch=B)

@@ -74,7 +74,7 @@ size_t hbl_ternarize_workspace_bytes(int64_t N, int64_t K);
 int hbl_ternarize_weights_absmean(const float* W, int64_t N, int64_t K, float eps, int8_t* codes,
                                   float* alpha, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of the packed form of an [N, K] ternary tensor: N*K/4 (2 bits per weight). */
+/* Bytes of the packed form of an [N, K] ternary tensor: N*K/4 (2 bits per weight) + 4*N (row sums). */
 size_t hbl_packed_bytes(int64_t N, int64_t K);
 
 /*
@@ -82,7 +82,8 @@ size_t hbl_packed_bytes(int64_t N, int64_t K);
  * the paper, which describes no storage format).  The layout is opaque to the
  * caller: 1 KiB tiles of 32 output rows x 128 input features, ordered so that
  * one 16-byte load per lane yields matrix-core operands; each weight is
- * stored as code+1 in {0,1,2}.  hbl_unpack_ternary_2bit is the exact inverse.
+ * stored as code+1 in {0,1,2}; the tiles are followed by the N int32 row sums
+ * sum_k c[o][k] that the epilogue uses.  hbl_unpack_ternary_2bit is the exact inverse.
  *   codes  [N, K] int8 in {-1,0,1};   packed  hbl_packed_bytes(N, K) bytes, 16-byte aligned
  */
 int hbl_pack_ternary_2bit(const int8_t* codes, int64_t N, int64_t K, void* packed, void* stream);
@@ -135,12 +136,17 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
 
 /*
  * Activation front end only (Eq. 3-6): transform (if hadamard != 0) and quantise.
+ *   code_offset  0: codes are stored as such.  8 (INT4 only): stored byte = code + 8 in 0..15 - the
+ *              form the forward calls use internally for INT4, because unsigned nibbles toggle far
+ *              fewer multiplier input bits than sign-extended bytes and the matrix cores are
+ *              power-limited; the GEMM epilogue removes the offset exactly in int32.
  *   codes      [T, K] int8 out in natural feature order
  *   s_dequant  [T] fp32 out: gamma/127 or beta/sqrt7
- *   code_sum   [T] int32 out or NULL: sum_k codes[t][k]
+ *   code_sum   [T] int32 out or NULL: sum_k code[t][k] of the true codes (without the offset)
  */
 int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps,
-                   int hadamard, int8_t* codes, float* s_dequant, int32_t* code_sum, void* stream);
+                   int hadamard, int code_offset, int8_t* codes, float* s_dequant, int32_t* code_sum,
+                   void* stream);
 
 /*
  * Integer contraction only: acc[t][o] = sum_k codes[t][k] * c[o][k] (int32, exact).
@@ -152,14 +158,14 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
 /*
  * GEMM + dequantising epilogue only (Eq. 7 given the quantised activations): the second of the
  * two launches the forward calls make, on caller-held intermediates.
- *   codes [T, K] int8, s_dequant [T] fp32, code_sum [T] int32: as written by hbl_fwht_quant
- *   y [T, N] bf16 out
- * hbl_hbitlinear_forward(x, ...) == hbl_fwht_quant(x, ..., hadamard=1) into the workspace followed
- * by this call; hbl_plain_bitlinear_forward likewise with hadamard=0.
+ *   codes [T, K] int8, s_dequant [T] fp32, code_sum [T] int32: as written by hbl_fwht_quant with
+ *   the same code_offset;  y [T, N] bf16 out
+ * hbl_hbitlinear_forward(x, ...) == hbl_fwht_quant(x, ..., hadamard=1, code_offset = bits==4 ? 8 : 0)
+ * into the workspace followed by this call; hbl_plain_bitlinear_forward likewise with hadamard=0.
  */
-int hbl_gemm_dequant_bf16(const int8_t* codes, const float* s_dequant, const int32_t* code_sum, int64_t T,
-                          int64_t K, const void* Wq_packed, int64_t N, const float* w_scales,
-                          int64_t n_scale_groups, void* y, void* stream);
+int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_dequant,
+                          const int32_t* code_sum, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+                          const float* w_scales, int64_t n_scale_groups, void* y, void* stream);
 
 #ifdef __cplusplus
 }

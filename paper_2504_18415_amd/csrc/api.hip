@@ -37,10 +37,12 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     if (workspace_bytes < hbl_workspace_bytes(T, K, N, bits)) return HBL_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Workspace ws = carve_workspace(workspace, T, K);
-    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, s);
+    // INT4 codes travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs
+    const int code_offset = bits == 4 ? 8 : 0;
+    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, code_offset, s);
     if (rc != HBL_OK) return rc;
-    return launch_ternary_gemm(ws.codes, T, K, Wq_packed, N, ws.s_dequant, ws.code_sum, w_scales, groups, y,
-                               nullptr, s);
+    return launch_ternary_gemm(ws.codes, code_offset, T, K, Wq_packed, N, ws.s_dequant, ws.code_sum, w_scales, groups,
+                               y, nullptr, s);
 }
 
 }  // namespace
@@ -82,7 +84,7 @@ int hbl_ternarize_weights_absmean(const float* W, int64_t N, int64_t K, float ep
 
 size_t hbl_packed_bytes(int64_t N, int64_t K) {
     if (N <= 0 || K <= 0) return 0;
-    return (size_t)N * (size_t)K / 4;
+    return packed_tile_bytes(N, K) + (size_t)N * sizeof(int32_t);
 }
 
 int hbl_pack_ternary_2bit(const int8_t* codes, int64_t N, int64_t K, void* packed, void* stream) {
@@ -123,7 +125,8 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
 }
 
 int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int hadamard,
-                   int8_t* codes, float* s_dequant, int32_t* code_sum, void* stream) {
+                   int code_offset, int8_t* codes, float* s_dequant, int32_t* code_sum, void* stream) {
+    if (code_offset != 0 && !(code_offset == 8 && bits == 4)) return HBL_E_BITS;
     if (bits != 4 && bits != 8) return HBL_E_BITS;
     if (x_dtype != HBL_F32 && x_dtype != HBL_BF16) return HBL_E_DTYPE;
     int rc = check_gemm_shape(T, K, 32, hadamard != 0);
@@ -131,7 +134,7 @@ int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, f
     if (T == 0) return HBL_OK;
     if (!x || !codes || !s_dequant) return HBL_E_NULL;
     if (!aligned16(x) || !aligned16(codes)) return HBL_E_ALIGN;
-    return launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard != 0, codes, s_dequant, code_sum,
+    return launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard != 0, codes, s_dequant, code_sum, code_offset,
                              static_cast<hipStream_t>(stream));
 }
 
@@ -142,21 +145,22 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
     if (T == 0) return HBL_OK;
     if (!codes || !Wq_packed || !acc) return HBL_E_NULL;
     if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(acc)) return HBL_E_ALIGN;
-    return launch_ternary_gemm(codes, T, K, Wq_packed, N, nullptr, nullptr, nullptr, 1, nullptr, acc,
+    return launch_ternary_gemm(codes, 0, T, K, Wq_packed, N, nullptr, nullptr, nullptr, 1, nullptr, acc,
                                static_cast<hipStream_t>(stream));
 }
 
-int hbl_gemm_dequant_bf16(const int8_t* codes, const float* s_dequant, const int32_t* code_sum, int64_t T,
-                          int64_t K, const void* Wq_packed, int64_t N, const float* w_scales,
+int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_dequant, const int32_t* code_sum,
+                          int64_t T, int64_t K, const void* Wq_packed, int64_t N, const float* w_scales,
                           int64_t n_scale_groups, void* y, void* stream) {
+    if (code_offset != 0 && code_offset != 8) return HBL_E_BITS;
     int rc = check_gemm_shape(T, K, N, false);
     if (rc != HBL_OK) return rc;
     if (n_scale_groups < 1 || (N % n_scale_groups) != 0 || ((N / n_scale_groups) % 32) != 0) return HBL_E_SHAPE;
     if (T == 0) return HBL_OK;
     if (!codes || !s_dequant || !code_sum || !Wq_packed || !w_scales || !y) return HBL_E_NULL;
     if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(y)) return HBL_E_ALIGN;
-    return launch_ternary_gemm(codes, T, K, Wq_packed, N, s_dequant, code_sum, w_scales, n_scale_groups, y,
-                               nullptr, static_cast<hipStream_t>(stream));
+    return launch_ternary_gemm(codes, code_offset, T, K, Wq_packed, N, s_dequant, code_sum, w_scales,
+                               n_scale_groups, y, nullptr, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -95,7 +95,7 @@ __device__ __forceinline__ void load_chunk(const void* x, int64_t off, float (&d
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
 __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restrict__ x, int8_t* __restrict__ codes,
                                                             float* __restrict__ s_dequant,
-                                                            int32_t* __restrict__ code_sum, float eps) {
+                                                            int32_t* __restrict__ code_sum, float eps, int code_offset) {
     constexpr int K = 1 << LOG2K;
     constexpr int NT = 64 * W;
     constexpr int E = K / NT;            // elements per thread
@@ -238,6 +238,8 @@ __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restri
     // leaves its two's complement in the low mantissa bits
     constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
     constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
+    // stored byte = code + code_offset: folding the offset into the rounding constant costs nothing
+    const float magic = kMagic + (float)code_offset;
     int isum = 0;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -248,7 +250,7 @@ __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restri
         for (int e = 0; e < CH; ++e) {
             const float y = v[r][e] * gain;
             const float t = __builtin_amdgcn_fmed3f(y, lo, hi);
-            const uint32_t bits = as_u(t + kMagic);
+            const uint32_t bits = as_u(t + magic);
             isum += (int)bits;
             packed[e / 4] |= (bits & 0xFFu) << (8 * (e % 4));
         }
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restri
             *reinterpret_cast<uint8_t*>(dst) = (uint8_t)packed[0];
         }
     }
-    isum = (int)((uint32_t)isum - (uint32_t)E * 0x4B400000u);  // remove the magic constant's bit pattern (mod 2^32)
+    isum = (int)((uint32_t)isum - (uint32_t)E * as_u(magic));  // remove the constant's bit pattern (mod 2^32)
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
     if constexpr (W > 1) {
@@ -288,7 +290,7 @@ __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restri
 
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
 int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, float eps,
-               hipStream_t stream) {
+               int code_offset, hipStream_t stream) {
     constexpr int K = 1 << LOG2K;
     const size_t lds = (HADAMARD && W > 1) ? sizeof(float) * K : 0;
     auto kern = fwht_quant_kernel<LOG2K, W, BITS, BF16, HADAMARD>;
@@ -297,7 +299,7 @@ int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return note_hip_error(e);
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, eps);
+    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, eps, code_offset);
     return after_launch();
 }
 
@@ -308,7 +310,7 @@ template <int BITS, bool BF16>
 __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restrict__ x, int K,
                                                             int8_t* __restrict__ codes,
                                                             float* __restrict__ s_dequant,
-                                                            int32_t* __restrict__ code_sum, float eps) {
+                                                            int32_t* __restrict__ code_sum, float eps, int code_offset) {
     constexpr int MAXC = 8;
     __shared__ double red_d[4];
     __shared__ float red_f[4];
@@ -358,6 +360,8 @@ __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restri
     }
     constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
     constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
+    // stored byte = code + code_offset: folding the offset into the rounding constant costs nothing
+    const float magic = kMagic + (float)code_offset;
     int isum = 0;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) {
@@ -367,8 +371,8 @@ __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restri
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float t = __builtin_amdgcn_fmed3f(v[c][e] * gain, lo, hi);
-                const uint32_t bits = as_u(t + kMagic);
-                isum += (int)bits - (int)0x4B400000;
+                const uint32_t bits = as_u(t + magic);
+                isum += (int)(bits - as_u(magic));
                 packed[e / 4] |= (bits & 0xFFu) << (8 * (e % 4));
             }
             *reinterpret_cast<uint2*>(codes + row_off + (int64_t)ch * 8) = make_uint2(packed[0], packed[1]);
@@ -385,50 +389,50 @@ __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restri
 }
 
 int launch_generic(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int8_t* codes,
-                   float* s_dequant, int32_t* code_sum, hipStream_t stream) {
+                   float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     const dim3 grid((unsigned)T), block(256);
     const bool bf = x_dtype == HBL_BF16;
     if (bits == 8) {
-        if (bf) hipLaunchKernelGGL((quant_generic_kernel<8, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps);
-        else    hipLaunchKernelGGL((quant_generic_kernel<8, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps);
+        if (bf) hipLaunchKernelGGL((quant_generic_kernel<8, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps, code_offset);
+        else    hipLaunchKernelGGL((quant_generic_kernel<8, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps, code_offset);
     } else {
-        if (bf) hipLaunchKernelGGL((quant_generic_kernel<4, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps);
-        else    hipLaunchKernelGGL((quant_generic_kernel<4, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps);
+        if (bf) hipLaunchKernelGGL((quant_generic_kernel<4, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps, code_offset);
+        else    hipLaunchKernelGGL((quant_generic_kernel<4, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps, code_offset);
     }
     return after_launch();
 }
 
 template <int LOG2K, int W>
 int dispatch(const void* x, int x_dtype, int64_t T, int bits, float eps, bool hadamard, int8_t* codes,
-             float* s_dequant, int32_t* code_sum, hipStream_t stream) {
+             float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     const bool bf = x_dtype == HBL_BF16;
     if (hadamard) {
-        if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, true>(x, T, codes, s_dequant, code_sum, eps, stream)
-                                 : launch_one<LOG2K, W, 8, false, true>(x, T, codes, s_dequant, code_sum, eps, stream);
-        return bf ? launch_one<LOG2K, W, 4, true, true>(x, T, codes, s_dequant, code_sum, eps, stream)
-                  : launch_one<LOG2K, W, 4, false, true>(x, T, codes, s_dequant, code_sum, eps, stream);
+        if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
+                                 : launch_one<LOG2K, W, 8, false, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
+        return bf ? launch_one<LOG2K, W, 4, true, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
+                  : launch_one<LOG2K, W, 4, false, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
     }
-    if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, false>(x, T, codes, s_dequant, code_sum, eps, stream)
-                             : launch_one<LOG2K, W, 8, false, false>(x, T, codes, s_dequant, code_sum, eps, stream);
-    return bf ? launch_one<LOG2K, W, 4, true, false>(x, T, codes, s_dequant, code_sum, eps, stream)
-              : launch_one<LOG2K, W, 4, false, false>(x, T, codes, s_dequant, code_sum, eps, stream);
+    if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
+                             : launch_one<LOG2K, W, 8, false, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
+    return bf ? launch_one<LOG2K, W, 4, true, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
+              : launch_one<LOG2K, W, 4, false, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
 }
 
 }  // namespace
 
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
-                      int8_t* codes, float* s_dequant, int32_t* code_sum, hipStream_t stream) {
+                      int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     if (T == 0) return HBL_OK;
-    if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, eps, codes, s_dequant, code_sum, stream);
+    if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
     switch (K) {
-        case 128:   return dispatch<7, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
-        case 256:   return dispatch<8, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
-        case 512:   return dispatch<9, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
-        case 1024:  return dispatch<10, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
-        case 2048:  return dispatch<11, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
-        case 4096:  return dispatch<12, 2>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
-        case 8192:  return dispatch<13, 4>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
-        case 16384: return dispatch<14, 4>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, stream);
+        case 128:   return dispatch<7, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 256:   return dispatch<8, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 512:   return dispatch<9, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 1024:  return dispatch<10, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 2048:  return dispatch<11, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 4096:  return dispatch<12, 2>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 8192:  return dispatch<13, 4>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 16384: return dispatch<14, 4>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
         default:    return HBL_E_SHAPE;
     }
 }

@@ -42,14 +42,18 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K) {
 }
 
 // Launchers (defined in the .hip files). All validate nothing: callers in api.hip do.
+// Codes are stored as code + code_offset (0, or 8 for INT4 so that the stored bytes are 0..15).
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
-                      int8_t* codes, float* s_dequant, int32_t* code_sum, hipStream_t stream);
+                      int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream);
 
 // GEMM + epilogue. If acc_out != nullptr the raw int32 accumulators are written
 // (no scales, no code_sum needed); otherwise y (bf16) is written.
-int launch_ternary_gemm(const int8_t* codes, int64_t T, int64_t K, const void* packed, int64_t N,
+int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,
                         const float* s_dequant, const int32_t* code_sum, const float* w_scales,
                         int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, hipStream_t stream);
+
+// Packed weight buffer: N*K/4 bytes of 2-bit tiles, then N int32 row sums of the ternary codes.
+inline size_t packed_tile_bytes(int64_t N, int64_t K) { return (size_t)N * (size_t)K / 4; }
 
 int launch_ternarize(const float* W, int64_t count, float eps, int8_t* codes, float* alpha, void* workspace,
                      hipStream_t stream);

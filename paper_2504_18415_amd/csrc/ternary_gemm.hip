@@ -12,6 +12,10 @@
 // sum_k q[t][k] (the per-token code sum written by the quantiser kernel) is subtracted in the
 // epilogue, all in int32.  Both operands are staged through LDS with direct global->LDS 16-byte
 // loads, NSTAGE deep: codes into an XOR-swizzled [token][128 B] layout, weights tile by tile.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "hbl_internal.h"
 
 namespace hbl {
@@ -28,9 +32,20 @@ __device__ __forceinline__ uint32_t as_u(float f) { return __builtin_bit_cast(ui
 // Written as one asm block: __syncthreads() carries a release fence that the compiler lowers to
 // vmcnt(0), which would drain the whole global->LDS pipeline at every stage.  The "memory" clobber
 // keeps every load / store on its side of the barrier.
+// lgkmcnt(0): this wave's own LDS reads of the buffer about to be recycled have returned.
 template <int N>
 __device__ __forceinline__ void wait_loads_then_barrier() {
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// One 16-byte-per-lane global -> LDS copy: lane l's 16 bytes at (base + voff) land at LDS byte
+// lds_addr + 16*l.  Written in asm so that the address is exactly "SGPR pair + 32-bit VGPR offset"
+// (no per-copy vector address arithmetic) and the copy stays where the source puts it.
+__device__ __forceinline__ void lds_dma16(uint32_t lds_addr, const void* base, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float v) {
@@ -60,7 +75,9 @@ struct GemmArgs {
     const int8_t* codes;      // [T, K]
     const uint32_t* packed;   // tiles [N/32][K/128][64 lanes][4 dwords]
     const float* s_dequant;   // [T]
-    const int32_t* code_sum;  // [T]
+    const int32_t* code_sum;  // [T] sum_k q[t][k] of the true (un-offset) codes
+    const int32_t* w_row_sum; // [N] sum_k c[o][k]
+    int code_offset;          // stored code byte = q + code_offset
     const float* w_scales;    // [groups]
     uint16_t* y;              // [T, N] bf16
     int32_t* acc_out;         // [T, N] (RAW only)
@@ -108,19 +125,23 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
     const int t0 = tile_t * BT;
     const int nkb = a.K / kBK;
 
-    // weight tiles this wave copies into LDS (tile index inside the workgroup tile: wave + NW*m);
-    // tiles past N are clamped (their results are dropped in the epilogue)
-    const uint32_t* wptr[WL];
+    // Global -> LDS copies: wave-uniform 64-bit base (SGPR pair) + 32-bit per-lane offset, so that
+    // advancing along K is scalar arithmetic only.
+    // weights: this wave copies tiles wave + NW*m of the workgroup tile; tiles past N are clamped (their
+    // results are dropped in the epilogue)
+    const char* wbase[WL];
 #pragma unroll
     for (int m = 0; m < WL; ++m) {
         int nt = n0 / 32 + wave + NW * m;
         const int nt_max = a.N / 32 - 1;
         nt = nt < nt_max ? nt : nt_max;
-        wptr[m] = a.packed + ((size_t)nt * nkb) * 256 + lane * 4;
+        wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb) * 1024;
     }
+    const uint32_t wlane = lane * 16;
     // activation codes: instruction q covers tokens 8q..8q+7, lane l -> token 8q + l/8, LDS slot l%8,
-    // global 16-byte chunk (l%8) ^ (token % 8)
-    const int8_t* xptr[XL];
+    // global 16-byte chunk (l%8) ^ (token % 8); rows past T are clamped to the last row
+    const char* xbase = reinterpret_cast<const char*>(a.codes) + (size_t)t0 * a.K;
+    uint32_t xlane[XL];
 #pragma unroll
     for (int m = 0; m < XL; ++m) {
         const int q = wave + NW * m;
@@ -128,29 +149,27 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
         int t = t0 + row;
         t = t < a.T ? t : a.T - 1;
         const int c = (lane & 7) ^ (row & 7);
-        xptr[m] = a.codes + (size_t)t * a.K + c * 16;
+        xlane[m] = (uint32_t)(t - t0) * (uint32_t)a.K + c * 16;
     }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
-    // stage kb -> LDS buffer `slot`; past the end of K the last block is re-read so that every
-    // iteration issues the same number of loads (the in-flight count above relies on it)
-    auto issue = [&](int kb, int slot) {
+    // Copy number m (0 .. XL+WL-1) of stage kb into LDS buffer `slot`.  Past the end of K the last
+    // block is re-read so that every stage issues the same number of copies (the in-flight count
+    // PENDING relies on it).
+    auto issue_one = [&](int m, int kb, int slot) {
         const int kbc = kb < nkb ? kb : nkb - 1;
-        char* base = lds + slot * STAGE;
-#pragma unroll
-        for (int m = 0; m < XL; ++m) {
+        if (m < XL) {
             const int q = wave + NW * m;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(xptr[m] + (size_t)kbc * kBK),
-                (__attribute__((address_space(3))) void*)(base + q * 1024), 16, 0, 0);
-        }
-#pragma unroll
-        for (int m = 0; m < WL; ++m) {
-            const int wtile = wave + NW * m;
+            lds_dma16(lds0 + slot * STAGE + q * 1024, xbase + (size_t)kbc * kBK, xlane[m]);
+        } else {
+            const int wtile = wave + NW * (m - XL);
             if ((BN / 32) % NW == 0 || wtile < BN / 32)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(wptr[m] + (size_t)kbc * 256),
-                    (__attribute__((address_space(3))) void*)(base + XBYTES + wtile * 1024), 16, 0, 0);
+                lds_dma16(lds0 + slot * STAGE + XBYTES + wtile * 1024, wbase[m - XL] + (size_t)kbc * 1024, wlane);
         }
+    };
+    auto issue = [&](int kb, int slot) {
+#pragma unroll
+        for (int m = 0; m < XL + WL; ++m) issue_one(m, kb, slot);
     };
 
     v16i acc[TN][TT];
@@ -168,48 +187,122 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
         xoff[ks] = (wt * TT * 32 + (lane & 31)) * kBK + (((2 * ks + (lane >> 5)) ^ (lane & 7)) << 4);
     const int woff = XBYTES + wn * TN * 1024 + lane * 16;
 
-    auto compute = [&](int slot) {
-        const char* sbase = lds + slot * STAGE;
-        v4i wpk[TN];
+    // Register pipeline.  With one or two waves per SIMD, whatever a wave issues between two MFMAs is
+    // time the matrix core idles unless it fits under the previous MFMA (8 passes = 32 cycles), so the
+    // work for K-step s+1 - LDS operand reads, weight expansion, and once per stage the barrier and the
+    // global->LDS copies - is dealt out in small pieces, one piece after each MFMA of K-step s.
+    // sched_barrier(0) after every piece pins that order.
+    v4i wpk[TN];      // packed weights of the current stage (reloaded for the next one in its last K-step)
+    v4i xop[2][TT];   // code operands of the current / next K-step
+    v4i wop[2][TN];   // expanded weight operands of the current / next K-step
+    constexpr int NMF = TN * TT;                 // MFMAs per K-step
+    constexpr int EOPS = RAW ? 19 : 7;           // VALU instructions to expand one packed dword
+    // one VALU instruction of the expansion of wpk[wbuf][i][ks] into wop[obuf][i]
+    auto expand_op = [&](int ks, int obuf, int i, int op) {
+        const uint32_t p = (uint32_t)wpk[i][ks];
+        if (op == 0) wop[obuf][i][0] = (int)(p & 0x03030303u);
+        else if (op <= 6) {
+            const int r = (op + 1) / 2;
+            if (op & 1) wop[obuf][i][r] = (int)(p >> (2 * r));
+            else wop[obuf][i][r] = (int)((uint32_t)wop[obuf][i][r] & 0x03030303u);
+        } else {
+            // RAW only: bytes {0,1,2} -> {-1,0,1}, three instructions per register
+            const int r = (op - 7) / 3, st = (op - 7) % 3;
+            uint32_t v = (uint32_t)wop[obuf][i][r];
+            v = st == 0 ? (v | 0x80808080u) : st == 1 ? (v - 0x01010101u) : (v ^ 0x80808080u);
+            wop[obuf][i][r] = (int)v;
+        }
+    };
+    auto expand_all = [&](int ks, int obuf) {
 #pragma unroll
-        for (int i = 0; i < TN; ++i) wpk[i] = *reinterpret_cast<const v4i*>(sbase + woff + i * 1024);
+        for (int i = 0; i < TN; ++i)
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            v4i xop[TT];
+            for (int op = 0; op < EOPS; ++op) expand_op(ks, obuf, i, op);
+    };
+    auto load_w_one = [&](int slot, int i) {
+        wpk[i] = *reinterpret_cast<const v4i*>(lds + slot * STAGE + woff + i * 1024);
+    };
+    auto load_x_one = [&](int slot, int ks, int buf, int j) {
+        xop[buf][j] = *reinterpret_cast<const v4i*>(lds + slot * STAGE + xoff[ks] + j * 32 * kBK);
+    };
+
+    // K-step with operands (wop[CUR], xop[CUR]); meanwhile fetch / expand K-step ks_next of the same
+    // stage into (wop[CUR^1], xop[CUR^1]).
+    auto kstep_inner = [&](auto cur_tag, int slot, int ks_next) {
+        constexpr int CUR = decltype(cur_tag)::value;
+        constexpr int TOTAL = EOPS * TN;
+        constexpr int VPER = (TOTAL + NMF - 1) / NMF;
 #pragma unroll
-            for (int j = 0; j < TT; ++j) xop[j] = *reinterpret_cast<const v4i*>(sbase + xoff[ks] + j * 32 * kBK);
+        for (int g = 0; g < NMF; ++g) {
+            const int i = g / TT, j = g % TT;
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop[CUR][i], xop[CUR][j], acc[i][j], 0, 0, 0);
+            if (g < TT) load_x_one(slot, ks_next, CUR ^ 1, g);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                const v4i wop = expand<RAW>((uint32_t)wpk[i][ks]);
+            for (int v = g * VPER; v < (g + 1) * VPER && v < TOTAL; ++v)
+                expand_op(ks_next, CUR ^ 1, v / EOPS, v % EOPS);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // Last K-step of a stage (operands in [1]; the packed weights in wpk are dead by now): the copies of
+    // stage kb+NSTAGE and the next stage's LDS reads go out under the first MFMAs, the expansion of the
+    // next stage's first K-step (which needs those reads) under the last ones.
+    auto kstep_last = [&](int kb, int slot) {
+        constexpr int TOTAL = EOPS * TN;
+        constexpr int SIDE = XL + WL > TN + TT ? XL + WL : TN + TT;   // MFMAs that carry a copy / read
+        constexpr int FIRSTV = SIDE < NMF ? SIDE : 0;                  // first MFMA that carries expansion
+        constexpr int VPER = (TOTAL + (NMF - FIRSTV) - 1) / (NMF - FIRSTV);
+        const int nslot = slot + 1 == NSTAGE ? 0 : slot + 1;
+        if (SIDE >= NMF) {   // small tiles: not enough MFMAs to hide the side work under, issue it up front
+            issue(kb + NSTAGE, slot);
 #pragma unroll
-                for (int j = 0; j < TT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop, xop[j], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < TN; ++i) load_w_one(nslot, i);
+#pragma unroll
+            for (int j = 0; j < TT; ++j) load_x_one(nslot, 0, 0, j);
+        }
+#pragma unroll
+        for (int g = 0; g < NMF; ++g) {
+            const int i = g / TT, j = g % TT;
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop[1][i], xop[1][j], acc[i][j], 0, 0, 0);
+            if (SIDE < NMF) {
+                if (g < XL + WL) issue_one(g, kb + NSTAGE, slot);
+                if (g < TN) load_w_one(nslot, g);
+                else if (g < TN + TT) load_x_one(nslot, 0, 0, g - TN);
             }
+            if (g >= FIRSTV) {
+#pragma unroll
+                for (int v = (g - FIRSTV) * VPER; v < (g - FIRSTV + 1) * VPER && v < TOTAL; ++v)
+                    expand_op(0, 0, v / EOPS, v % EOPS);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // prologue: stages 0 .. NSTAGE-2 in flight
+    // prologue: stages 0 .. NSTAGE-2 in flight, then stage 0 visible and NSTAGE-1 issued
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) issue(s, s);
+    wait_loads_then_barrier<PENDING>();
+    issue(NSTAGE - 1, NSTAGE - 1);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) load_w_one(0, i);
+#pragma unroll
+    for (int j = 0; j < TT; ++j) load_x_one(0, 0, 0, j);
+    expand_all(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
 
-    // One iteration: this wave's loads for stage kb have landed; after the barrier so have everyone's,
-    // and every wave is done reading the buffer that stage kb+NSTAGE-1 is about to overwrite.
-    int kb0 = 0;
-    for (; kb0 + NSTAGE <= nkb; kb0 += NSTAGE) {
-#pragma unroll
-        for (int u = 0; u < NSTAGE; ++u) {
-            wait_loads_then_barrier<PENDING>();
-            issue(kb0 + u + NSTAGE - 1, (u + NSTAGE - 1) % NSTAGE);
-            compute(u);
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < NSTAGE - 1; ++u) {
-        if (kb0 + u < nkb) {
-            wait_loads_then_barrier<PENDING>();
-            issue(kb0 + u + NSTAGE - 1, (u + NSTAGE - 1) % NSTAGE);
-            compute(u);
-        }
+    // Stage kb sits in LDS buffer `slot`; on entry wpk holds its packed weights and (wop[0], xop[0])
+    // the operands of its K-step 0.  Before the last K-step the next stage is made visible (barrier)
+    // and this stage's buffer is handed to the copies of stage kb+NSTAGE.  The last stage runs the same
+    // code (one code path keeps the 256 accumulators in place): its "next stage" work re-reads stale
+    // data that nothing consumes.
+    using std::integral_constant;
+    int slot = 0;
+    for (int kb = 0; kb < nkb; ++kb) {
+        kstep_inner(integral_constant<int, 0>{}, slot, 1);
+        kstep_inner(integral_constant<int, 1>{}, slot, 2);
+        kstep_inner(integral_constant<int, 0>{}, slot, 3);
+        wait_loads_then_barrier<PENDING>();
+        kstep_last(kb, slot);
+        slot = slot + 1 == NSTAGE ? 0 : slot + 1;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the clamped tail loads before the LDS is released
 
@@ -226,6 +319,9 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
         }
 #pragma unroll
         for (int i = 0; i < TN; ++i) {
+            // one accumulator tile at a time: without this fence the compiler reads all TN*TT*16
+            // accumulators out of the AGPRs up front and spills
+            __builtin_amdgcn_sched_barrier(0);
             const int nb = n0 + (wn * TN + i) * 32;
             if (nb >= a.N) continue;
             if constexpr (RAW) {
@@ -242,10 +338,17 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int n = nb + 8 * g + 4 * (lane >> 5);
+                    // sum (q+off)(c+1) = sum q c + sum q + off * (sum c + K): remove the last two terms
+                    v4i corr = {sx, sx, sx, sx};
+                    if (a.code_offset != 0) {
+                        const v4i ws = *reinterpret_cast<const v4i*>(a.w_row_sum + n);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) corr[r] += a.code_offset * (ws[r] + a.K);
+                    }
                     uint32_t h[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float v = ((float)(acc[i][j][4 * g + r] - sx) * sd) * alpha;
+                        const float v = ((float)(acc[i][j][4 * g + r] - corr[r]) * sd) * alpha;
                         h[r] = f32_to_bf16_rne(v);
                     }
                     *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
@@ -272,18 +375,38 @@ int launch_cfg(GemmArgs a, hipStream_t stream) {
     return after_launch();
 }
 
+// Developer override for tile-shape experiments: HBL_GEMM_TILE=<index into the table below>.
+int tile_override() {
+    static const int v = [] {
+        const char* e = getenv("HBL_GEMM_TILE");
+        return e ? atoi(e) : -1;
+    }();
+    return v;
+}
+
 template <bool RAW>
 int choose(const GemmArgs& a, hipStream_t stream) {
     const int64_t big_tiles = (int64_t)((a.N + 255) / 256) * ((a.T + 255) / 256);
-    if (a.T <= 32) return launch_cfg<4, 1, 2, 1, 4, RAW>(a, stream);        // 256 features x 32 tokens
-    if (a.T <= 64) return launch_cfg<4, 1, 2, 2, 4, RAW>(a, stream);        // 256 x 64
-    if (big_tiles >= 200) return launch_cfg<2, 2, 4, 4, 3, RAW>(a, stream);  // 256 x 256, 4 waves
-    return launch_cfg<2, 2, 2, 2, 4, RAW>(a, stream);                        // 128 x 128
+    int cfg;
+    if (a.T <= 32) cfg = 0;
+    else if (a.T <= 64) cfg = 1;
+    else if (big_tiles >= 200) cfg = 3;
+    else cfg = 2;
+    if (tile_override() >= 0) cfg = tile_override();
+    switch (cfg) {
+        case 0: return launch_cfg<4, 1, 2, 1, 4, RAW>(a, stream);   // 256 features x 32 tokens, 4 waves
+        case 1: return launch_cfg<4, 1, 2, 2, 4, RAW>(a, stream);   // 256 x 64, 4 waves
+        case 2: return launch_cfg<2, 2, 2, 2, 4, RAW>(a, stream);   // 128 x 128, 4 waves
+        case 3: return launch_cfg<2, 2, 4, 4, 3, RAW>(a, stream);   // 256 x 256, 4 waves of 128 x 128
+        case 4: return launch_cfg<2, 4, 4, 2, 3, RAW>(a, stream);   // 256 x 256, 8 waves of 128 x 64
+        case 5: return launch_cfg<4, 2, 2, 4, 3, RAW>(a, stream);   // 256 x 256, 8 waves of 64 x 128
+        default: return HBL_E_SHAPE;
+    }
 }
 
 }  // namespace
 
-int launch_ternary_gemm(const int8_t* codes, int64_t T, int64_t K, const void* packed, int64_t N,
+int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,
                         const float* s_dequant, const int32_t* code_sum, const float* w_scales,
                         int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, hipStream_t stream) {
     if (T == 0) return HBL_OK;
@@ -292,6 +415,8 @@ int launch_ternary_gemm(const int8_t* codes, int64_t T, int64_t K, const void* p
     a.packed = static_cast<const uint32_t*>(packed);
     a.s_dequant = s_dequant;
     a.code_sum = code_sum;
+    a.w_row_sum = reinterpret_cast<const int32_t*>(static_cast<const char*>(packed) + packed_tile_bytes(N, K));
+    a.code_offset = code_offset;
     a.w_scales = w_scales;
     a.y = static_cast<uint16_t*>(y_bf16);
     a.acc_out = acc_out;

@@ -10,6 +10,7 @@
 // i.e. exactly one lane's share of a 32x32x32 int8 matrix-core operand for K-step s.
 // Weight i = 4*j + b of that group sits at bits [8*b + 2*j, 8*b + 2*j + 1] as code+1,
 // so that (dword >> 2*j) & 0x03030303 is operand register j (bytes b = 0..3).
+// After the N*K/4 bytes of tiles come N int32 row sums sum_k c[o][k].
 #include "hbl_internal.h"
 
 namespace hbl {
@@ -115,6 +116,25 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
     *reinterpret_cast<uint4*>(codes + row * K + k0) = raw;
 }
 
+// Row sums of the ternary codes, sum_k c[o][k], one wave per output row: the GEMM epilogue needs them
+// when activation codes are stored with an offset.
+__global__ __launch_bounds__(256) void row_sum_kernel(const int8_t* __restrict__ codes, int64_t N, int64_t K,
+                                                      int32_t* __restrict__ row_sum) {
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= N) return;
+    const int lane = threadIdx.x & 63;
+    int s = 0;
+    for (int64_t k = lane * 16; k < K; k += 64 * 16) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(codes + row * K + k);
+        const int8_t* c = reinterpret_cast<const int8_t*>(&raw);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += c[i];
+    }
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+    if (lane == 0) row_sum[row] = s;
+}
+
 int64_t sum_blocks(int64_t count) { return (count + kSumBlock * kSumItems - 1) / (kSumBlock * kSumItems); }
 
 }  // namespace
@@ -141,6 +161,10 @@ int launch_pack(const int8_t* codes, int64_t N, int64_t K, void* packed, hipStre
     const int64_t total = (N / 32) * (K / 128) * 256;
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
                        static_cast<uint32_t*>(packed));
+    int rc = after_launch();
+    if (rc != HBL_OK) return rc;
+    int32_t* row_sum = reinterpret_cast<int32_t*>(static_cast<char*>(packed) + packed_tile_bytes(N, K));
+    hipLaunchKernelGGL(row_sum_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, codes, N, K, row_sum);
     return after_launch();
 }
 

@@ -68,9 +68,9 @@ def lib():
         fwd = [vp, ci, i64, i64, vp, i64, vp, i64, ci, f32, vp, vp, sz, vp]
         L.hbl_hbitlinear_forward.argtypes = fwd
         L.hbl_plain_bitlinear_forward.argtypes = fwd
-        L.hbl_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, vp, vp, vp, vp]
+        L.hbl_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, ci, vp, vp, vp, vp]
         L.hbl_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp, vp]
-        L.hbl_gemm_dequant_bf16.argtypes = [vp, vp, vp, i64, i64, vp, i64, vp, i64, vp, vp]
+        L.hbl_gemm_dequant_bf16.argtypes = [vp, ci, vp, vp, i64, i64, vp, i64, vp, i64, vp, vp]
         _lib = L
     return _lib
 
@@ -119,7 +119,7 @@ def packed_bytes(N: int, K: int) -> int:
 
 
 def pack_ternary_2bit(codes: torch.Tensor) -> torch.Tensor:
-    """codes int8 [N,K] in {-1,0,1} -> opaque packed uint8 [N*K/4]."""
+    """codes int8 [N,K] in {-1,0,1} -> opaque packed uint8 [N*K/4 + 4*N]."""
     _dev_check(codes)
     N, K = codes.shape
     packed = torch.empty(packed_bytes(N, K), dtype=torch.uint8, device=codes.device)
@@ -170,15 +170,15 @@ def plain_bitlinear_forward(x: torch.Tensor, Wq_packed: torch.Tensor, N: int, w_
                     eps, y, workspace)
 
 
-def fwht_quant(x: torch.Tensor, bits: int, hadamard: bool = True, eps: float = EPS):
-    """Eq. 3-6 only -> (codes int8 [T,K], s_dequant fp32 [T], code_sum int32 [T])."""
+def fwht_quant(x: torch.Tensor, bits: int, hadamard: bool = True, eps: float = EPS, code_offset: int = 0):
+    """Eq. 3-6 only -> (codes int8 [T,K] stored as code+code_offset, s_dequant fp32 [T], code_sum int32 [T])."""
     _dev_check(x)
     T, K = x.shape
     codes = torch.empty((T, K), dtype=torch.int8, device=x.device)
     sd = torch.empty(T, dtype=torch.float32, device=x.device)
     cs = torch.empty(T, dtype=torch.int32, device=x.device)
-    _check(lib().hbl_fwht_quant(_ptr(x), _x_dtype(x), T, K, bits, eps, int(hadamard), _ptr(codes), _ptr(sd),
-                                _ptr(cs), _stream()), "fwht_quant")
+    _check(lib().hbl_fwht_quant(_ptr(x), _x_dtype(x), T, K, bits, eps, int(hadamard), code_offset, _ptr(codes),
+                                _ptr(sd), _ptr(cs), _stream()), "fwht_quant")
     return codes, sd, cs
 
 
@@ -192,20 +192,21 @@ def gemm_i32(codes: torch.Tensor, Wq_packed: torch.Tensor, N: int) -> torch.Tens
 
 
 def gemm_dequant_bf16(codes: torch.Tensor, s_dequant: torch.Tensor, code_sum: torch.Tensor, Wq_packed: torch.Tensor,
-                      N: int, w_scales: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+                      N: int, w_scales: torch.Tensor, y: Optional[torch.Tensor] = None,
+                      code_offset: int = 0) -> torch.Tensor:
     """Second launch of the forward on caller-held intermediates: y bf16 [T,N]."""
     _dev_check(codes, s_dequant, code_sum, Wq_packed, w_scales, y)
     T, K = codes.shape
     if y is None:
         y = torch.empty((T, N), dtype=torch.bfloat16, device=codes.device)
-    _check(lib().hbl_gemm_dequant_bf16(_ptr(codes), _ptr(s_dequant), _ptr(code_sum), T, K, _ptr(Wq_packed), N,
+    _check(lib().hbl_gemm_dequant_bf16(_ptr(codes), code_offset, _ptr(s_dequant), _ptr(code_sum), T, K, _ptr(Wq_packed), N,
                                        _ptr(w_scales), w_scales.numel(), _ptr(y), _stream()), "gemm_dequant_bf16")
     return y
 
 
 def fwht_quant_into(x: torch.Tensor, bits: int, hadamard: bool, codes: torch.Tensor, s_dequant: torch.Tensor,
-                    code_sum: torch.Tensor, eps: float = EPS) -> None:
+                    code_sum: torch.Tensor, eps: float = EPS, code_offset: int = 0) -> None:
     """hbl_fwht_quant into caller-held buffers (no allocation)."""
     T, K = x.shape
-    _check(lib().hbl_fwht_quant(_ptr(x), _x_dtype(x), T, K, bits, eps, int(hadamard), _ptr(codes), _ptr(s_dequant),
-                                _ptr(code_sum), _stream()), "fwht_quant")
+    _check(lib().hbl_fwht_quant(_ptr(x), _x_dtype(x), T, K, bits, eps, int(hadamard), code_offset, _ptr(codes),
+                                _ptr(s_dequant), _ptr(code_sum), _stream()), "fwht_quant")

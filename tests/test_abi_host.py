@@ -41,8 +41,8 @@ def test_status_text(L):
 
 
 def test_size_queries(L):
-    assert L.hbl_packed_bytes(4096, 16384) == 4096 * 16384 // 4
-    assert L.hbl_packed_bytes(256, 256) == 16384
+    assert L.hbl_packed_bytes(4096, 16384) == 4096 * 16384 // 4 + 4 * 4096   # 2-bit tiles + int32 row sums
+    assert L.hbl_packed_bytes(256, 256) == 16384 + 1024
     ws = L.hbl_workspace_bytes(8192, 16384, 4096, 4)
     assert ws >= 8192 * 16384 + 8 * 8192 and ws % 256 == 0
     assert L.hbl_workspace_bytes(17, 256, 256, 8) >= 17 * 256 + 8 * 17
@@ -80,8 +80,9 @@ def test_argument_errors_before_any_launch(L):
     assert fwd(wsb=100) == hbl.E_WORKSPACE
     assert fwd(T=0, x=NUL, y=NUL) == hbl.OK              # empty batch is a no-op
     assert fwd(fn=L.hbl_plain_bitlinear_forward, K=384, wsb=100) == hbl.E_WORKSPACE   # K=384 is fine without Hadamard
-    assert L.hbl_fwht_quant(P, hbl.BF16, 4, 256, 3, 1e-5, 1, P, P, P, None) == hbl.E_BITS
-    assert L.hbl_fwht_quant(NUL, hbl.BF16, 4, 256, 4, 1e-5, 1, P, P, P, None) == hbl.E_NULL
+    assert L.hbl_fwht_quant(P, hbl.BF16, 4, 256, 3, 1e-5, 1, 0, P, P, P, None) == hbl.E_BITS
+    assert L.hbl_fwht_quant(P, hbl.BF16, 4, 256, 8, 1e-5, 1, 8, P, P, P, None) == hbl.E_BITS   # offset 8 is INT4 only
+    assert L.hbl_fwht_quant(NUL, hbl.BF16, 4, 256, 4, 1e-5, 1, 0, P, P, P, None) == hbl.E_NULL
     assert L.hbl_gemm_i32(P, 4, 100, P, 64, P, None) == hbl.E_SHAPE
     assert L.hbl_pack_ternary_2bit(P, 33, 256, P, None) == hbl.E_SHAPE
     assert L.hbl_pack_ternary_2bit(NUL, 32, 256, P, None) == hbl.E_NULL

@@ -117,7 +117,9 @@ def test_ternarize_and_pack_roundtrip(hbl, N, K):
     assert a_dev.cpu().numpy()[0] == a_ref
     assert np.array_equal(c_dev.cpu().numpy(), c_ref)
     packed = hbl.pack_ternary_2bit(c_dev)
-    assert packed.numel() == N * K // 4
+    assert packed.numel() == N * K // 4 + 4 * N
+    row_sums = packed[N * K // 4:].view(torch.int32).cpu().numpy()
+    assert np.array_equal(row_sums, c_ref.astype(np.int32).sum(1))
     back = hbl.unpack_ternary_2bit(packed, N, K)
     assert np.array_equal(back.cpu().numpy(), c_ref)
 
@@ -176,6 +178,36 @@ def test_fwht_quant_parity(hbl, K, bits, hadamard):
         rate = check_codes(codes.cpu().numpy(), c_ref)
         assert rate == 0.0
         assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
+
+
+@pytest.mark.parametrize("K,hadamard", [(256, True), (4096, True), (16384, True), (640, False)])
+def test_int4_offset_codes_and_split_calls(hbl, K, hadamard):
+    """The forward calls carry INT4 codes as code+8 (bytes 0..15); the stage-level calls expose that form.
+    Stored bytes must be oracle code + 8, the code sum the true sum, and the two-launch split must
+    reproduce the single call bit for bit."""
+    note(f"int4 offset codes K={K} hadamard={hadamard}")
+    site = synth.Site("a", 45, K, 96, hadamard=hadamard, outlier_frac=0.01, outlier_scale=30.0, seed=K + 1)
+    x = synth.make_x(site)
+    c_ref, s_ref = O.fwht_quant(x, 4, hadamard=hadamard, eps=EPS)
+    xd = dev_x(x)
+    codes, sd, cs = hbl.fwht_quant(xd, 4, hadamard, EPS, code_offset=8)
+    got = codes.cpu().numpy()
+    assert got.min() >= 0 and got.max() <= 15
+    assert np.array_equal(got, c_ref + 8)
+    assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
+    assert np.array_equal(sd.cpu().numpy(), s_ref)
+    wc_ref, al_ref, wc_d, al_d, packed = setup_weights(hbl, site)
+    y_split = hbl.gemm_dequant_bf16(codes, sd, cs, packed, site.N, al_d, code_offset=8)
+    codes0, sd0, cs0 = hbl.fwht_quant(xd, 4, hadamard, EPS, code_offset=0)
+    y_split0 = hbl.gemm_dequant_bf16(codes0, sd0, cs0, packed, site.N, al_d, code_offset=0)
+    fn = hbl.hbitlinear_forward if hadamard else hbl.plain_bitlinear_forward
+    y_one = fn(xd, packed, site.N, al_d, 4, EPS)
+    y_ref = O.bitlinear_forward(x, wc_ref, al_ref, 4, hadamard, EPS)
+    assert np.array_equal(host_bf16_bits(y_split), host_bf16_bits(y_one))
+    assert np.array_equal(host_bf16_bits(y_split0), host_bf16_bits(y_one))
+    assert np.array_equal(host_bf16_bits(y_one), y_ref)
+    with pytest.raises(hbl.HblError):
+        hbl.fwht_quant(xd, 8, hadamard, EPS, code_offset=8)
 
 
 @pytest.mark.parametrize("K", [384, 1536, 11008 // 128 * 128])
