@@ -169,19 +169,39 @@ def bench_decode(args, hbl, synth, torch, np):
         for l in range(layers):
             layer(l)
         torch.cuda.synchronize()
-        reps = 3
+        # one HIP graph of all layers (8 kernel nodes per layer, no memset nodes), replayed
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for l in range(layers):
+                    layer(l)
+        torch.cuda.synchronize()
+        y_eager = [y.clone() for y in ys]
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(y_eager, ys)), \
+            "graph replay differs from eager"
+        reps = 5
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(reps):
-            for l in range(layers):
-                layer(l)
+            graph.replay()
         e1.record()
         torch.cuda.synchronize()
         us_layer = e0.elapsed_time(e1) * 1e3 / (reps * layers)
+        e0.record()
+        for l in range(layers):
+            layer(l)
+        e1.record()
+        torch.cuda.synchronize()
+        us_layer_eager = e0.elapsed_time(e1) * 1e3 / layers
         io_bytes = sum(2 * B * s.K + 2 * B * s.N for s in sites)
         gbs = (w_bytes + io_bytes) / (us_layer * 1e-6) / 1e9
-        res[str(B)] = {"us_per_layer": us_layer, "GBps": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS}
-    return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes, "launch": "eager, 8 launches per layer",
+        res[str(B)] = {"us_per_layer": us_layer, "us_per_layer_eager": us_layer_eager, "GBps": gbs,
+                       "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+    return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes, "launch": "one HIP graph of all layers, 8 kernel nodes per layer (4 projections x [quantiser, GEMM])",
             "batch": res}
 
 

@@ -1,9 +1,20 @@
 // C-ABI entry points of libhbitlinear: argument validation and kernel sequencing only.
+#include <stdlib.h>
+
 #include "hbl_internal.h"
 
 namespace hbl {
 
 static thread_local int g_last_hip_error = 0;
+
+int decode_wg_target() {
+    static const int v = [] {
+        const char* e = getenv("HBL_DECODE_WGS");
+        const int t = e ? atoi(e) : 192;
+        return t > 0 ? t : 192;
+    }();
+    return v;
+}
 
 int note_hip_error(hipError_t e) {
     g_last_hip_error = (int)e;
@@ -36,13 +47,13 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
         return HBL_E_ALIGN;
     if (workspace_bytes < hbl_workspace_bytes(T, K, N, bits)) return HBL_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const Workspace ws = carve_workspace(workspace, T, K);
+    const Workspace ws = carve_workspace(workspace, T, K, N);
     // INT4 codes travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs
     const int code_offset = bits == 4 ? 8 : 0;
     rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, code_offset, s);
     if (rc != HBL_OK) return rc;
     return launch_ternary_gemm(ws.codes, code_offset, T, K, Wq_packed, N, ws.s_dequant, ws.code_sum, w_scales, groups,
-                               y, nullptr, s);
+                               y, nullptr, ws.partial, s);
 }
 
 }  // namespace
@@ -104,10 +115,9 @@ int hbl_unpack_ternary_2bit(const void* packed, int64_t N, int64_t K, int8_t* co
 }
 
 size_t hbl_workspace_bytes(int64_t T, int64_t K, int64_t N, int bits) {
-    (void)N;
     (void)bits;
     if (T <= 0 || K <= 0) return 256;
-    return carve_workspace(nullptr, T, K).bytes;
+    return carve_workspace(nullptr, T, K, N).bytes;
 }
 
 int hbl_hbitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
@@ -146,7 +156,7 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
     if (!codes || !Wq_packed || !acc) return HBL_E_NULL;
     if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(acc)) return HBL_E_ALIGN;
     return launch_ternary_gemm(codes, 0, T, K, Wq_packed, N, nullptr, nullptr, nullptr, 1, nullptr, acc,
-                               static_cast<hipStream_t>(stream));
+                               nullptr, static_cast<hipStream_t>(stream));
 }
 
 int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_dequant, const int32_t* code_sum,
@@ -160,7 +170,7 @@ int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_d
     if (!codes || !s_dequant || !code_sum || !Wq_packed || !w_scales || !y) return HBL_E_NULL;
     if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(y)) return HBL_E_ALIGN;
     return launch_ternary_gemm(codes, code_offset, T, K, Wq_packed, N, s_dequant, code_sum, w_scales,
-                               n_scale_groups, y, nullptr, static_cast<hipStream_t>(stream));
+                               n_scale_groups, y, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

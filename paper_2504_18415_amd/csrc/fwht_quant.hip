@@ -17,6 +17,8 @@
 // so that every global access is one contiguous CH-element piece per lane and
 // the stage order e -> lane -> r -> wave is ascending.  The wave stages swap
 // the wave bits with the low r bits through LDS once, then run in registers.
+#include <atomic>
+
 #include "hbl_internal.h"
 
 namespace hbl {
@@ -294,10 +296,12 @@ int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_
     constexpr int K = 1 << LOG2K;
     const size_t lds = (HADAMARD && W > 1) ? sizeof(float) * K : 0;
     auto kern = fwht_quant_kernel<LOG2K, W, BITS, BF16, HADAMARD>;
-    if (lds > 48 * 1024) {
+    static std::atomic<bool> attr_set{false};   // once per process (one device)
+    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return note_hip_error(e);
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, eps, code_offset);
     return after_launch();

@@ -21,14 +21,28 @@ inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Layout of the forward workspace: int8 codes [T,K] | float s_dequant [T] | int32 code_sum [T].
+// Split-K factor of the small-T (decode) GEMM: split K only until there are enough workgroups (128
+// output rows each) to occupy the chip, and never below 4 K-blocks of 128 per workgroup.  Every
+// split costs a second launch (the reduction) and T*N*4 bytes of partials per slice.
+int decode_wg_target();   // HBL_DECODE_WGS developer override, default 192
+inline int decode_split_k(int64_t T, int64_t K, int64_t N) {
+    if (T > 64 || T <= 0) return 1;
+    const int64_t nkb = K / 128, groups = (N + 127) / 128;
+    int sk = 1;
+    while ((int64_t)sk * groups < decode_wg_target() && nkb % (sk * 2) == 0 && nkb / (sk * 2) >= 4) sk *= 2;
+    return sk;
+}
+
+// Layout of the forward workspace: int8 codes [T,K] | float s_dequant [T] | int32 code_sum [T], and for
+// T <= 64: | int32 partial [split_k][T][N].
 struct Workspace {
     int8_t* codes;
     float* s_dequant;
     int32_t* code_sum;
+    int32_t* partial;
     size_t bytes;
 };
-inline Workspace carve_workspace(void* base, int64_t T, int64_t K) {
+inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
     Workspace w;
     size_t off = 0;
     w.codes = reinterpret_cast<int8_t*>(static_cast<char*>(base) + off);
@@ -37,6 +51,11 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K) {
     off += round_up(static_cast<size_t>(T) * sizeof(float), 256);
     w.code_sum = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
     off += round_up(static_cast<size_t>(T) * sizeof(int32_t), 256);
+    w.partial = nullptr;
+    if (T <= 64) {
+        w.partial = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
+        off += round_up(static_cast<size_t>(decode_split_k(T, K, N)) * T * N * sizeof(int32_t), 256);
+    }
     w.bytes = off;
     return w;
 }
@@ -50,7 +69,8 @@ int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits
 // (no scales, no code_sum needed); otherwise y (bf16) is written.
 int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,
                         const float* s_dequant, const int32_t* code_sum, const float* w_scales,
-                        int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, hipStream_t stream);
+                        int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, int32_t* splitk_partial,
+                        hipStream_t stream);
 
 // Packed weight buffer: N*K/4 bytes of 2-bit tiles, then N int32 row sums of the ternary codes.
 inline size_t packed_tile_bytes(int64_t N, int64_t K) { return (size_t)N * (size_t)K / 4; }

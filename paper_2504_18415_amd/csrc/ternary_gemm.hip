@@ -14,6 +14,7 @@
 // loads, NSTAGE deep: codes into an XOR-swizzled [token][128 B] layout, weights tile by tile.
 #include <stdlib.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "hbl_internal.h"
@@ -84,11 +85,36 @@ struct GemmArgs {
     int T, K, N;
     int rows_per_group;
     int tiles_n, tiles_t;
+    // split-K (small T only): workgroup (tile, ks) covers K-blocks [ks*nkb/split_k, (ks+1)*nkb/split_k)
+    // and writes its int32 partial tile to partial[ks][T][N]; splitk_reduce_kernel finishes the job
+    int split_k;
+    int32_t* partial;
 };
+
+typedef int v4i_ __attribute__((ext_vector_type(4)));
+
+// Outer factors of Eq. 1 and Eq. 5/6 on four consecutive output features of one token:
+// y = bf16(((float)(acc - corr) * s_d) * alpha), corr = sum_k q + code_offset * (sum_k c + K).
+__device__ __forceinline__ uint2 dequant_quad(v4i_ acc, int sx, float sd, float alpha, int code_offset,
+                                              const int32_t* w_row_sum, int K) {
+    v4i_ corr = {sx, sx, sx, sx};
+    if (code_offset != 0) {
+        const v4i_ ws = *reinterpret_cast<const v4i_*>(w_row_sum);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) corr[r] += code_offset * (ws[r] + K);
+    }
+    uint32_t h[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float v = ((float)(acc[r] - corr[r]) * sd) * alpha;
+        h[r] = f32_to_bf16_rne(v);
+    }
+    return make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+}
 
 // WAVES_N x WAVES_T waves; each wave owns TN x TT MFMA tiles (32 features x 32 tokens each).
 // LDS stage = [BT tokens x 128 B codes, XOR-swizzled][BN/32 packed weight tiles x 1 KiB].
-template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW>
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT>
 __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(const GemmArgs a) {
     constexpr int NW = WAVES_N * WAVES_T;
     constexpr int BN = WAVES_N * TN * 32;
@@ -117,13 +143,21 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
     // Workgroups are dealt round-robin over the 8 XCDs; give each XCD a contiguous run of tiles
     // (feature tile fastest) so that the workgroups sharing an activation panel share an L2.
     int wg = blockIdx.x;
+    int ks = 0;
     const int nwg = a.tiles_n * a.tiles_t;
-    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
+    if constexpr (SPLIT) {
+        ks = wg % a.split_k;
+        wg = wg / a.split_k;
+    } else {
+        if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
+    }
     const int tile_n = wg % a.tiles_n;
     const int tile_t = wg / a.tiles_n;
     const int n0 = tile_n * BN;
     const int t0 = tile_t * BT;
-    const int nkb = a.K / kBK;
+    const int nkb_total = a.K / kBK;
+    const int nkb = SPLIT ? nkb_total / a.split_k : nkb_total;   // K-blocks of this workgroup
+    const int kb_first = ks * nkb;
 
     // Global -> LDS copies: wave-uniform 64-bit base (SGPR pair) + 32-bit per-lane offset, so that
     // advancing along K is scalar arithmetic only.
@@ -135,12 +169,12 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
         int nt = n0 / 32 + wave + NW * m;
         const int nt_max = a.N / 32 - 1;
         nt = nt < nt_max ? nt : nt_max;
-        wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb) * 1024;
+        wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb_total + kb_first) * 1024;
     }
     const uint32_t wlane = lane * 16;
     // activation codes: instruction q covers tokens 8q..8q+7, lane l -> token 8q + l/8, LDS slot l%8,
     // global 16-byte chunk (l%8) ^ (token % 8); rows past T are clamped to the last row
-    const char* xbase = reinterpret_cast<const char*>(a.codes) + (size_t)t0 * a.K;
+    const char* xbase = reinterpret_cast<const char*>(a.codes) + (size_t)t0 * a.K + (size_t)kb_first * kBK;
     uint32_t xlane[XL];
 #pragma unroll
     for (int m = 0; m < XL; ++m) {
@@ -307,6 +341,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the clamped tail loads before the LDS is released
 
     // epilogue: lane holds token t = ..+(lane&31); register quad g holds features 8g + 4*(lane>>5) + 0..3
+    const bool write_partial = SPLIT && a.split_k > 1;
 #pragma unroll
     for (int j = 0; j < TT; ++j) {
         const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
@@ -324,54 +359,69 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
             __builtin_amdgcn_sched_barrier(0);
             const int nb = n0 + (wn * TN + i) * 32;
             if (nb >= a.N) continue;
-            if constexpr (RAW) {
+            float alpha = 0.0f;
+            if constexpr (!RAW) alpha = a.w_scales[nb / a.rows_per_group];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nb + 8 * g + 4 * (lane >> 5);
-                    v4i o;
+            for (int g = 0; g < 4; ++g) {
+                const int n = nb + 8 * g + 4 * (lane >> 5);
+                v4i o;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = acc[i][j][4 * g + r];
+                for (int r = 0; r < 4; ++r) o[r] = acc[i][j][4 * g + r];
+                if constexpr (RAW) {
                     *reinterpret_cast<v4i*>(a.acc_out + (size_t)t * a.N + n) = o;
-                }
-            } else {
-                const float alpha = a.w_scales[nb / a.rows_per_group];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = nb + 8 * g + 4 * (lane >> 5);
-                    // sum (q+off)(c+1) = sum q c + sum q + off * (sum c + K): remove the last two terms
-                    v4i corr = {sx, sx, sx, sx};
-                    if (a.code_offset != 0) {
-                        const v4i ws = *reinterpret_cast<const v4i*>(a.w_row_sum + n);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) corr[r] += a.code_offset * (ws[r] + a.K);
-                    }
-                    uint32_t h[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float v = ((float)(acc[i][j][4 * g + r] - corr[r]) * sd) * alpha;
-                        h[r] = f32_to_bf16_rne(v);
-                    }
-                    *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                } else if (write_partial) {
+                    *reinterpret_cast<v4i*>(a.partial + ((size_t)ks * a.T + t) * a.N + n) = o;
+                } else {
+                    *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) =
+                        dequant_quad(o, sx, sd, alpha, a.code_offset, a.w_row_sum + n, a.K);
                 }
             }
         }
     }
 }
 
-template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW>
+// Second half of the split-K path: y[t][n..n+3] from the split_k int32 partial tiles, summed in fixed
+// order (integer, so exact) and passed through the same dequantising epilogue.  A separate launch: the
+// kernel boundary is what makes the partials of workgroups on other XCDs visible.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs a) {
+    const int quads = a.N / 4;
+    const int64_t total = (int64_t)a.T * quads;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+        const int t = (int)(idx / quads);
+        const int n = (int)(idx % quads) * 4;
+        v4i sum = {0, 0, 0, 0};
+        for (int k = 0; k < a.split_k; ++k)
+            sum += *reinterpret_cast<const v4i*>(a.partial + ((size_t)k * a.T + t) * a.N + n);
+        *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) =
+            dequant_quad(sum, a.code_sum[t], a.s_dequant[t], a.w_scales[n / a.rows_per_group], a.code_offset,
+                         a.w_row_sum + n, a.K);
+    }
+}
+
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT = false>
 int launch_cfg(GemmArgs a, hipStream_t stream) {
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int BT = WAVES_T * TT * 32;
     constexpr size_t lds = (size_t)NSTAGE * (BT * kBK + (BN / 32) * 1024);
     a.tiles_n = (a.N + BN - 1) / BN;
     a.tiles_t = (a.T + BT - 1) / BT;
-    auto kern = ternary_gemm_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, RAW>;
-    if (lds > 48 * 1024) {
+    if (!SPLIT) a.split_k = 1;
+    auto kern = ternary_gemm_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, RAW, SPLIT>;
+    static std::atomic<bool> attr_set{false};   // once per process (one device)
+    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return note_hip_error(e);
+        attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t)), dim3(64 * WAVES_N * WAVES_T), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t * a.split_k)), dim3(64 * WAVES_N * WAVES_T), lds,
+                       stream, a);
+    int rc = after_launch();
+    if (rc != HBL_OK || !SPLIT || a.split_k == 1) return rc;
+    const int64_t quads = (int64_t)a.T * (a.N / 4);
+    int64_t blocks = (quads + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
     return after_launch();
 }
 
@@ -388,11 +438,12 @@ template <bool RAW>
 int choose(const GemmArgs& a, hipStream_t stream) {
     const int64_t big_tiles = (int64_t)((a.N + 255) / 256) * ((a.T + 255) / 256);
     int cfg;
-    if (a.T <= 32) cfg = 0;
+    if (a.T <= 64 && a.partial != nullptr && !RAW) cfg = a.T <= 32 ? 6 : 7;
+    else if (a.T <= 32) cfg = 0;
     else if (a.T <= 64) cfg = 1;
     else if (big_tiles >= 200) cfg = 3;
     else cfg = 2;
-    if (tile_override() >= 0) cfg = tile_override();
+    if (tile_override() >= 0 && cfg < 6) cfg = tile_override();
     switch (cfg) {
         case 0: return launch_cfg<4, 1, 2, 1, 4, RAW>(a, stream);   // 256 features x 32 tokens, 4 waves
         case 1: return launch_cfg<4, 1, 2, 2, 4, RAW>(a, stream);   // 256 x 64, 4 waves
@@ -400,6 +451,8 @@ int choose(const GemmArgs& a, hipStream_t stream) {
         case 3: return launch_cfg<2, 2, 4, 4, 3, RAW>(a, stream);   // 256 x 256, 4 waves of 128 x 128
         case 4: return launch_cfg<2, 4, 4, 2, 3, RAW>(a, stream);   // 256 x 256, 8 waves of 128 x 64
         case 5: return launch_cfg<4, 2, 2, 4, 3, RAW>(a, stream);   // 256 x 256, 8 waves of 64 x 128
+        case 6: if constexpr (!RAW) return launch_cfg<4, 1, 1, 1, 4, false, true>(a, stream);   // 128 x 32, split-K
+        case 7: if constexpr (!RAW) return launch_cfg<4, 1, 1, 2, 4, false, true>(a, stream);   // 128 x 64, split-K
         default: return HBL_E_SHAPE;
     }
 }
@@ -408,7 +461,8 @@ int choose(const GemmArgs& a, hipStream_t stream) {
 
 int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,
                         const float* s_dequant, const int32_t* code_sum, const float* w_scales,
-                        int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, hipStream_t stream) {
+                        int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, int32_t* splitk_partial,
+                        hipStream_t stream) {
     if (T == 0) return HBL_OK;
     GemmArgs a;
     a.codes = codes;
@@ -425,6 +479,8 @@ int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t
     a.N = (int)N;
     a.rows_per_group = n_scale_groups > 0 ? (int)(N / n_scale_groups) : (int)N;
     a.tiles_n = a.tiles_t = 0;
+    a.split_k = splitk_partial ? decode_split_k(T, K, N) : 1;
+    a.partial = splitk_partial;
     return acc_out ? choose<true>(a, stream) : choose<false>(a, stream);
 }
 

@@ -332,6 +332,20 @@ def test_config4_full_size_sampled(hbl, idx):
     run_site(hbl, site, 4, sample_rows=rows)
 
 
+@pytest.mark.parametrize("T,K,N,groups,bits,hadamard", [
+    (1, 512, 32, 1, 4, True), (7, 2048, 96, 3, 4, False), (33, 4096, 544, 1, 8, True), (64, 1024, 160, 1, 4, True),
+    (17, 8192, 288, 1, 4, True), (64, 640, 96, 1, 8, False), (5, 16384, 64, 2, 4, True),
+])
+def test_small_batch_split_k_path(hbl, T, K, N, groups, bits, hadamard):
+    """T <= 64 takes the split-K kernel pair (partial tiles + reduction): ragged T, N not a multiple of the
+    128-row workgroup tile, several scale groups, both code widths."""
+    note(f"split-K T={T} K={K} N={N} groups={groups} bits={bits} hadamard={hadamard}")
+    site = synth.Site("s", T, K, N, hadamard=hadamard, groups=groups, outlier_frac=0.01, outlier_scale=30.0,
+                      seed=T + K + N)
+    rate, exact = run_site(hbl, site, bits)
+    assert rate == 0 and exact == 1.0
+
+
 @pytest.mark.parametrize("batch", [1, 8, 32, 64])
 def test_config5_decode_layer(hbl, batch):
     note(f"config 5 batch={batch}")
