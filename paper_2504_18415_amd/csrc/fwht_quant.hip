@@ -17,6 +17,8 @@
 // so that every global access is one contiguous CH-element piece per lane and
 // the stage order e -> lane -> r -> wave is ascending.  The wave stages swap
 // the wave bits with the low r bits through LDS once, then run in registers.
+#include <stdlib.h>
+
 #include <atomic>
 
 #include "hbl_internal.h"
@@ -406,6 +408,259 @@ int launch_generic(const void* x, int x_dtype, int64_t T, int64_t K, int bits, f
     return after_launch();
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Large rows (K = 4096, 8192, 16384): every butterfly stage runs in registers.
+//
+// A thread holds 64 values = 16 float4 "chunks"; a chunk is 4 consecutive elements (index bits 0-1)
+// and the chunk number j carries four more index bits.  Three layouts follow one another, each putting
+// the next four index bits into j; between them the row is exchanged through LDS (one float per
+// element, 16-byte accesses, XOR-swizzled so that both sides are conflict free):
+//   layout A: j = index bits 2-5,   thread = bits 6..m-1   stages 0-5   (64 contiguous elements / thread)
+//   layout B: j = index bits 6-9,   thread = bits 2-5,10..  stages 6-9
+//   layout C: j = index bits 10..   (+ finished low bits when m < 14)   stages 10..m-1
+// Stage order stays ascending, so every value equals the one the reference order produces.
+// In float4 units (q = index >> 2) every layout is q = q_t(thread) ^ q_j(j) with disjoint bit sets,
+// and the swizzle q ^ ((q >> 4) & 15) is linear over xor: an LDS address is one xor of a per-thread
+// base with a compile-time constant.
+template <int LOG2K, int LAYOUT>
+struct BigRowLayout {
+    static constexpr int M = LOG2K;
+    __host__ __device__ static constexpr uint32_t qj(int j) {
+        if (LAYOUT == 0) return (uint32_t)j;
+        if (LAYOUT == 1) return (uint32_t)j << 4;
+        if (M == 14) return (uint32_t)j << 8;
+        if (M == 13) return ((uint32_t)(j & 7) << 8) | (uint32_t)(j >> 3);
+        return ((uint32_t)(j & 3) << 8) | (uint32_t)(j >> 2);   // M == 12
+    }
+    __device__ static uint32_t qt(uint32_t tid) {
+        if (LAYOUT == 0) return tid << 4;
+        if (LAYOUT == 1) return (tid & 15u) | ((tid >> 4) << 8);
+        if (M == 14) return tid;
+        if (M == 13) return tid << 1;
+        return tid << 2;
+    }
+    // number of chunk bits that are unfinished index bits in this layout (stages to run on j)
+    static constexpr int stages() { return LAYOUT < 2 ? 4 : M - 10; }
+};
+__host__ __device__ constexpr uint32_t swz16(uint32_t q) { return q ^ ((q >> 4) & 15u); }
+
+template <int LOG2K, int BITS, bool BF16>
+__global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
+    const void* __restrict__ x, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
+    int32_t* __restrict__ code_sum, float eps, int code_offset) {
+    constexpr int K = 1 << LOG2K;
+    constexpr int NT = K / 64;
+    constexpr int W = NT / 64;
+    using LA = BigRowLayout<LOG2K, 0>;
+    using LB = BigRowLayout<LOG2K, 1>;
+    using LC = BigRowLayout<LOG2K, 2>;
+    extern __shared__ __attribute__((aligned(16))) float row_lds[];   // K floats
+    __shared__ double red_d[W];
+    __shared__ float red_f[W];
+    __shared__ int red_i[W];
+
+    const uint32_t tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int64_t row = blockIdx.x;
+    const int64_t row_off = row * (int64_t)K;
+
+    float v[16][4];
+    // layout A: 64 contiguous elements per thread
+    if constexpr (BF16) {
+        const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(x) + row_off + tid * 64);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint4 raw = src[i];
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                v[2 * i + h / 2][2 * (h % 2)] = as_f(w[h] << 16);
+                v[2 * i + h / 2][2 * (h % 2) + 1] = as_f(w[h] & 0xFFFF0000u);
+            }
+        }
+    } else {
+        const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(x) + row_off + tid * 64);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float4 raw = src[j];
+            v[j][0] = raw.x; v[j][1] = raw.y; v[j][2] = raw.z; v[j][3] = raw.w;
+        }
+    }
+
+    auto stages_e = [&]() {   // index bits 0, 1: inside a chunk
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float a0 = v[j][0] + v[j][1], a1 = v[j][0] - v[j][1];
+            const float a2 = v[j][2] + v[j][3], a3 = v[j][2] - v[j][3];
+            v[j][0] = a0 + a2; v[j][2] = a0 - a2;
+            v[j][1] = a1 + a3; v[j][3] = a1 - a3;
+        }
+    };
+    auto stages_j = [&](int nstages) {   // the low `nstages` bits of the chunk number, ascending
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            if (b >= nstages) break;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (!(j & (1 << b))) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float a = v[j][e], c = v[j | (1 << b)][e];
+                        v[j][e] = a + c;
+                        v[j | (1 << b)][e] = a - c;
+                    }
+                }
+        }
+    };
+    auto lds_write = [&](auto layout_tag) {
+        using L = decltype(layout_tag);
+        const uint32_t base = swz16(L::qt(tid)) << 4;   // bytes
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            constexpr uint32_t dummy = 0;
+            (void)dummy;
+            float4* dst = reinterpret_cast<float4*>(reinterpret_cast<char*>(row_lds) + (base ^ (swz16(L::qj(j)) << 4)));
+            *dst = make_float4(v[j][0], v[j][1], v[j][2], v[j][3]);
+        }
+    };
+    auto lds_read = [&](auto layout_tag) {
+        using L = decltype(layout_tag);
+        const uint32_t base = swz16(L::qt(tid)) << 4;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float4 t = *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(row_lds) +
+                                                              (base ^ (swz16(L::qj(j)) << 4)));
+            v[j][0] = t.x; v[j][1] = t.y; v[j][2] = t.z; v[j][3] = t.w;
+        }
+    };
+
+    stages_e();
+    stages_j(4);              // index bits 2-5
+    lds_write(LA{});
+    __syncthreads();
+    lds_read(LB{});
+    stages_j(4);              // index bits 6-9
+    __syncthreads();          // everyone has read before the buffer is rewritten
+    lds_write(LB{});
+    __syncthreads();
+    lds_read(LC{});
+    stages_j(LC::stages());   // index bits 10..m-1
+
+    // c_n = (float)(1/sqrt(K)).  For even log2 K it is a power of two: scaling by it commutes exactly
+    // with every later rounding (max, fp64 sum, the gain product), so it is applied to the row
+    // statistics and folded into the gain instead of costing one multiply per element.
+    const float c_n = (float)(1.0 / sqrt((double)K));
+    constexpr bool FOLD = (LOG2K % 2) == 0;
+    if constexpr (!FOLD) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[j][e] = v[j][e] * c_n;
+    }
+
+    float gain, s_d;
+    if constexpr (BITS == 8) {
+        float m = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) m = fmaxf(m, fabsf(v[j][e]));
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+        if constexpr (W > 1) {
+            if (lane == 0) red_f[wave] = m;
+            __syncthreads();
+            m = red_f[0];
+#pragma unroll
+            for (int w = 1; w < W; ++w) m = fmaxf(m, red_f[w]);
+        }
+        if constexpr (FOLD) m = m * c_n;
+        gain = 127.0f / (m + eps);
+        s_d = m / 127.0f;
+    } else {
+        double s = 0.0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s += (double)fabsf(v[j][e]);
+#pragma unroll
+        for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+        if constexpr (W > 1) {
+            if (lane == 0) red_d[wave] = s;
+            __syncthreads();
+            s = red_d[0];
+#pragma unroll
+            for (int w = 1; w < W; ++w) s += red_d[w];
+        }
+        if constexpr (FOLD) s = s * (double)c_n;
+        const float beta = (float)(s / (double)K);
+        gain = kRoot7 / (beta + eps);
+        s_d = beta / kRoot7;
+    }
+
+    constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
+    constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
+    const float magic = kMagic + (float)code_offset;
+    if constexpr (FOLD) gain = gain * c_n;
+    int isum = 0;
+    int8_t* out = codes + row_off + (LC::qt(tid) << 2);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        uint32_t packed = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float t = __builtin_amdgcn_fmed3f(v[j][e] * gain, lo, hi);
+            const uint32_t bits = as_u(t + magic);
+            packed |= (bits & 0xFFu) << (8 * e);
+        }
+        isum = __builtin_amdgcn_sdot4((int)packed, 0x01010101, isum, false);   // += the 4 stored bytes
+        *reinterpret_cast<uint32_t*>(out + (LC::qj(j) << 2)) = packed;
+    }
+    isum -= 64 * code_offset;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
+    if constexpr (W > 1) {
+        if (lane == 0) red_i[wave] = isum;
+        __syncthreads();
+        isum = 0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) isum += red_i[w];
+    }
+    if (tid == 0) {
+        s_dequant[row] = s_d;
+        if (code_sum) code_sum[row] = isum;
+    }
+}
+
+template <int LOG2K, int BITS, bool BF16>
+int launch_bigrow(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, float eps,
+                  int code_offset, hipStream_t stream) {
+    constexpr int K = 1 << LOG2K;
+    constexpr size_t lds = sizeof(float) * K;
+    auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16>;
+    static std::atomic<bool> attr_set{false};   // once per process (one device)
+    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return note_hip_error(e);
+        attr_set.store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(K / 64), lds, stream, x, codes, s_dequant, code_sum, eps,
+                       code_offset);
+    return after_launch();
+}
+
+template <int LOG2K>
+int dispatch_bigrow(const void* x, int x_dtype, int64_t T, int bits, float eps, int8_t* codes, float* s_dequant,
+                    int32_t* code_sum, int code_offset, hipStream_t stream) {
+    const bool bf = x_dtype == HBL_BF16;
+    if (bits == 8) return bf ? launch_bigrow<LOG2K, 8, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
+                             : launch_bigrow<LOG2K, 8, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
+    return bf ? launch_bigrow<LOG2K, 4, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
+              : launch_bigrow<LOG2K, 4, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
+}
+
 template <int LOG2K, int W>
 int dispatch(const void* x, int x_dtype, int64_t T, int bits, float eps, bool hadamard, int8_t* codes,
              float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
@@ -428,6 +683,11 @@ int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     if (T == 0) return HBL_OK;
     if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
+    if (hadamard && !getenv("HBL_FWHT_OLD")) {
+        if (K == 4096) return dispatch_bigrow<12>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
+        if (K == 8192) return dispatch_bigrow<13>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
+        if (K == 16384) return dispatch_bigrow<14>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
+    }
     switch (K) {
         case 128:   return dispatch<7, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
         case 256:   return dispatch<8, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
