@@ -103,19 +103,22 @@ __device__ __forceinline__ uint2 dequant_quad(v4i_ acc, int sx, float sd, float 
 #pragma unroll
         for (int r = 0; r < 4; ++r) corr[r] += code_offset * (ws[r] + K);
     }
-    uint32_t h[4];
+    float v[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const float v = ((float)(acc[r] - corr[r]) * sd) * alpha;
-        h[r] = f32_to_bf16_rne(v);
-    }
-    return make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+    for (int r = 0; r < 4; ++r) v[r] = ((float)(acc[r] - corr[r]) * sd) * alpha;
+    // v_cvt_pk_bf16_f32: round to nearest even, two values per instruction
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 lo = __builtin_convertvector((f32x2){v[0], v[1]}, bf16x2);
+    const bf16x2 hi = __builtin_convertvector((f32x2){v[2], v[3]}, bf16x2);
+    return make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
 }
 
 // WAVES_N x WAVES_T waves; each wave owns TN x TT MFMA tiles (32 features x 32 tokens each).
 // LDS stage = [BT tokens x 128 B codes, XOR-swizzled][BN/32 packed weight tiles x 1 KiB].
-template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT>
-__global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(const GemmArgs a) {
+// OCC = waves per SIMD the register budget must allow (2: two workgroups of 4 waves share a CU).
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT, int OCC>
+__global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kernel(const GemmArgs a) {
     constexpr int NW = WAVES_N * WAVES_T;
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int BT = WAVES_T * TT * 32;
@@ -173,7 +176,8 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
     }
     const uint32_t wlane = lane * 16;
     // activation codes: instruction q covers tokens 8q..8q+7, lane l -> token 8q + l/8, LDS slot l%8,
-    // global 16-byte chunk (l%8) ^ (token % 8); rows past T are clamped to the last row
+    // global 16-byte chunk (l%8) ^ ((token/2) % 8); rows past T are clamped to the last row.
+    // (rows are 128 B = half of the 64 LDS banks: 16 consecutive rows then cover every bank group once)
     const char* xbase = reinterpret_cast<const char*>(a.codes) + (size_t)t0 * a.K + (size_t)kb_first * kBK;
     uint32_t xlane[XL];
 #pragma unroll
@@ -182,7 +186,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
         const int row = 8 * q + (lane >> 3);
         int t = t0 + row;
         t = t < a.T ? t : a.T - 1;
-        const int c = (lane & 7) ^ (row & 7);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
         xlane[m] = (uint32_t)(t - t0) * (uint32_t)a.K + c * 16;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
@@ -214,11 +218,11 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_kernel(co
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // LDS read offsets: token row = tile*32 + (lane & 31), chunk = 2*ks + (lane >> 5), swizzled by row % 8
+    // LDS read offsets: token row = tile*32 + (lane & 31), chunk = 2*ks + (lane >> 5), swizzled by (row/2) % 8
     int xoff[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-        xoff[ks] = (wt * TT * 32 + (lane & 31)) * kBK + (((2 * ks + (lane >> 5)) ^ (lane & 7)) << 4);
+        xoff[ks] = (wt * TT * 32 + (lane & 31)) * kBK + (((2 * ks + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
     const int woff = XBYTES + wn * TN * 1024 + lane * 16;
 
     // Register pipeline.  With one or two waves per SIMD, whatever a wave issues between two MFMAs is
@@ -398,7 +402,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs a) {
     }
 }
 
-template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT = false>
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT = false, int OCC = 1>
 int launch_cfg(GemmArgs a, hipStream_t stream) {
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int BT = WAVES_T * TT * 32;
@@ -406,7 +410,7 @@ int launch_cfg(GemmArgs a, hipStream_t stream) {
     a.tiles_n = (a.N + BN - 1) / BN;
     a.tiles_t = (a.T + BT - 1) / BT;
     if (!SPLIT) a.split_k = 1;
-    auto kern = ternary_gemm_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, RAW, SPLIT>;
+    auto kern = ternary_gemm_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, RAW, SPLIT, OCC>;
     static std::atomic<bool> attr_set{false};   // once per process (one device)
     if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -451,6 +455,9 @@ int choose(const GemmArgs& a, hipStream_t stream) {
         case 3: return launch_cfg<2, 2, 4, 4, 3, RAW>(a, stream);   // 256 x 256, 4 waves of 128 x 128
         case 4: return launch_cfg<2, 4, 4, 2, 3, RAW>(a, stream);   // 256 x 256, 8 waves of 128 x 64
         case 5: return launch_cfg<4, 2, 2, 4, 3, RAW>(a, stream);   // 256 x 256, 8 waves of 64 x 128
+        case 8: return launch_cfg<2, 2, 2, 4, 2, RAW, false, 2>(a, stream);   // 128 x 256, two workgroups per CU
+        case 9: return launch_cfg<2, 2, 4, 2, 3, RAW, false, 2>(a, stream);   // 256 x 128, two workgroups per CU
+        case 10: return launch_cfg<2, 2, 4, 2, 2, RAW, false, 2>(a, stream);  // 256 x 128, 2 stages
         case 6: if constexpr (!RAW) return launch_cfg<4, 1, 1, 1, 4, false, true>(a, stream);   // 128 x 32, split-K
         case 7: if constexpr (!RAW) return launch_cfg<4, 1, 1, 2, 4, false, true>(a, stream);   // 128 x 64, split-K
         default: return HBL_E_SHAPE;
