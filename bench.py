@@ -153,7 +153,7 @@ def bench_decode(args, hbl, synth, torch, np):
             del c
         packed.append(per)
     alphas = [torch.full((s.groups,), 0.016, dtype=torch.float32, device="cuda") for s in base]
-    w_bytes = sum(s.N * s.K // 4 + 4 * s.N for s in base)
+    w_bytes = sum(s.N * s.K // 4 + 4 * s.N for s in base)   # the 2-bit form a decode call streams, + row sums
     res = {}
     for B in (1, 8, 32, 64):
         sites = synth.config_sites(5, batch=B)

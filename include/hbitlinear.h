@@ -49,6 +49,13 @@ extern "C" {
 #define HBL_F32 0
 #define HBL_BF16 1
 
+/* forms in which the quantised activation codes travel between the two launches (stage-level calls) */
+#define HBL_CODES_INT8 0        /* one signed byte per code                                              */
+#define HBL_CODES_UINT4_PLUS8 8 /* INT4 only: byte = code + 8 in 0..15                                   */
+#define HBL_CODES_BF6 6         /* INT4 only, Hadamard with K in {4096, 8192, 16384}: per 32 features a
+                                   32-byte record, first 24 bytes = the 32 codes as 6-bit floats (e3m2,
+                                   feature i at bits [6i, 6i+6)), every integer in [-8, 7] exact          */
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* hbl_strerror(int status);
 /* The hipError_t value behind the most recent HBL_E_HIP on this thread (0 if none). */
@@ -74,7 +81,8 @@ size_t hbl_ternarize_workspace_bytes(int64_t N, int64_t K);
 int hbl_ternarize_weights_absmean(const float* W, int64_t N, int64_t K, float eps, int8_t* codes,
                                   float* alpha, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of the packed form of an [N, K] ternary tensor: N*K/4 (2 bits per weight) + 4*N (row sums). */
+/* Bytes of the packed form of an [N, K] ternary tensor: two 2-bit forms (one per matrix-core path,
+ * N*K/4 bytes each; a forward call streams only one of them) + 4*N (row sums). */
 size_t hbl_packed_bytes(int64_t N, int64_t K);
 
 /*
@@ -136,10 +144,13 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
 
 /*
  * Activation front end only (Eq. 3-6): transform (if hadamard != 0) and quantise.
- *   code_offset  0: codes are stored as such.  8 (INT4 only): stored byte = code + 8 in 0..15 - the
- *              form the forward calls use internally for INT4, because unsigned nibbles toggle far
- *              fewer multiplier input bits than sign-extended bytes and the matrix cores are
- *              power-limited; the GEMM epilogue removes the offset exactly in int32.
+ *   code_offset  one of HBL_CODES_*: HBL_CODES_INT8 stores the codes as such; HBL_CODES_UINT4_PLUS8
+ *              stores code + 8 - the form the forward calls use for INT4 on the int8 matrix-core
+ *              path, because unsigned nibbles toggle far fewer multiplier input bits than
+ *              sign-extended bytes and the matrix cores are power-limited (the GEMM epilogue removes
+ *              the offset exactly in int32); HBL_CODES_BF6 writes the records the fp6 x fp4
+ *              matrix-core path reads - the form the forward calls use for INT4 when T > 64 and the
+ *              Hadamard size is 4096, 8192 or 16384.
  *   codes      [T, K] int8 out in natural feature order
  *   s_dequant  [T] fp32 out: gamma/127 or beta/sqrt7
  *   code_sum   [T] int32 out or NULL: sum_k code[t][k] of the true codes (without the offset)

@@ -48,7 +48,16 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     if (workspace_bytes < hbl_workspace_bytes(T, K, N, bits)) return HBL_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Workspace ws = carve_workspace(workspace, T, K, N);
-    // INT4 codes travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs
+    // INT4 at prefill sizes behind a large Hadamard transform: bf6 code records and the fp6 x fp4 matrix
+    // cores (exact, twice the int8 MFMA rate).  HBL_NO_F6F4=1 keeps everything on the int8 path.
+    static const bool no_f6f4 = getenv("HBL_NO_F6F4") != nullptr;
+    if (!no_f6f4 && bf6_path_supported(T, K, bits, hadamard)) {
+        rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, kCodesBf6,
+                               s);
+        if (rc != HBL_OK) return rc;
+        return launch_ternary_gemm_f6f4(ws.codes, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, s);
+    }
+    // otherwise INT4 codes travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs
     const int code_offset = bits == 4 ? 8 : 0;
     rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, code_offset, s);
     if (rc != HBL_OK) return rc;
@@ -95,7 +104,7 @@ int hbl_ternarize_weights_absmean(const float* W, int64_t N, int64_t K, float ep
 
 size_t hbl_packed_bytes(int64_t N, int64_t K) {
     if (N <= 0 || K <= 0) return 0;
-    return packed_tile_bytes(N, K) + (size_t)N * sizeof(int32_t);
+    return packed_total_bytes(N, K);
 }
 
 int hbl_pack_ternary_2bit(const int8_t* codes, int64_t N, int64_t K, void* packed, void* stream) {
@@ -136,7 +145,9 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
 
 int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int hadamard,
                    int code_offset, int8_t* codes, float* s_dequant, int32_t* code_sum, void* stream) {
-    if (code_offset != 0 && !(code_offset == 8 && bits == 4)) return HBL_E_BITS;
+    if (code_offset != HBL_CODES_INT8 && !((code_offset == HBL_CODES_UINT4_PLUS8 || code_offset == HBL_CODES_BF6) && bits == 4))
+        return HBL_E_BITS;
+    if (code_offset == HBL_CODES_BF6 && !(hadamard && (K == 4096 || K == 8192 || K == 16384))) return HBL_E_SHAPE;
     if (bits != 4 && bits != 8) return HBL_E_BITS;
     if (x_dtype != HBL_F32 && x_dtype != HBL_BF16) return HBL_E_DTYPE;
     int rc = check_gemm_shape(T, K, 32, hadamard != 0);
@@ -162,13 +173,17 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
 int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_dequant, const int32_t* code_sum,
                           int64_t T, int64_t K, const void* Wq_packed, int64_t N, const float* w_scales,
                           int64_t n_scale_groups, void* y, void* stream) {
-    if (code_offset != 0 && code_offset != 8) return HBL_E_BITS;
+    if (code_offset != HBL_CODES_INT8 && code_offset != HBL_CODES_UINT4_PLUS8 && code_offset != HBL_CODES_BF6)
+        return HBL_E_BITS;
     int rc = check_gemm_shape(T, K, N, false);
     if (rc != HBL_OK) return rc;
     if (n_scale_groups < 1 || (N % n_scale_groups) != 0 || ((N / n_scale_groups) % 32) != 0) return HBL_E_SHAPE;
     if (T == 0) return HBL_OK;
     if (!codes || !s_dequant || !code_sum || !Wq_packed || !w_scales || !y) return HBL_E_NULL;
     if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(y)) return HBL_E_ALIGN;
+    if (code_offset == HBL_CODES_BF6)
+        return launch_ternary_gemm_f6f4(codes, T, K, Wq_packed, N, s_dequant, w_scales, n_scale_groups, y,
+                                        static_cast<hipStream_t>(stream));
     return launch_ternary_gemm(codes, code_offset, T, K, Wq_packed, N, s_dequant, code_sum, w_scales,
                                n_scale_groups, y, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }

@@ -445,7 +445,10 @@ struct BigRowLayout {
 };
 __host__ __device__ constexpr uint32_t swz16(uint32_t q) { return q ^ ((q >> 4) & 15u); }
 
-template <int LOG2K, int BITS, bool BF16>
+// BF6OUT (INT4 only): instead of one byte per code, write the form the fp6 x fp4 GEMM reads - per 32
+// consecutive features a 32-byte record whose first 24 bytes hold the 32 codes as bf6 (e3m2) values,
+// feature i at bits [6i, 6i+6); every integer in [-8, 7] is exact in that format.
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT>
 __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
     const void* __restrict__ x, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
     int32_t* __restrict__ code_sum, float eps, int code_offset) {
@@ -601,10 +604,14 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
 
     constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
     constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
+    static_assert(!BF6OUT || BITS == 4, "bf6 records carry INT4 codes only");
+    if constexpr (BF6OUT) code_offset = 8;   // the table below is indexed by code + 8
     const float magic = kMagic + (float)code_offset;
     if constexpr (FOLD) gain = gain * c_n;
     int isum = 0;
     int8_t* out = codes + row_off + (LC::qt(tid) << 2);
+    uint32_t* c24 = reinterpret_cast<uint32_t*>(row_lds);   // BF6OUT: 24 bits of bf6 per chunk, by chunk number
+    const uint32_t cbase = LC::qt(tid);
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
         uint32_t packed = 0;
@@ -615,7 +622,33 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
             packed |= (bits & 0xFFu) << (8 * e);
         }
         isum = __builtin_amdgcn_sdot4((int)packed, 0x01010101, isum, false);   // += the 4 stored bytes
-        *reinterpret_cast<uint32_t*>(out + (LC::qj(j) << 2)) = packed;
+        if constexpr (!BF6OUT) {
+            *reinterpret_cast<uint32_t*>(out + (LC::qj(j) << 2)) = packed;
+        } else {
+            // bytes code+8 in 0..15 -> bf6 bit patterns by two 8-entry byte-permute look-ups:
+            // -8..-5 = 38 37 36 35, -4..-1 = 34 32 30 2c, 0..3 = 00 0c 10 12, 4..7 = 14 15 16 17 (hex)
+            const uint32_t sel = packed & 0x07070707u;
+            const uint32_t neg = __builtin_amdgcn_perm(0x2C303234u, 0x35363738u, sel);
+            const uint32_t pos = __builtin_amdgcn_perm(0x17161514u, 0x12100C00u, sel);
+            const uint32_t is_pos = ((packed >> 3) & 0x01010101u) * 0xFFu;
+            const uint32_t r = (pos & is_pos) | (neg & ~is_pos);
+            // four 6-bit fields, one per byte -> 24 contiguous bits
+            const uint32_t t2 = (r & 0x003F003Fu) | ((r & 0x3F003F00u) >> 2);
+            c24[cbase ^ LC::qj(j)] = (t2 & 0xFFFu) | ((t2 >> 4) & 0xFFF000u);
+        }
+    }
+    if constexpr (BF6OUT) {
+        // regroup through LDS: four consecutive chunks (16 features, 96 bits) become three dwords
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t quad = tid + NT * i;
+            const uint4 c = *reinterpret_cast<const uint4*>(c24 + 4 * quad);
+            uint32_t* dst = reinterpret_cast<uint32_t*>(codes + row_off + 32 * (quad >> 1) + 12 * (quad & 1));
+            dst[0] = c.x | (c.y << 24);
+            dst[1] = (c.y >> 8) | (c.z << 16);
+            dst[2] = (c.z >> 16) | (c.w << 8);
+        }
     }
     isum -= 64 * code_offset;
 #pragma unroll
@@ -633,12 +666,12 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
     }
 }
 
-template <int LOG2K, int BITS, bool BF16>
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT = false>
 int launch_bigrow(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, float eps,
                   int code_offset, hipStream_t stream) {
     constexpr int K = 1 << LOG2K;
     constexpr size_t lds = sizeof(float) * K;
-    auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16>;
+    auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16, BF6OUT>;
     static std::atomic<bool> attr_set{false};   // once per process (one device)
     if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -655,6 +688,9 @@ template <int LOG2K>
 int dispatch_bigrow(const void* x, int x_dtype, int64_t T, int bits, float eps, int8_t* codes, float* s_dequant,
                     int32_t* code_sum, int code_offset, hipStream_t stream) {
     const bool bf = x_dtype == HBL_BF16;
+    if (code_offset == kCodesBf6)
+        return bf ? launch_bigrow<LOG2K, 4, true, true>(x, T, codes, s_dequant, code_sum, eps, 8, stream)
+                  : launch_bigrow<LOG2K, 4, false, true>(x, T, codes, s_dequant, code_sum, eps, 8, stream);
     if (bits == 8) return bf ? launch_bigrow<LOG2K, 8, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
                              : launch_bigrow<LOG2K, 8, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
     return bf ? launch_bigrow<LOG2K, 4, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
@@ -683,7 +719,8 @@ int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     if (T == 0) return HBL_OK;
     if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
-    if (hadamard && !getenv("HBL_FWHT_OLD")) {
+    if (code_offset == kCodesBf6 && !(hadamard && (K == 4096 || K == 8192 || K == 16384))) return HBL_E_SHAPE;
+    if (hadamard && (code_offset == kCodesBf6 || !getenv("HBL_FWHT_OLD"))) {
         if (K == 4096) return dispatch_bigrow<12>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
         if (K == 8192) return dispatch_bigrow<13>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
         if (K == 16384) return dispatch_bigrow<14>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);

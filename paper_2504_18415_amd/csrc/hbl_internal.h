@@ -61,7 +61,12 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
 }
 
 // Launchers (defined in the .hip files). All validate nothing: callers in api.hip do.
-// Codes are stored as code + code_offset (0, or 8 for INT4 so that the stored bytes are 0..15).
+// Codes are stored as code + code_offset (0, or 8 for INT4 so that the stored bytes are 0..15), or -
+// code_offset == kCodesBf6 - as bf6 records (see fwht_quant.hip; Hadamard with K in {4096, 8192, 16384}).
+constexpr int kCodesBf6 = 6;
+inline bool bf6_path_supported(int64_t T, int64_t K, int bits, bool hadamard) {
+    return bits == 4 && hadamard && T > 64 && (K == 4096 || K == 8192 || K == 16384);
+}
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream);
 
@@ -72,8 +77,17 @@ int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t
                         int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, int32_t* splitk_partial,
                         hipStream_t stream);
 
-// Packed weight buffer: N*K/4 bytes of 2-bit tiles, then N int32 row sums of the ternary codes.
+// GEMM + epilogue on the fp6 x fp4 matrix-core path: codes as bf6 records, weights from the second
+// packed form; exact, INT4 activations only.
+int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, const void* packed, int64_t N,
+                             const float* s_dequant, const float* w_scales, int64_t n_scale_groups, void* y_bf16,
+                             hipStream_t stream);
+
+// Packed weight buffer: N*K/4 bytes of 2-bit tiles for the int8 matrix-core path, N int32 row sums of
+// the ternary codes, then N*K/4 bytes of 2-bit tiles in the form the fp6 x fp4 path reads.
 inline size_t packed_tile_bytes(int64_t N, int64_t K) { return (size_t)N * (size_t)K / 4; }
+inline size_t packed_f4_offset(int64_t N, int64_t K) { return packed_tile_bytes(N, K) + (size_t)N * sizeof(int32_t); }
+inline size_t packed_total_bytes(int64_t N, int64_t K) { return packed_f4_offset(N, K) + packed_tile_bytes(N, K); }
 
 int launch_ternarize(const float* W, int64_t count, float eps, int8_t* codes, float* alpha, void* workspace,
                      hipStream_t stream);

@@ -17,43 +17,13 @@
 #include <atomic>
 #include <type_traits>
 
-#include "hbl_internal.h"
+#include "gemm_common.h"
 
 namespace hbl {
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
+using namespace gemm;
 typedef int v16i __attribute__((ext_vector_type(16)));
-
-constexpr int kBK = 128;  // features per pipeline stage = one packed weight tile
-
-__device__ __forceinline__ uint32_t as_u(float f) { return __builtin_bit_cast(uint32_t, f); }
-
-// Wait until at most N of this wave's vector-memory loads are still in flight, then workgroup barrier.
-// Written as one asm block: __syncthreads() carries a release fence that the compiler lowers to
-// vmcnt(0), which would drain the whole global->LDS pipeline at every stage.  The "memory" clobber
-// keeps every load / store on its side of the barrier.
-// lgkmcnt(0): this wave's own LDS reads of the buffer about to be recycled have returned.
-template <int N>
-__device__ __forceinline__ void wait_loads_then_barrier() {
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
-}
-
-// One 16-byte-per-lane global -> LDS copy: lane l's 16 bytes at (base + voff) land at LDS byte
-// lds_addr + 16*l.  Written in asm so that the address is exactly "SGPR pair + 32-bit VGPR offset"
-// (no per-copy vector address arithmetic) and the copy stays where the source puts it.
-__device__ __forceinline__ void lds_dma16(uint32_t lds_addr, const void* base, uint32_t voff) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(voff), "s"(base)
-                 : "memory", "m0");
-}
-
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float v) {
-    uint32_t u = as_u(v);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
 
 // Expand one packed dword into the four operand registers of a lane.
 template <bool SUBTRACT_ONE>
@@ -72,50 +42,6 @@ __device__ __forceinline__ v4i expand(uint32_t p) {
     return r;
 }
 
-struct GemmArgs {
-    const int8_t* codes;      // [T, K]
-    const uint32_t* packed;   // tiles [N/32][K/128][64 lanes][4 dwords]
-    const float* s_dequant;   // [T]
-    const int32_t* code_sum;  // [T] sum_k q[t][k] of the true (un-offset) codes
-    const int32_t* w_row_sum; // [N] sum_k c[o][k]
-    int code_offset;          // stored code byte = q + code_offset
-    const float* w_scales;    // [groups]
-    uint16_t* y;              // [T, N] bf16
-    int32_t* acc_out;         // [T, N] (RAW only)
-    int T, K, N;
-    int rows_per_group;
-    int tiles_n, tiles_t;
-    // split-K (small T only): workgroup (tile, ks) covers K-blocks [ks*nkb/split_k, (ks+1)*nkb/split_k)
-    // and writes its int32 partial tile to partial[ks][T][N]; splitk_reduce_kernel finishes the job
-    int split_k;
-    int32_t* partial;
-};
-
-typedef int v4i_ __attribute__((ext_vector_type(4)));
-
-// Outer factors of Eq. 1 and Eq. 5/6 on four consecutive output features of one token:
-// y = bf16(((float)(acc - corr) * s_d) * alpha), corr = sum_k q + code_offset * (sum_k c + K).
-__device__ __forceinline__ uint2 dequant_quad(v4i_ acc, int sx, float sd, float alpha, int code_offset,
-                                              const int32_t* w_row_sum, int K) {
-    v4i_ corr = {sx, sx, sx, sx};
-    if (code_offset != 0) {
-        const v4i_ ws = *reinterpret_cast<const v4i_*>(w_row_sum);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) corr[r] += code_offset * (ws[r] + K);
-    }
-    float v[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) v[r] = ((float)(acc[r] - corr[r]) * sd) * alpha;
-    // v_cvt_pk_bf16_f32: round to nearest even, two values per instruction
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    const bf16x2 lo = __builtin_convertvector((f32x2){v[0], v[1]}, bf16x2);
-    const bf16x2 hi = __builtin_convertvector((f32x2){v[2], v[3]}, bf16x2);
-    return make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
-}
-
-// WAVES_N x WAVES_T waves; each wave owns TN x TT MFMA tiles (32 features x 32 tokens each).
-// LDS stage = [BT tokens x 128 B codes, XOR-swizzled][BN/32 packed weight tiles x 1 KiB].
 // OCC = waves per SIMD the register budget must allow (2: two workgroups of 4 waves share a CU).
 template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT, int OCC>
 __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kernel(const GemmArgs a) {

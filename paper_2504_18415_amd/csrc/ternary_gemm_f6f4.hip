@@ -1,0 +1,320 @@
+// Ternary GEMM of H-BitLinear for INT4 activations on the fp6 x fp4 matrix-core path (Eq. 7):
+//   acc[t][o] = sum_k q[t][k] * c[o][k],  q in [-8, 7] carried as bf6 (e3m2), c in {-1, 0, 1} as fp4 (e2m1).
+// Every code and weight is exactly representable, every product is an integer of magnitude <= 8 and
+// every partial sum stays below 2^24, so the fp32 accumulators of v_mfma_f32_32x32x64_f8f6f4 hold the
+// same integers the int8 path produces (checked bit for bit by the parity tests) - at twice the int8
+// MFMA rate per instruction and with far fewer toggling multiplier bits, which matters because the
+// matrix cores are power-limited.  No offset trick is needed here: the operands are signed.
+//
+// Same skeleton as ternary_gemm.hip (256 x 256 tiles, 4 waves of 128 x 128, direct global->LDS copies,
+// one small piece of side work after every MFMA).  Differences:
+//   - a pipeline stage is still 128 features but only two MFMA K-steps of 64;
+//   - activation codes arrive as 32-byte records (24 bytes of bf6 + 8 unused) so a token row of a
+//     stage is 128 bytes as before and an operand is one 16-byte + one 8-byte LDS read;
+//   - weights come from the second packed form (sign / magnitude bit pairs): two AND and one shift
+//     turn a packed dword into two operand registers of eight fp4 values each.
+#include <stdlib.h>
+
+#include <atomic>
+#include <type_traits>
+
+#include "gemm_common.h"
+
+namespace hbl {
+namespace {
+
+using namespace gemm;
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE>
+__global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kernel(const GemmArgs a) {
+    constexpr int NW = WAVES_N * WAVES_T;
+    constexpr int BN = WAVES_N * TN * 32;
+    constexpr int BT = WAVES_T * TT * 32;
+    constexpr int XBYTES = BT * kBK;               // code records per stage (1 byte of storage per feature)
+    constexpr int WBYTES = (BN / 32) * 1024;       // packed weights per stage
+    constexpr int STAGE = XBYTES + WBYTES;
+    constexpr int XL = (BT / 8) / NW;              // global->LDS copies per wave per stage: codes
+    constexpr int WL = (BN / 32) / NW;             // ... and weights
+    static_assert((BT / 8) % NW == 0 && (BN / 32) % NW == 0, "stage copies must divide evenly over the waves");
+    static_assert(NSTAGE >= 2, "need at least double buffering");
+    constexpr int PENDING = (NSTAGE - 2) * (XL + WL);
+
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave % WAVES_N;
+    const int wt = wave / WAVES_N;
+
+    // each XCD gets a contiguous run of tiles, feature tile fastest (workgroups are dealt round-robin)
+    int wg = blockIdx.x;
+    const int nwg = a.tiles_n * a.tiles_t;
+    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
+    const int tile_n = wg % a.tiles_n;
+    const int tile_t = wg / a.tiles_n;
+    const int n0 = tile_n * BN;
+    const int t0 = tile_t * BT;
+    const int nkb = a.K / kBK;
+
+    const char* wbase[WL];
+#pragma unroll
+    for (int m = 0; m < WL; ++m) {
+        int nt = n0 / 32 + wave + NW * m;
+        const int nt_max = a.N / 32 - 1;
+        nt = nt < nt_max ? nt : nt_max;
+        wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb) * 1024;
+    }
+    const uint32_t wlane = lane * 16;
+    // copy q covers tokens 8q..8q+7: lane l -> token 8q + l/8, LDS slot l%8, global 16-byte chunk
+    // (l%8) ^ ((token/2) % 8); tokens past T are clamped to the last row
+    const char* xbase = reinterpret_cast<const char*>(a.codes) + (size_t)t0 * a.K;
+    uint32_t xlane[XL];
+#pragma unroll
+    for (int m = 0; m < XL; ++m) {
+        const int q = wave + NW * m;
+        const int row = 8 * q + (lane >> 3);
+        int t = t0 + row;
+        t = t < a.T ? t : a.T - 1;
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        xlane[m] = (uint32_t)(t - t0) * (uint32_t)a.K + c * 16;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+
+    auto issue_one = [&](int m, int kb, int slot) {
+        const int kbc = kb < nkb ? kb : nkb - 1;   // past the end: re-read the last block (keeps PENDING valid)
+        if (m < XL) {
+            const int q = wave + NW * m;
+            lds_dma16(lds0 + slot * STAGE + q * 1024, xbase + (size_t)kbc * kBK, xlane[m]);
+        } else {
+            const int wtile = wave + NW * (m - XL);
+            lds_dma16(lds0 + slot * STAGE + XBYTES + wtile * 1024, wbase[m - XL] + (size_t)kbc * 1024, wlane);
+        }
+    };
+    auto issue = [&](int kb, int slot) {
+#pragma unroll
+        for (int m = 0; m < XL + WL; ++m) issue_one(m, kb, slot);
+    };
+
+    v16f acc[TN][TT];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TT; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // record of K-step s (64 features) for lane half h = lane >> 5 starts at chunk 4s + 2h of the token's
+    // 128-byte row: 16 bytes there, 8 more at the start of the next chunk
+    int xoff_lo[2], xoff_hi[2];
+    {
+        const int rowoff = (wt * TT * 32 + (lane & 31)) * kBK;
+        const int sw = (lane >> 1) & 7;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int c = 4 * s + 2 * (lane >> 5);
+            xoff_lo[s] = rowoff + ((c ^ sw) << 4);
+            xoff_hi[s] = rowoff + (((c + 1) ^ sw) << 4);
+        }
+    }
+    const int woff = XBYTES + wn * TN * 1024 + lane * 16;
+
+    v4i wpk[TN];      // packed weights of the current stage: dword 2s + d
+    v8i xop[2][TT];   // code operands (6 registers used) of the current / next K-step
+    v8i wop[2][TN];   // weight operands (4 registers used)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+        for (int j = 0; j < TT; ++j) xop[b][j][6] = xop[b][j][7] = 0;
+#pragma unroll
+        for (int i = 0; i < TN; ++i) wop[b][i][4] = wop[b][i][5] = wop[b][i][6] = wop[b][i][7] = 0;
+    }
+    constexpr int NMF = TN * TT;
+    constexpr int EOPS = 6;   // VALU instructions to expand the two packed dwords of one K-step
+    auto expand_op = [&](int s, int obuf, int i, int op) {
+        const uint32_t p = (uint32_t)wpk[i][2 * s + op / 3];
+        const int r = 2 * (op / 3);
+        const int st = op % 3;
+        if (st == 0) wop[obuf][i][r] = (int)(p & 0xAAAAAAAAu);
+        else if (st == 1) wop[obuf][i][r + 1] = (int)(p << 1);
+        else wop[obuf][i][r + 1] = (int)((uint32_t)wop[obuf][i][r + 1] & 0xAAAAAAAAu);
+    };
+    auto load_w_one = [&](int slot, int i) {
+        wpk[i] = *reinterpret_cast<const v4i*>(lds + slot * STAGE + woff + i * 1024);
+    };
+    // half an operand per call: part 0 = the 16-byte piece, part 1 = the 8-byte piece
+    auto load_x_part = [&](int slot, int s, int buf, int j, int part) {
+        const char* base = lds + slot * STAGE + j * 32 * kBK;
+        if (part == 0) {
+            const v4i lo = *reinterpret_cast<const v4i*>(base + xoff_lo[s]);
+            xop[buf][j][0] = lo[0]; xop[buf][j][1] = lo[1]; xop[buf][j][2] = lo[2]; xop[buf][j][3] = lo[3];
+        } else {
+            const int2 hi = *reinterpret_cast<const int2*>(base + xoff_hi[s]);
+            xop[buf][j][4] = hi.x; xop[buf][j][5] = hi.y;
+        }
+    };
+    auto mfma = [&](int cur, int g) {
+        const int i = g / TT, j = g % TT;
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wop[cur][i], xop[cur][j], acc[i][j], 4 /*A: fp4*/,
+                                                                    3 /*B: bf6*/, 0, 0, 0, 0);
+    };
+
+    // K-step 0 of a stage (operands in [0]); meanwhile fetch / expand K-step 1 into [1]
+    auto kstep_first = [&](int slot) {
+        constexpr int TOTAL = EOPS * TN;
+        constexpr int VPER = (TOTAL + NMF - 1) / NMF;
+        if (2 * TT > NMF) {
+#pragma unroll
+            for (int x = 0; x < 2 * TT; ++x) load_x_part(slot, 1, 1, x / 2, x % 2);
+        }
+#pragma unroll
+        for (int g = 0; g < NMF; ++g) {
+            mfma(0, g);
+            if (2 * TT <= NMF && g < 2 * TT) load_x_part(slot, 1, 1, g / 2, g % 2);
+#pragma unroll
+            for (int v = g * VPER; v < (g + 1) * VPER && v < TOTAL; ++v) expand_op(1, 1, v / EOPS, v % EOPS);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // K-step 1 (operands in [1]; wpk is dead): copies of stage kb+NSTAGE and the next stage's LDS reads go
+    // out under the first MFMAs, the expansion of the next stage's K-step 0 under the last ones
+    auto kstep_last = [&](int kb, int slot) {
+        constexpr int TOTAL = EOPS * TN;
+        constexpr int READS = TN + 2 * TT;
+        constexpr int SIDE = XL + WL > READS ? XL + WL : READS;
+        constexpr bool FITS = SIDE <= NMF - 2;
+        constexpr int FIRSTV = FITS ? (TN + 2 < NMF - 2 ? TN + 2 : NMF - 2) : 0;
+        constexpr int VPER = (TOTAL + (NMF - FIRSTV) - 1) / (NMF - FIRSTV);
+        const int nslot = slot + 1 == NSTAGE ? 0 : slot + 1;
+        if (!FITS) {
+            issue(kb + NSTAGE, slot);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) load_w_one(nslot, i);
+#pragma unroll
+            for (int x = 0; x < 2 * TT; ++x) load_x_part(nslot, 0, 0, x / 2, x % 2);
+        }
+#pragma unroll
+        for (int g = 0; g < NMF; ++g) {
+            mfma(1, g);
+            if (FITS) {
+                if (g < XL + WL) issue_one(g, kb + NSTAGE, slot);
+                if (g < TN) load_w_one(nslot, g);
+                else if (g < READS) load_x_part(nslot, 0, 0, (g - TN) / 2, (g - TN) % 2);
+            }
+            if (g >= FIRSTV) {
+#pragma unroll
+                for (int v = (g - FIRSTV) * VPER; v < (g - FIRSTV + 1) * VPER && v < TOTAL; ++v)
+                    expand_op(0, 0, v / EOPS, v % EOPS);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // prologue
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s) issue(s, s);
+    wait_loads_then_barrier<PENDING>();
+    issue(NSTAGE - 1, NSTAGE - 1);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) load_w_one(0, i);
+#pragma unroll
+    for (int x = 0; x < 2 * TT; ++x) load_x_part(0, 0, 0, x / 2, x % 2);
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int op = 0; op < EOPS; ++op) expand_op(0, 0, i, op);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // One code path for every stage (the last one's "next stage" work re-reads stale data nobody uses).
+    int slot = 0;
+    for (int kb = 0; kb < nkb; ++kb) {
+        kstep_first(slot);
+        wait_loads_then_barrier<PENDING>();
+        kstep_last(kb, slot);
+        slot = slot + 1 == NSTAGE ? 0 : slot + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the clamped tail copies before the LDS is released
+
+    // epilogue: lane holds token t = ..+(lane&31); register quad g holds features 8g + 4*(lane>>5) + 0..3.
+    // The accumulators are integers held in fp32: y = bf16((acc * s_d) * alpha) as on the int8 path.
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int j = 0; j < TT; ++j) {
+        const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
+        if (t >= a.T) continue;
+        const float sd = a.s_dequant[t];
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            __builtin_amdgcn_sched_barrier(0);   // one accumulator tile at a time (register pressure)
+            const int nb = n0 + (wn * TN + i) * 32;
+            if (nb >= a.N) continue;
+            const float alpha = a.w_scales[nb / a.rows_per_group];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = nb + 8 * g + 4 * (lane >> 5);
+                float v[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = (acc[i][j][4 * g + r] * sd) * alpha;
+                const bf16x2 lo = __builtin_convertvector((f32x2){v[0], v[1]}, bf16x2);
+                const bf16x2 hi = __builtin_convertvector((f32x2){v[2], v[3]}, bf16x2);
+                *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) =
+                    make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+            }
+        }
+    }
+}
+
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE>
+int launch_cfg(GemmArgs a, hipStream_t stream) {
+    constexpr int BN = WAVES_N * TN * 32;
+    constexpr int BT = WAVES_T * TT * 32;
+    constexpr size_t lds = (size_t)NSTAGE * (BT * kBK + (BN / 32) * 1024);
+    a.tiles_n = (a.N + BN - 1) / BN;
+    a.tiles_t = (a.T + BT - 1) / BT;
+    auto kern = ternary_gemm_f6f4_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE>;
+    static std::atomic<bool> attr_set{false};   // once per process (one device)
+    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return note_hip_error(e);
+        attr_set.store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t)), dim3(64 * WAVES_N * WAVES_T), lds, stream, a);
+    return after_launch();
+}
+
+}  // namespace
+
+int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, const void* packed, int64_t N,
+                             const float* s_dequant, const float* w_scales, int64_t n_scale_groups, void* y_bf16,
+                             hipStream_t stream) {
+    if (T == 0) return HBL_OK;
+    GemmArgs a = {};
+    a.codes = code_records;
+    a.packed = reinterpret_cast<const uint32_t*>(static_cast<const char*>(packed) + packed_f4_offset(N, K));
+    a.s_dequant = s_dequant;
+    a.w_scales = w_scales;
+    a.y = static_cast<uint16_t*>(y_bf16);
+    a.T = (int)T;
+    a.K = (int)K;
+    a.N = (int)N;
+    a.rows_per_group = n_scale_groups > 0 ? (int)(N / n_scale_groups) : (int)N;
+    a.split_k = 1;
+    const int64_t big_tiles = (int64_t)((N + 255) / 256) * ((T + 255) / 256);
+    static const int override_tile = [] {
+        const char* e = getenv("HBL_GEMM_F6F4_TILE");
+        return e ? atoi(e) : -1;
+    }();
+    int cfg = big_tiles >= 200 ? 0 : 1;
+    if (override_tile >= 0) cfg = override_tile;
+    switch (cfg) {
+        case 0: return launch_cfg<2, 2, 4, 4, 3>(a, stream);   // 256 x 256, 4 waves of 128 x 128
+        case 1: return launch_cfg<2, 2, 2, 2, 4>(a, stream);   // 128 x 128
+        default: return HBL_E_SHAPE;
+    }
+}
+
+}  // namespace hbl

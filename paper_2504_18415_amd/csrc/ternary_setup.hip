@@ -10,7 +10,8 @@
 // i.e. exactly one lane's share of a 32x32x32 int8 matrix-core operand for K-step s.
 // Weight i = 4*j + b of that group sits at bits [8*b + 2*j, 8*b + 2*j + 1] as code+1,
 // so that (dword >> 2*j) & 0x03030303 is operand register j (bytes b = 0..3).
-// After the N*K/4 bytes of tiles come N int32 row sums sum_k c[o][k].
+// After the N*K/4 bytes of tiles come N int32 row sums sum_k c[o][k], then the second packed form
+// (pack_f4_kernel below).
 #include "hbl_internal.h"
 
 namespace hbl {
@@ -116,6 +117,40 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
     *reinterpret_cast<uint4*>(codes + row * K + k0) = raw;
 }
 
+// Second packed form, for the fp6 x fp4 matrix-core path (INT4 activations at prefill sizes): the same
+// 1 KiB tiles of 32 rows x 128 features and the same lane order, but lane l's 16 bytes are
+//   dword 2*s + d (s = 64-feature K-step 0..1, d = 0..1): the 16 weights of row 32*nt + (l & 31) at
+//   features 128*kb + 64*s + 32*(l >> 5) + 16*d + i, i = 0..15,
+// stored sign/magnitude: weight i < 8 has its magnitude at bit 4*i + 1 and its sign at bit 4*i + 3,
+// weight i >= 8 its magnitude at bit 4*(i-8) and its sign at bit 4*(i-8) + 2.  Then
+//   p & 0xAAAAAAAA  and  (p << 1) & 0xAAAAAAAA
+// are eight fp4 (e2m1) values each (+-1.0 = s010, 0 = 0000): operand registers of the 32x32x64 MFMA.
+__global__ __launch_bounds__(256) void pack_f4_kernel(const int8_t* __restrict__ codes, int64_t N, int64_t K,
+                                                      uint32_t* __restrict__ packed) {
+    const int64_t kblocks = K / 128;
+    const int64_t total = (N / 32) * kblocks * 256;  // dwords
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d >= total) return;
+    const int dd = (int)(d & 3);
+    const int lane = (int)((d >> 2) & 63);
+    const int64_t tile = d >> 8;
+    const int64_t kb = tile % kblocks, nt = tile / kblocks;
+    const int64_t row = nt * 32 + (lane & 31);
+    const int64_t k0 = kb * 128 + (dd >> 1) * 64 + (lane >> 5) * 32 + (dd & 1) * 16;
+    const uint4 raw = *reinterpret_cast<const uint4*>(codes + row * K + k0);
+    const int8_t* c = reinterpret_cast<const int8_t*>(&raw);
+    uint32_t out = 0;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+        const int a = c[n], b = c[8 + n];
+        out |= (uint32_t)(a != 0) << (4 * n + 1);
+        out |= (uint32_t)(a < 0) << (4 * n + 3);
+        out |= (uint32_t)(b != 0) << (4 * n);
+        out |= (uint32_t)(b < 0) << (4 * n + 2);
+    }
+    packed[d] = out;
+}
+
 // Row sums of the ternary codes, sum_k c[o][k], one wave per output row: the GEMM epilogue needs them
 // when activation codes are stored with an offset.
 __global__ __launch_bounds__(256) void row_sum_kernel(const int8_t* __restrict__ codes, int64_t N, int64_t K,
@@ -165,6 +200,10 @@ int launch_pack(const int8_t* codes, int64_t N, int64_t K, void* packed, hipStre
     if (rc != HBL_OK) return rc;
     int32_t* row_sum = reinterpret_cast<int32_t*>(static_cast<char*>(packed) + packed_tile_bytes(N, K));
     hipLaunchKernelGGL(row_sum_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, codes, N, K, row_sum);
+    rc = after_launch();
+    if (rc != HBL_OK) return rc;
+    hipLaunchKernelGGL(pack_f4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
+                       reinterpret_cast<uint32_t*>(static_cast<char*>(packed) + packed_f4_offset(N, K)));
     return after_launch();
 }
 

@@ -22,6 +22,7 @@ LIB_PATH = os.path.join(_PKG, "libhbitlinear.so")
 OK = 0
 E_NULL, E_SHAPE, E_BITS, E_DTYPE, E_WORKSPACE, E_HIP, E_ALIGN = -1, -2, -3, -4, -5, -6, -7
 F32, BF16 = 0, 1
+CODES_INT8, CODES_UINT4_PLUS8, CODES_BF6 = 0, 8, 6
 EPS = 1e-5
 
 EXPORTS = [
@@ -119,7 +120,7 @@ def packed_bytes(N: int, K: int) -> int:
 
 
 def pack_ternary_2bit(codes: torch.Tensor) -> torch.Tensor:
-    """codes int8 [N,K] in {-1,0,1} -> opaque packed uint8 [N*K/4 + 4*N]."""
+    """codes int8 [N,K] in {-1,0,1} -> opaque packed uint8 [N*K/2 + 4*N]."""
     _dev_check(codes)
     N, K = codes.shape
     packed = torch.empty(packed_bytes(N, K), dtype=torch.uint8, device=codes.device)

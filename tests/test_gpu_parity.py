@@ -117,8 +117,8 @@ def test_ternarize_and_pack_roundtrip(hbl, N, K):
     assert a_dev.cpu().numpy()[0] == a_ref
     assert np.array_equal(c_dev.cpu().numpy(), c_ref)
     packed = hbl.pack_ternary_2bit(c_dev)
-    assert packed.numel() == N * K // 4 + 4 * N
-    row_sums = packed[N * K // 4:].view(torch.int32).cpu().numpy()
+    assert packed.numel() == N * K // 2 + 4 * N          # two 2-bit forms + int32 row sums
+    row_sums = packed[N * K // 4:N * K // 4 + 4 * N].view(torch.int32).cpu().numpy()
     assert np.array_equal(row_sums, c_ref.astype(np.int32).sum(1))
     back = hbl.unpack_ternary_2bit(packed, N, K)
     assert np.array_equal(back.cpu().numpy(), c_ref)
@@ -208,6 +208,111 @@ def test_int4_offset_codes_and_split_calls(hbl, K, hadamard):
     assert np.array_equal(host_bf16_bits(y_one), y_ref)
     with pytest.raises(hbl.HblError):
         hbl.fwht_quant(xd, 8, hadamard, EPS, code_offset=8)
+
+
+def decode_bf6_records(rec, K):
+    """[T, K] bytes of 32-byte records (24 bytes = 32 six-bit e3m2 floats, feature i at bits [6i, 6i+6)) -> int codes."""
+    T = rec.shape[0]
+    r = rec.reshape(T, K // 32, 32)[:, :, :24].astype(np.uint64)
+    lo = sum(r[:, :, b] << np.uint64(8 * b) for b in range(8))
+    mid = sum(r[:, :, 8 + b] << np.uint64(8 * b) for b in range(8))
+    hi = sum(r[:, :, 16 + b] << np.uint64(8 * b) for b in range(8))
+    out = np.empty((T, K // 32, 32), np.int32)
+    for i in range(32):
+        bit = 6 * i
+        word, off = divmod(bit, 64)
+        src = (lo, mid, hi)[word]
+        v = (src >> np.uint64(off)) & np.uint64(0x3F)
+        if off > 58:
+            nxt = (lo, mid, hi)[word + 1]
+            v |= (nxt << np.uint64(64 - off)) & np.uint64(0x3F)
+        v = v.astype(np.int32)
+        sign, e, m = v >> 5, (v >> 2) & 7, v & 3
+        mag = np.where(e == 0, m / 16.0, (2.0 ** (e - 3)) * (1 + m / 4.0))
+        out[:, :, i] = np.where(sign == 1, -mag, mag).astype(np.int32)
+        assert np.all(np.where(sign == 1, -mag, mag) == out[:, :, i])       # every stored value is an integer
+    return out.reshape(T, K)
+
+
+@pytest.mark.parametrize("K", [4096, 8192, 16384])
+def test_bf6_code_records_and_f6f4_gemm(hbl, K):
+    """INT4 codes as 6-bit float records (the form the fp6 x fp4 matrix-core path reads): the decoded
+    records equal the oracle codes, and the two-launch split on that path reproduces the oracle's
+    outputs and the int8 path bit for bit."""
+    note(f"bf6 records K={K}")
+    T, N = 150, 288
+    site = synth.Site("a", T, K, N, outlier_frac=0.01, outlier_scale=30.0, seed=K + 6)
+    x = synth.make_x(site)
+    c_ref, s_ref = O.fwht_quant(x, 4, hadamard=True, eps=EPS)
+    xd = dev_x(x)
+    rec, sd, cs = hbl.fwht_quant(xd, 4, True, EPS, code_offset=hbl.CODES_BF6)
+    assert np.array_equal(decode_bf6_records(rec.cpu().numpy().view(np.uint8), K), c_ref.astype(np.int32))
+    assert np.array_equal(sd.cpu().numpy(), s_ref)
+    assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
+    wc_ref, al_ref, wc_d, al_d, packed = setup_weights(hbl, site)
+    y6 = hbl.gemm_dequant_bf16(rec, sd, cs, packed, N, al_d, code_offset=hbl.CODES_BF6)
+    c8, sd8, cs8 = hbl.fwht_quant(xd, 4, True, EPS, code_offset=8)
+    y8 = hbl.gemm_dequant_bf16(c8, sd8, cs8, packed, N, al_d, code_offset=8)
+    y1 = hbl.hbitlinear_forward(xd, packed, N, al_d, 4, EPS)
+    y_ref = O.hbitlinear_forward(x, wc_ref, al_ref, 4, EPS)
+    assert np.array_equal(host_bf16_bits(y6), y_ref)
+    assert np.array_equal(host_bf16_bits(y8), y_ref)
+    assert np.array_equal(host_bf16_bits(y1), y_ref)
+    with pytest.raises(hbl.HblError):
+        hbl.fwht_quant(xd[:, :2048].contiguous(), 4, True, EPS, code_offset=hbl.CODES_BF6)
+
+
+BF6_OF_CODE = {-8: 0x38, -7: 0x37, -6: 0x36, -5: 0x35, -4: 0x34, -3: 0x32, -2: 0x30, -1: 0x2C, 0: 0x00,
+               1: 0x0C, 2: 0x10, 3: 0x12, 4: 0x14, 5: 0x15, 6: 0x16, 7: 0x17}
+
+
+def encode_bf6_records(codes):
+    """int codes [T, K] in [-8, 7] -> [T, K] bytes of 32-byte records (inverse of decode_bf6_records)."""
+    T, K = codes.shape
+    lut = np.zeros(16, np.uint64)
+    for c, v in BF6_OF_CODE.items():
+        lut[c + 8] = v
+    six = lut[codes.astype(np.int64) + 8].reshape(T, K // 32, 32)
+    words = [np.zeros((T, K // 32), np.uint64) for _ in range(3)]
+    for i in range(32):
+        word, off = divmod(6 * i, 64)
+        words[word] |= six[:, :, i] << np.uint64(off)
+        if off > 58:
+            words[word + 1] |= six[:, :, i] >> np.uint64(64 - off)
+    rec = np.zeros((T, K // 32, 32), np.uint8)
+    for w in range(3):
+        for b in range(8):
+            rec[:, :, 8 * w + b] = ((words[w] >> np.uint64(8 * b)) & np.uint64(0xFF)).astype(np.uint8)
+    return rec.reshape(T, K)
+
+
+def test_f6f4_gemm_extreme_codes(hbl):
+    """Hand-made records: every code -8 (one row +7, one row random) against all-(+1) / all-(-1) weight
+    rows - the largest accumulator magnitude the path can see (8 * 16384 = 2^17) must come out exact
+    from the fp32 accumulators of the fp6 x fp4 matrix cores."""
+    note("f6f4 extreme codes")
+    T, K, N = 130, 16384, 64
+    rng = np.random.default_rng(9)
+    codes = np.full((T, K), -8, np.int8)
+    codes[7] = 7
+    codes[9] = rng.integers(-8, 8, K)
+    assert np.array_equal(decode_bf6_records(encode_bf6_records(codes), K), codes)
+    wc = np.ones((N, K), np.int8)
+    wc[1::2] = -1
+    wc[5] = rng.integers(-1, 2, K)
+    packed = hbl.pack_ternary_2bit(torch.from_numpy(wc).cuda())
+    al = torch.ones(1, dtype=torch.float32, device="cuda")
+    sd = torch.ones(T, dtype=torch.float32, device="cuda")
+    cs = torch.from_numpy(codes.astype(np.int32).sum(1).astype(np.int32)).cuda()
+    rec = torch.from_numpy(encode_bf6_records(codes).view(np.int8)).cuda()
+    y = hbl.gemm_dequant_bf16(rec, sd, cs, packed, N, al, code_offset=hbl.CODES_BF6)
+    acc = O.gemm_i32(codes, wc)
+    assert np.abs(acc).max() == 8 * K
+    want = O.dequant_bf16(acc, np.ones(T, np.float32), np.ones(1, np.float32))
+    assert np.array_equal(host_bf16_bits(y), want)
+    # rows whose sums are exactly representable in bf16 pin the integers themselves
+    assert synth.bf16_bits_to_f32(host_bf16_bits(y))[0, 0] == -8.0 * K
+    assert synth.bf16_bits_to_f32(host_bf16_bits(y))[7, 1] == -7.0 * K
 
 
 @pytest.mark.parametrize("K", [384, 1536, 11008 // 128 * 128])
