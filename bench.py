@@ -67,14 +67,16 @@ def bench_prefill(args, hbl, synth, torch, np):
     cs = torch.empty(T, dtype=torch.int32, device="cuda")
     y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
     ws = hbl.alloc_workspace(T, K, N, bits)
+    # the code form hbl_hbitlinear_forward itself uses for this shape (INT4, T > 64, n = 16384 / 4096)
+    code_form = hbl.CODES_UINT4_PLUS8 if os.environ.get("HBL_NO_F6F4") else hbl.CODES_BF6
 
     def step_split(ev=None):
         if ev:
             ev[0].record()
-        hbl.fwht_quant_into(x, bits, site.hadamard, codes, sd, cs, eps, code_offset=8)
+        hbl.fwht_quant_into(x, bits, site.hadamard, codes, sd, cs, eps, code_offset=code_form)
         if ev:
             ev[1].record()
-        hbl.gemm_dequant_bf16(codes, sd, cs, packed, N, alphas, y=y, code_offset=8)
+        hbl.gemm_dequant_bf16(codes, sd, cs, packed, N, alphas, y=y, code_offset=code_form)
         if ev:
             ev[2].record()
 

@@ -52,8 +52,7 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     // cores (exact, twice the int8 MFMA rate).  HBL_NO_F6F4=1 keeps everything on the int8 path.
     static const bool no_f6f4 = getenv("HBL_NO_F6F4") != nullptr;
     if (!no_f6f4 && bf6_path_supported(T, K, bits, hadamard)) {
-        rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, kCodesBf6,
-                               s);
+        rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, kCodesBf6, s);
         if (rc != HBL_OK) return rc;
         return launch_ternary_gemm_f6f4(ws.codes, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, s);
     }

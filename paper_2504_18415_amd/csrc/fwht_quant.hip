@@ -621,7 +621,7 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
             const uint32_t bits = as_u(t + magic);
             packed |= (bits & 0xFFu) << (8 * e);
         }
-        isum = __builtin_amdgcn_sdot4((int)packed, 0x01010101, isum, false);   // += the 4 stored bytes
+        if (code_sum) isum = __builtin_amdgcn_sdot4((int)packed, 0x01010101, isum, false);   // += the 4 stored bytes
         if constexpr (!BF6OUT) {
             *reinterpret_cast<uint32_t*>(out + (LC::qj(j) << 2)) = packed;
         } else {
@@ -630,8 +630,9 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
             const uint32_t sel = packed & 0x07070707u;
             const uint32_t neg = __builtin_amdgcn_perm(0x2C303234u, 0x35363738u, sel);
             const uint32_t pos = __builtin_amdgcn_perm(0x17161514u, 0x12100C00u, sel);
-            const uint32_t is_pos = ((packed >> 3) & 0x01010101u) * 0xFFu;
-            const uint32_t r = (pos & is_pos) | (neg & ~is_pos);
+            // byte i of the result: byte i of `pos` if bit 3 of the index is set, else byte i of `neg`
+            const uint32_t pick = ((packed >> 1) & 0x04040404u) | 0x03020100u;
+            const uint32_t r = __builtin_amdgcn_perm(pos, neg, pick);
             // four 6-bit fields, one per byte -> 24 contiguous bits
             const uint32_t t2 = (r & 0x003F003Fu) | ((r & 0x3F003F00u) >> 2);
             c24[cbase ^ LC::qj(j)] = (t2 & 0xFFFu) | ((t2 >> 4) & 0xFFF000u);
@@ -650,20 +651,20 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
             dst[2] = (c.z >> 16) | (c.w << 8);
         }
     }
-    isum -= 64 * code_offset;
+    if (code_sum) {   // uniform: the fp6 x fp4 GEMM needs no code sum
+        isum -= 64 * code_offset;
 #pragma unroll
-    for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
-    if constexpr (W > 1) {
-        if (lane == 0) red_i[wave] = isum;
-        __syncthreads();
-        isum = 0;
+        for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
+        if constexpr (W > 1) {
+            if (lane == 0) red_i[wave] = isum;
+            __syncthreads();
+            isum = 0;
 #pragma unroll
-        for (int w = 0; w < W; ++w) isum += red_i[w];
+            for (int w = 0; w < W; ++w) isum += red_i[w];
+        }
+        if (tid == 0) code_sum[row] = isum;
     }
-    if (tid == 0) {
-        s_dequant[row] = s_d;
-        if (code_sum) code_sum[row] = isum;
-    }
+    if (tid == 0) s_dequant[row] = s_d;
 }
 
 template <int LOG2K, int BITS, bool BF16, bool BF6OUT = false>
