@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X published dense int8 (5.0 POP/s)
+F6F4_MFMA_PEAK_TOPS = 10100.0  # MI355X published dense fp6 / fp4 (10.1 PFLOP/s)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
 
@@ -221,19 +222,25 @@ def main():
     torch.cuda.set_device(0)
 
     pre, site, x_host, W_host = bench_prefill(args, hbl, synth, torch, np)
+    int8_path = bool(os.environ.get("HBL_NO_F6F4"))
+    gemm_peak = INT8_MFMA_PEAK_TOPS if int8_path else F6F4_MFMA_PEAK_TOPS
     result = {
         "metric": "H-BitLinear TOPS (INT4 acts)", "value": pre["tops_end_to_end"], "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": pre["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i8" if int8_path else "bf6 x fp4 (exact small integers), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"config 4 (7B prefill) {site.name}: X bf16 [{site.T}x{site.K}] -> {site.N}, "
                                f"Hadamard n={site.K}, INT4 activations, 2-bit packed ternary W",
                    "T": site.T, "K": site.K, "N": site.N, "bits": 4},
         "frac_int8_mfma_peak_end_to_end": pre["tops_end_to_end"] / INT8_MFMA_PEAK_TOPS,
-        "roofline": {"kernel": "ternary_gemm_kernel (GEMM + dequant epilogue)", "bound": "mfma",
-                     "achieved": pre["tops_gemm"], "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": pre["tops_gemm"] / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                     "avg_kernel_ms": pre["ms_gemm"]},
+        # the GEMM's own dtype sets its roofline; the benchmark's target is quoted against the int8 peak,
+        # so that fraction is given too
+        "roofline": {"kernel": "ternary_gemm_kernel (int8 MFMA)" if int8_path
+                               else "ternary_gemm_f6f4_kernel (fp6 x fp4 MFMA, GEMM + dequant epilogue)",
+                     "bound": "mfma", "achieved": pre["tops_gemm"], "peak": gemm_peak, "unit": "TOP/s",
+                     "frac": pre["tops_gemm"] / gemm_peak, "traffic": None, "avg_kernel_ms": pre["ms_gemm"],
+                     "frac_of_int8_mfma_peak": pre["tops_gemm"] / INT8_MFMA_PEAK_TOPS},
         "fwht_quant": {"avg_kernel_ms": pre["ms_fwht_quant"], "bound": "hbm", "achieved": pre["fwht_quant_gbs"],
                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pre["fwht_quant_gbs"] / HBM_PEAK_GBS},
         "ms_single_call": pre["ms_single_call"],

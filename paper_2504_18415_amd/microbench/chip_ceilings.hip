@@ -1,0 +1,134 @@
+// Stand-alone micro-benchmarks of what one MI355X sustains, used to put the library's kernels in
+// context (the design doc quotes the figures): matrix-core rate with register-resident operands for the
+// two MFMA forms the GEMM kernels use, by operand bit pattern, and HBM read / copy bandwidth.
+// Build and run:  python -m paper_2504_18415_amd.microbench
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+#define CHECK(x)                                                                  \
+    do {                                                                          \
+        hipError_t e_ = (x);                                                      \
+        if (e_ != hipSuccess) {                                                   \
+            fprintf(stderr, "%s failed: %s\n", #x, hipGetErrorString(e_));        \
+            exit(1);                                                              \
+        }                                                                         \
+    } while (0)
+
+__device__ unsigned lcg(unsigned& h) { return h = h * 1664525u + 1013904223u; }
+
+// 16 independent 32x32x32 int8 MFMAs per iteration and wave, operands fixed in registers
+__global__ __launch_bounds__(256) void mfma_i8_kernel(int* out, int iters, unsigned mask_a, unsigned mask_b) {
+    unsigned h = (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u);
+    v4i a[4], b[4];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j) {
+            a[i][j] = (int)(lcg(h) & mask_a);
+            b[i][j] = (int)(lcg(h) & mask_b);
+        }
+    v16i acc[16];
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
+    }
+    int s = 0;
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// 16 independent 32x32x64 f8f6f4 MFMAs per iteration and wave: A = fp4 (e2m1), B = bf6 (e3m2)
+__global__ __launch_bounds__(256) void mfma_f6f4_kernel(float* out, int iters, unsigned mask_a, unsigned mask_b) {
+    unsigned h = (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u);
+    v8i a[4], b[4];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 8; ++j) {
+            a[i][j] = (int)(lcg(h) & mask_a);
+            b[i][j] = (int)(lcg(h) & mask_b);
+        }
+    v16f acc[16];
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i & 3], b[i >> 2], acc[i], 4, 3, 0, 0, 0, 0);
+    }
+    float s = 0;
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src, size_t n, uint4* sink) {
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const uint4 v = src[i];
+        acc.x ^= v.x; acc.y ^= v.y; acc.z ^= v.z; acc.w ^= v.w;
+    }
+    if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u) *sink = acc;   // never true in practice: keeps the loads
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+template <class F>
+float time_ms(F launch, int reps) {
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    launch();
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipEventRecord(e0));
+    for (int i = 0; i < reps; ++i) launch();
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms;
+    CHECK(hipEventElapsedTime(&ms, e0, e1));
+    CHECK(hipEventDestroy(e0));
+    CHECK(hipEventDestroy(e1));
+    return ms / reps;
+}
+
+int main() {
+    const int blocks = 512, iters = 4096;
+    void* out;
+    CHECK(hipMalloc(&out, (size_t)blocks * 256 * 4));
+    struct { const char* name; unsigned ma, mb; } i8[] = {
+        {"int8 32x32x32  zeros", 0u, 0u},
+        {"int8 32x32x32  4-bit unsigned x {0,1,2}", 0x0F0F0F0Fu, 0x03030303u},
+        {"int8 32x32x32  random int8 x {0,1,2}", 0xFFFFFFFFu, 0x03030303u},
+        {"int8 32x32x32  random int8 x int8", 0xFFFFFFFFu, 0xFFFFFFFFu}};
+    for (auto& p : i8) {
+        const float ms = time_ms([&] { mfma_i8_kernel<<<blocks, 256>>>((int*)out, iters, p.ma, p.mb); }, 1);
+        printf("%-48s %8.1f TOP/s\n", p.name, (double)blocks * 4 * iters * 16 * 65536.0 / ms / 1e9);
+    }
+    struct { const char* name; unsigned ma, mb; } f6[] = {
+        {"f8f6f4 32x32x64  fp4 x bf6 zeros", 0u, 0u},
+        {"f8f6f4 32x32x64  fp4 {0,+-1} x bf6 random", 0xAAAAAAAAu, 0xFFFFFFFFu},
+        {"f8f6f4 32x32x64  fp4 x bf6 random bits", 0xFFFFFFFFu, 0xFFFFFFFFu}};
+    for (auto& p : f6) {
+        const float ms = time_ms([&] { mfma_f6f4_kernel<<<blocks, 256>>>((float*)out, iters, p.ma, p.mb); }, 1);
+        printf("%-48s %8.1f TOP/s\n", p.name, (double)blocks * 4 * iters * 16 * 131072.0 / ms / 1e9);
+    }
+    const size_t bytes = (size_t)2 << 30;   // 2 GiB: far larger than the 256 MB memory-side cache
+    uint4 *src, *dst;
+    CHECK(hipMalloc(&src, bytes));
+    CHECK(hipMalloc(&dst, bytes));
+    CHECK(hipMemset(src, 1, bytes));
+    CHECK(hipMemset(dst, 0, bytes));
+    const float r = time_ms([&] { read_kernel<<<4096, 256>>>(src, bytes / 16, dst); }, 5);
+    printf("%-48s %8.1f GB/s\n", "HBM read stream, 2 GiB", bytes / r / 1e6);
+    const float c = time_ms([&] { copy_kernel<<<4096, 256>>>(src, dst, bytes / 16); }, 5);
+    printf("%-48s %8.1f GB/s (read + write)\n", "HBM copy, 2 GiB -> 2 GiB", 2.0 * bytes / c / 1e6);
+    return 0;
+}
