@@ -52,7 +52,7 @@ extern "C" {
 /* forms in which the quantised activation codes travel between the two launches (stage-level calls) */
 #define HBL_CODES_INT8 0        /* one signed byte per code                                              */
 #define HBL_CODES_UINT4_PLUS8 8 /* INT4 only: byte = code + 8 in 0..15                                   */
-#define HBL_CODES_BF6 6         /* INT4 only, Hadamard with K in {4096, 8192, 16384}: per 32 features a
+#define HBL_CODES_BF6 6         /* INT4 only, K >= 512: per 32 features a
                                    32-byte record, first 24 bytes = the 32 codes as 6-bit floats (e3m2,
                                    feature i at bits [6i, 6i+6)), every integer in [-8, 7] exact          */
 
@@ -149,8 +149,8 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
  *              path, because unsigned nibbles toggle far fewer multiplier input bits than
  *              sign-extended bytes and the matrix cores are power-limited (the GEMM epilogue removes
  *              the offset exactly in int32); HBL_CODES_BF6 writes the records the fp6 x fp4
- *              matrix-core path reads - the form the forward calls use for INT4 when T > 64 and the
- *              Hadamard size is 4096, 8192 or 16384.
+ *              matrix-core path reads - the form the forward calls use for INT4 when T > 64 and
+ *              K >= 512.
  *   codes      [T, K] int8 out in natural feature order
  *   s_dequant  [T] fp32 out: gamma/127 or beta/sqrt7
  *   code_sum   [T] int32 out or NULL: sum_k code[t][k] of the true codes (without the offset)

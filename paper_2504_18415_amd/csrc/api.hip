@@ -48,8 +48,8 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     if (workspace_bytes < hbl_workspace_bytes(T, K, N, bits)) return HBL_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Workspace ws = carve_workspace(workspace, T, K, N);
-    // INT4 at prefill sizes behind a large Hadamard transform: bf6 code records and the fp6 x fp4 matrix
-    // cores (exact, twice the int8 MFMA rate).  HBL_NO_F6F4=1 keeps everything on the int8 path.
+    // INT4 at prefill sizes: bf6 code records and the fp6 x fp4 matrix cores (exact, twice the int8
+    // MFMA rate).  HBL_NO_F6F4=1 keeps everything on the int8 path.
     static const bool no_f6f4 = getenv("HBL_NO_F6F4") != nullptr;
     if (!no_f6f4 && bf6_path_supported(T, K, bits, hadamard)) {
         rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, kCodesBf6, s);
@@ -146,7 +146,7 @@ int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, f
                    int code_offset, int8_t* codes, float* s_dequant, int32_t* code_sum, void* stream) {
     if (code_offset != HBL_CODES_INT8 && !((code_offset == HBL_CODES_UINT4_PLUS8 || code_offset == HBL_CODES_BF6) && bits == 4))
         return HBL_E_BITS;
-    if (code_offset == HBL_CODES_BF6 && !(hadamard && (K == 4096 || K == 8192 || K == 16384))) return HBL_E_SHAPE;
+    if (code_offset == HBL_CODES_BF6 && K < 512) return HBL_E_SHAPE;
     if (bits != 4 && bits != 8) return HBL_E_BITS;
     if (x_dtype != HBL_F32 && x_dtype != HBL_BF16) return HBL_E_DTYPE;
     int rc = check_gemm_shape(T, K, 32, hadamard != 0);

@@ -96,6 +96,36 @@ __device__ __forceinline__ void load_chunk(const void* x, int64_t off, float (&d
     }
 }
 
+// Four stored bytes code + 8 (0..15) -> their bf6 (e3m2) bit patterns, 6 bits each, as 24 contiguous
+// bits.  Two 8-entry byte-permute look-ups and a select:
+//   -8..-5 = 38 37 36 35, -4..-1 = 34 32 30 2c, 0..3 = 00 0c 10 12, 4..7 = 14 15 16 17 (hex)
+__device__ __forceinline__ uint32_t bf6_pack4(uint32_t packed) {
+    const uint32_t sel = packed & 0x07070707u;
+    const uint32_t neg = __builtin_amdgcn_perm(0x2C303234u, 0x35363738u, sel);
+    const uint32_t pos = __builtin_amdgcn_perm(0x17161514u, 0x12100C00u, sel);
+    // byte i of the result: byte i of `pos` if bit 3 of the index is set, else byte i of `neg`
+    const uint32_t pick = ((packed >> 1) & 0x04040404u) | 0x03020100u;
+    const uint32_t r = __builtin_amdgcn_perm(pos, neg, pick);
+    // four 6-bit fields, one per byte -> 24 contiguous bits
+    const uint32_t t2 = (r & 0x003F003Fu) | ((r & 0x3F003F00u) >> 2);
+    return (t2 & 0xFFFu) | ((t2 >> 4) & 0xFFF000u);
+}
+
+// bf6 record output for a lane that holds the 8 features of chunk `chunk8` of its row as two 24-bit
+// halves, where neighbouring lanes hold neighbouring chunks: the even lane of each pair fetches its
+// partner's halves and writes the pair's 16 features as three dwords.  A record covers 32 features
+// (four chunks) in 32 bytes, the last 8 of them unused.  Every lane of a quad must call this.
+__device__ __forceinline__ void bf6_store_pair(int8_t* row_codes, int chunk8, uint32_t lo, uint32_t hi) {
+    const uint32_t p_lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)lo, 0xB1, 0xF, 0xF, false);   // lane ^ 1
+    const uint32_t p_hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)hi, 0xB1, 0xF, 0xF, false);
+    if ((chunk8 & 1) == 0) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(row_codes + 32 * (chunk8 >> 2) + 12 * ((chunk8 >> 1) & 1));
+        dst[0] = lo | (hi << 24);
+        dst[1] = (hi >> 8) | (p_lo << 16);
+        dst[2] = (p_lo >> 16) | (p_hi << 8);
+    }
+}
+
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
 __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restrict__ x, int8_t* __restrict__ codes,
                                                             float* __restrict__ s_dequant,
@@ -242,6 +272,9 @@ __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restri
     // leaves its two's complement in the low mantissa bits
     constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
     constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
+    // bf6 records (INT4, 8-element chunks only; the launcher rejects the rest) are built from code + 8
+    const bool bf6 = BITS == 4 && CH == 8 && code_offset == kCodesBf6;
+    if (bf6) code_offset = 8;
     // stored byte = code + code_offset: folding the offset into the rounding constant costs nothing
     const float magic = kMagic + (float)code_offset;
     int isum = 0;
@@ -267,7 +300,8 @@ __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restri
         }
         int8_t* dst = codes + row_off + (int64_t)(g * 64 + lane) * CH;
         if constexpr (CH == 8) {
-            *reinterpret_cast<uint2*>(dst) = make_uint2(packed[0], packed[1]);
+            if (bf6) bf6_store_pair(codes + row_off, g * 64 + lane, bf6_pack4(packed[0]), bf6_pack4(packed[1]));
+            else *reinterpret_cast<uint2*>(dst) = make_uint2(packed[0], packed[1]);
         } else if constexpr (CH == 4) {
             *reinterpret_cast<uint32_t*>(dst) = packed[0];
         } else if constexpr (CH == 2) {
@@ -366,6 +400,8 @@ __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restri
     }
     constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
     constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
+    const bool bf6 = BITS == 4 && code_offset == kCodesBf6;   // bf6 records are built from code + 8
+    if (bf6) code_offset = 8;
     // stored byte = code + code_offset: folding the offset into the rounding constant costs nothing
     const float magic = kMagic + (float)code_offset;
     int isum = 0;
@@ -381,7 +417,9 @@ __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restri
                 isum += (int)(bits - as_u(magic));
                 packed[e / 4] |= (bits & 0xFFu) << (8 * (e % 4));
             }
-            *reinterpret_cast<uint2*>(codes + row_off + (int64_t)ch * 8) = make_uint2(packed[0], packed[1]);
+            // K / 8 is a multiple of 16: the lanes of a quad are in or out of this branch together
+            if (bf6) bf6_store_pair(codes + row_off, ch, bf6_pack4(packed[0]), bf6_pack4(packed[1]));
+            else *reinterpret_cast<uint2*>(codes + row_off + (int64_t)ch * 8) = make_uint2(packed[0], packed[1]);
         }
     }
 #pragma unroll
@@ -625,17 +663,7 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
         if constexpr (!BF6OUT) {
             *reinterpret_cast<uint32_t*>(out + (LC::qj(j) << 2)) = packed;
         } else {
-            // bytes code+8 in 0..15 -> bf6 bit patterns by two 8-entry byte-permute look-ups:
-            // -8..-5 = 38 37 36 35, -4..-1 = 34 32 30 2c, 0..3 = 00 0c 10 12, 4..7 = 14 15 16 17 (hex)
-            const uint32_t sel = packed & 0x07070707u;
-            const uint32_t neg = __builtin_amdgcn_perm(0x2C303234u, 0x35363738u, sel);
-            const uint32_t pos = __builtin_amdgcn_perm(0x17161514u, 0x12100C00u, sel);
-            // byte i of the result: byte i of `pos` if bit 3 of the index is set, else byte i of `neg`
-            const uint32_t pick = ((packed >> 1) & 0x04040404u) | 0x03020100u;
-            const uint32_t r = __builtin_amdgcn_perm(pos, neg, pick);
-            // four 6-bit fields, one per byte -> 24 contiguous bits
-            const uint32_t t2 = (r & 0x003F003Fu) | ((r & 0x3F003F00u) >> 2);
-            c24[cbase ^ LC::qj(j)] = (t2 & 0xFFFu) | ((t2 >> 4) & 0xFFF000u);
+            c24[cbase ^ LC::qj(j)] = bf6_pack4(packed);
         }
     }
     if constexpr (BF6OUT) {
@@ -719,8 +747,8 @@ int dispatch(const void* x, int x_dtype, int64_t T, int bits, float eps, bool ha
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     if (T == 0) return HBL_OK;
+    if (code_offset == kCodesBf6 && (bits != 4 || K < 512)) return HBL_E_SHAPE;   // records need 8-element chunks
     if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
-    if (code_offset == kCodesBf6 && !(hadamard && (K == 4096 || K == 8192 || K == 16384))) return HBL_E_SHAPE;
     if (hadamard && (code_offset == kCodesBf6 || !getenv("HBL_FWHT_OLD"))) {
         if (K == 4096) return dispatch_bigrow<12>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
         if (K == 8192) return dispatch_bigrow<13>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);

@@ -62,10 +62,11 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
 
 // Launchers (defined in the .hip files). All validate nothing: callers in api.hip do.
 // Codes are stored as code + code_offset (0, or 8 for INT4 so that the stored bytes are 0..15), or -
-// code_offset == kCodesBf6 - as bf6 records (see fwht_quant.hip; Hadamard with K in {4096, 8192, 16384}).
+// code_offset == kCodesBf6 - as bf6 records (see fwht_quant.hip; INT4 with K >= 512).
 constexpr int kCodesBf6 = 6;
 inline bool bf6_path_supported(int64_t T, int64_t K, int bits, bool hadamard) {
-    return bits == 4 && hadamard && T > 64 && (K == 4096 || K == 8192 || K == 16384);
+    (void)hadamard;
+    return bits == 4 && T > 64 && K >= 512;
 }
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream);

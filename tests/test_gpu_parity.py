@@ -234,32 +234,38 @@ def decode_bf6_records(rec, K):
     return out.reshape(T, K)
 
 
-@pytest.mark.parametrize("K", [4096, 8192, 16384])
-def test_bf6_code_records_and_f6f4_gemm(hbl, K):
-    """INT4 codes as 6-bit float records (the form the fp6 x fp4 matrix-core path reads): the decoded
-    records equal the oracle codes, and the two-launch split on that path reproduces the oracle's
-    outputs and the int8 path bit for bit."""
-    note(f"bf6 records K={K}")
+@pytest.mark.parametrize("K,hadamard", [(4096, True), (8192, True), (16384, True), (512, True), (1024, True),
+                                        (2048, True), (2048, False), (4096, False), (16384, False),
+                                        (640, False), (1536, False), (11008, False)])
+def test_bf6_code_records_and_f6f4_gemm(hbl, K, hadamard):
+    """INT4 codes as 6-bit float records (the form the fp6 x fp4 matrix-core path reads), from every
+    quantiser kernel that writes them: the decoded records equal the oracle codes, and the two-launch
+    split on that path reproduces the oracle's outputs and the int8 path bit for bit."""
+    note(f"bf6 records K={K} hadamard={hadamard}")
     T, N = 150, 288
-    site = synth.Site("a", T, K, N, outlier_frac=0.01, outlier_scale=30.0, seed=K + 6)
+    site = synth.Site("a", T, K, N, hadamard=hadamard, outlier_frac=0.01, outlier_scale=30.0, seed=K + 6)
     x = synth.make_x(site)
-    c_ref, s_ref = O.fwht_quant(x, 4, hadamard=True, eps=EPS)
+    c_ref, s_ref = O.fwht_quant(x, 4, hadamard=hadamard, eps=EPS)
     xd = dev_x(x)
-    rec, sd, cs = hbl.fwht_quant(xd, 4, True, EPS, code_offset=hbl.CODES_BF6)
+    rec, sd, cs = hbl.fwht_quant(xd, 4, hadamard, EPS, code_offset=hbl.CODES_BF6)
     assert np.array_equal(decode_bf6_records(rec.cpu().numpy().view(np.uint8), K), c_ref.astype(np.int32))
     assert np.array_equal(sd.cpu().numpy(), s_ref)
     assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
     wc_ref, al_ref, wc_d, al_d, packed = setup_weights(hbl, site)
     y6 = hbl.gemm_dequant_bf16(rec, sd, cs, packed, N, al_d, code_offset=hbl.CODES_BF6)
-    c8, sd8, cs8 = hbl.fwht_quant(xd, 4, True, EPS, code_offset=8)
+    c8, sd8, cs8 = hbl.fwht_quant(xd, 4, hadamard, EPS, code_offset=8)
     y8 = hbl.gemm_dequant_bf16(c8, sd8, cs8, packed, N, al_d, code_offset=8)
-    y1 = hbl.hbitlinear_forward(xd, packed, N, al_d, 4, EPS)
-    y_ref = O.hbitlinear_forward(x, wc_ref, al_ref, 4, EPS)
+    fn = hbl.hbitlinear_forward if hadamard else hbl.plain_bitlinear_forward
+    y1 = fn(xd, packed, N, al_d, 4, EPS)
+    y_ref = O.bitlinear_forward(x, wc_ref, al_ref, 4, hadamard, EPS)
     assert np.array_equal(host_bf16_bits(y6), y_ref)
     assert np.array_equal(host_bf16_bits(y8), y_ref)
     assert np.array_equal(host_bf16_bits(y1), y_ref)
+    # records need 8-element chunks per lane: rows shorter than 512 and INT8 codes are rejected
     with pytest.raises(hbl.HblError):
-        hbl.fwht_quant(xd[:, :2048].contiguous(), 4, True, EPS, code_offset=hbl.CODES_BF6)
+        hbl.fwht_quant(xd[:, :256].contiguous(), 4, hadamard, EPS, code_offset=hbl.CODES_BF6)
+    with pytest.raises(hbl.HblError):
+        hbl.fwht_quant(xd, 8, hadamard, EPS, code_offset=hbl.CODES_BF6)
 
 
 BF6_OF_CODE = {-8: 0x38, -7: 0x37, -6: 0x36, -5: 0x35, -4: 0x34, -3: 0x32, -2: 0x30, -1: 0x2C, 0: 0x00,
