@@ -163,48 +163,68 @@ def bench_decode(args, hbl, synth, torch, np):
         xs = [to_dev(torch, np, synth.make_x(s)) for s in sites]
         ys = [torch.empty((B, s.N), dtype=torch.bfloat16, device="cuda") for s in sites]
         wss = [hbl.alloc_workspace(B, s.K, s.N, bits) for s in sites]
+        # grouped form: the four projections of a layer (independent inputs here) in one call
+        items = [[(xs[i], packed[l][i], s.N, alphas[i], bits, s.hadamard, ys[i]) for i, s in enumerate(sites)]
+                 for l in range(layers)]
+        probs = [hbl.make_problems(it) for it in items]
+        gws = torch.empty(hbl.grouped_workspace_bytes(probs[0], len(sites)), dtype=torch.uint8, device="cuda")
 
-        def layer(l):
+        def layer_sequential(l):
             for i, s in enumerate(sites):
                 fn = hbl.hbitlinear_forward if s.hadamard else hbl.plain_bitlinear_forward
                 fn(xs[i], packed[l][i], s.N, alphas[i], bits, eps, y=ys[i], workspace=wss[i])
 
-        for l in range(layers):
-            layer(l)
-        torch.cuda.synchronize()
-        # one HIP graph of all layers (8 kernel nodes per layer, no memset nodes), replayed
-        graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                for l in range(layers):
-                    layer(l)
-        torch.cuda.synchronize()
-        y_eager = [y.clone() for y in ys]
-        graph.replay()
-        torch.cuda.synchronize()
-        assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(y_eager, ys)), \
-            "graph replay differs from eager"
-        reps = 5
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            graph.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        us_layer = e0.elapsed_time(e1) * 1e3 / (reps * layers)
-        e0.record()
-        for l in range(layers):
-            layer(l)
-        e1.record()
-        torch.cuda.synchronize()
-        us_layer_eager = e0.elapsed_time(e1) * 1e3 / layers
+        def layer_grouped(l):
+            hbl.bitlinear_forward_grouped(items[l], eps, workspace=gws, problems=probs[l])
+
         io_bytes = sum(2 * B * s.K + 2 * B * s.N for s in sites)
-        gbs = (w_bytes + io_bytes) / (us_layer * 1e-6) / 1e9
-        res[str(B)] = {"us_per_layer": us_layer, "us_per_layer_eager": us_layer_eager, "GBps": gbs,
-                       "frac_hbm_peak": gbs / HBM_PEAK_GBS}
-    return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes, "launch": "one HIP graph of all layers, 8 kernel nodes per layer (4 projections x [quantiser, GEMM])",
+        entry = {}
+        y_first = None
+        for mode, layer in (("sequential", layer_sequential), ("grouped", layer_grouped)):
+            for l in range(layers):
+                layer(l)
+            torch.cuda.synchronize()
+            # one HIP graph of all layers (kernel nodes only, no memset nodes), replayed
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    for l in range(layers):
+                        layer(l)
+            torch.cuda.synchronize()
+            y_eager = [y.clone() for y in ys]
+            graph.replay()
+            torch.cuda.synchronize()
+            assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(y_eager, ys)), \
+                "graph replay differs from eager"
+            if y_first is None:
+                y_first = y_eager
+            else:   # both forms end on the last layer's weights: identical outputs
+                assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(y_first, ys)), \
+                    "grouped call differs from the per-projection calls"
+            reps = 5
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            us_layer = e0.elapsed_time(e1) * 1e3 / (reps * layers)
+            e0.record()
+            for l in range(layers):
+                layer(l)
+            e1.record()
+            torch.cuda.synchronize()
+            us_layer_eager = e0.elapsed_time(e1) * 1e3 / layers
+            gbs = (w_bytes + io_bytes) / (us_layer * 1e-6) / 1e9
+            entry[mode] = {"us_per_layer": us_layer, "us_per_layer_eager": us_layer_eager, "GBps": gbs,
+                           "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+        res[str(B)] = entry
+    return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes,
+            "launch": "one HIP graph of all layers; sequential = four forward calls per layer in model order "
+                      "(2-3 kernel nodes each), grouped = one hbl_bitlinear_forward_grouped call per layer "
+                      "(one quantiser launch, one weight-streaming GEMM launch, one reduction launch for batch > 16)",
             "batch": res}
 
 

@@ -138,6 +138,36 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
                                 int64_t n_scale_groups, int bits, float eps, void* y,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Several independent projections in one call (Eq. 7 applied to each): the result in every y is
+ * bit-identical to hbl_hbitlinear_forward / hbl_plain_bitlinear_forward on that problem alone.
+ * Meant for small batches (decode), where one projection's launches are too short to keep HBM
+ * busy: when every T <= 64, n_problems <= 8 and all problems share bits and x_dtype, the rows of
+ * all problems are quantised by one launch and all packed weights are streamed by one launch
+ * (plus one reduction launch for 16 < T <= 64 when a K range is split); otherwise the problems
+ * run one after the other through the calls above.
+ *   problems   host array, read during the call only; fields as the arguments of the forward
+ *              calls above (hadamard != 0 selects H-BitLinear, eps is shared)
+ *   workspace  device, >= hbl_grouped_workspace_bytes(problems, n_problems), 256-byte aligned
+ * The problems must not overlap: no y may alias another problem's x or y.
+ * Returns the first error of any problem (nothing is launched then) or of a launch.
+ */
+typedef struct hbl_problem {
+    const void* x;          /* device [T, K], row-major, x_dtype                       */
+    int x_dtype;            /* HBL_F32 or HBL_BF16                                     */
+    int bits;               /* 4 or 8                                                  */
+    int hadamard;           /* 0: plain BitLinear, else H-BitLinear (K a power of two) */
+    int reserved;           /* set to 0                                                */
+    int64_t T, K, N;
+    const void* Wq_packed;  /* device, from hbl_pack_ternary_2bit                      */
+    const float* w_scales;  /* device [n_scale_groups]                                 */
+    int64_t n_scale_groups;
+    void* y;                /* device [T, N] bf16 out                                  */
+} hbl_problem;
+size_t hbl_grouped_workspace_bytes(const hbl_problem* problems, int n_problems);
+int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, float eps,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Stage-level entry points (parity checks and profiling; same kernels)
  * ------------------------------------------------------------------------- */

@@ -32,9 +32,10 @@ int check_gemm_shape(int64_t T, int64_t K, int64_t N, bool hadamard) {
     return HBL_OK;
 }
 
-int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
-            const float* w_scales, int64_t groups, int bits, float eps, void* y, void* workspace,
-            size_t workspace_bytes, void* stream, bool hadamard) {
+// Argument checks of one forward problem (everything but the workspace size).
+int check_forward_args(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+                       const float* w_scales, int64_t groups, int bits, const void* y, const void* workspace,
+                       bool hadamard) {
     if (bits != 4 && bits != 8) return HBL_E_BITS;
     if (x_dtype != HBL_F32 && x_dtype != HBL_BF16) return HBL_E_DTYPE;
     int rc = check_gemm_shape(T, K, N, hadamard);
@@ -45,6 +46,33 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     if (!aligned16(x) || !aligned16(Wq_packed) || !aligned16(y) ||
         (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
         return HBL_E_ALIGN;
+    return HBL_OK;
+}
+
+void fill_decode_problem(DecodeProblem& dp, const Workspace& ws, int32_t* partial, int64_t T, int64_t K,
+                         const void* Wq_packed, int64_t N, const float* w_scales, int64_t groups, int code_offset,
+                         void* y) {
+    dp.codes = ws.codes;
+    dp.packed = static_cast<const uint32_t*>(Wq_packed);
+    dp.s_dequant = ws.s_dequant;
+    dp.code_sum = ws.code_sum;
+    dp.w_row_sum = reinterpret_cast<const int32_t*>(static_cast<const char*>(Wq_packed) + packed_tile_bytes(N, K));
+    dp.w_scales = w_scales;
+    dp.y = static_cast<uint16_t*>(y);
+    dp.partial = partial;
+    dp.T = (int)T;
+    dp.K = (int)K;
+    dp.N = (int)N;
+    dp.rows_per_group = (int)(N / groups);
+    dp.code_offset = code_offset;
+}
+
+int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+            const float* w_scales, int64_t groups, int bits, float eps, void* y, void* workspace,
+            size_t workspace_bytes, void* stream, bool hadamard) {
+    int rc = check_forward_args(x, x_dtype, T, K, Wq_packed, N, w_scales, groups, bits, y, workspace, hadamard);
+    if (rc != HBL_OK) return rc;
+    if (T == 0) return HBL_OK;
     if (workspace_bytes < hbl_workspace_bytes(T, K, N, bits)) return HBL_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Workspace ws = carve_workspace(workspace, T, K, N);
@@ -60,8 +88,24 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     const int code_offset = bits == 4 ? 8 : 0;
     rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, code_offset, s);
     if (rc != HBL_OK) return rc;
+    static const bool no_stream = getenv("HBL_NO_DECODE_STREAM") != nullptr;
+    if (!no_stream && decode_stream_preferred(T, K, N)) {   // a handful of tokens: one weight-streaming launch
+        DecodeArgs da = {};
+        da.n = 1;
+        fill_decode_problem(da.p[0], ws, nullptr, T, K, Wq_packed, N, w_scales, groups, code_offset, y);
+        return launch_decode_gemm(da, s);
+    }
     return launch_ternary_gemm(ws.codes, code_offset, T, K, Wq_packed, N, ws.s_dequant, ws.code_sum, w_scales, groups,
                                y, nullptr, ws.partial, s);
+}
+
+// Workspace region of one problem of a grouped call: large enough for the grouped launches (partials
+// for the largest K split they may choose) and for the stand-alone forward call.
+size_t group_region_bytes(const hbl_problem& q) {
+    if (q.T <= 0 || q.K <= 0 || q.N <= 0) return 256;
+    size_t b = carve_workspace(nullptr, q.T, q.K, q.N).bytes;
+    if (q.T <= 64) b += round_up((size_t)kMaxDecodeSplit * q.T * q.N * sizeof(int32_t), 256);
+    return b;
 }
 
 }  // namespace
@@ -140,6 +184,77 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
                                 void* workspace, size_t workspace_bytes, void* stream) {
     return forward(x, x_dtype, T, K, Wq_packed, N, w_scales, n_scale_groups, bits, eps, y, workspace,
                    workspace_bytes, stream, false);
+}
+
+size_t hbl_grouped_workspace_bytes(const hbl_problem* problems, int n_problems) {
+    size_t total = 256;
+    if (!problems) return total;
+    for (int i = 0; i < n_problems; ++i) total += group_region_bytes(problems[i]);
+    return total;
+}
+
+int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, float eps, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+    if (n_problems < 0) return HBL_E_SHAPE;
+    if (n_problems == 0) return HBL_OK;
+    if (!problems) return HBL_E_NULL;
+    bool grouped = n_problems <= kMaxGroup;
+    bool any_rows = false;
+    for (int i = 0; i < n_problems; ++i) {
+        const hbl_problem& q = problems[i];
+        const int rc = check_forward_args(q.x, q.x_dtype, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups,
+                                          q.bits, q.y, workspace, q.hadamard != 0);
+        if (rc != HBL_OK) return rc;
+        if (q.T > 64 || q.bits != problems[0].bits || q.x_dtype != problems[0].x_dtype) grouped = false;
+        any_rows = any_rows || q.T > 0;
+    }
+    if (!any_rows) return HBL_OK;
+    if (!workspace) return HBL_E_NULL;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return HBL_E_ALIGN;
+    if (workspace_bytes < hbl_grouped_workspace_bytes(problems, n_problems)) return HBL_E_WORKSPACE;
+    char* base = static_cast<char*>(workspace);
+    if (!grouped) {
+        for (int i = 0; i < n_problems; ++i) {
+            const hbl_problem& q = problems[i];
+            const size_t region = group_region_bytes(q);
+            const int rc = forward(q.x, q.x_dtype, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups, q.bits, eps,
+                                   q.y, base, region, stream, q.hadamard != 0);
+            if (rc != HBL_OK) return rc;
+            base += region;
+        }
+        return HBL_OK;
+    }
+    QuantGroupArgs qa = {};
+    DecodeArgs da = {};
+    qa.eps = eps;
+    int rows = 0;
+    for (int i = 0; i < n_problems; ++i) {
+        const hbl_problem& q = problems[i];
+        const size_t region = group_region_bytes(q);
+        if (q.T > 0) {
+            const Workspace ws = carve_workspace(base, q.T, q.K, q.N);
+            int32_t* partial = reinterpret_cast<int32_t*>(base + carve_workspace(nullptr, q.T, q.K, q.N).bytes);
+            const int code_offset = q.bits == 4 ? 8 : 0;   // INT4 codes travel as code + 8 (bytes 0..15)
+            QuantProblem& qp = qa.p[qa.n++];
+            qp.x = q.x;
+            qp.codes = ws.codes;
+            qp.s_dequant = ws.s_dequant;
+            qp.code_sum = ws.code_sum;
+            qp.T = (int)q.T;
+            qp.K = (int)q.K;
+            qp.hadamard = q.hadamard != 0;
+            qp.code_offset = code_offset;
+            qp.row_begin = rows;
+            rows += (int)q.T;
+            fill_decode_problem(da.p[da.n++], ws, partial, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups,
+                                code_offset, q.y);
+        }
+        base += region;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int rc = launch_quant_grouped(qa, problems[0].bits, problems[0].x_dtype, s);
+    if (rc != HBL_OK) return rc;
+    return launch_decode_gemm(da, s);
 }
 
 int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int hadamard,

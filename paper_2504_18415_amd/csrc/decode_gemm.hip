@@ -1,0 +1,362 @@
+// Small-batch (decode) form of the ternary GEMM of Eq. 7: T <= 64 tokens, so the packed weights are
+// read once from HBM and dominate the traffic, and the job is to keep as many weight tiles in flight as
+// the memory system needs.  One launch serves up to kMaxGroup independent projections.
+//
+// A wave owns one 32-row weight tile at a time and walks its K range tile by tile (1 KiB of packed
+// weights = 32 rows x 128 features).  Weights and activation codes both arrive by direct global->LDS
+// copies, D stages deep per wave; per stage a wave expands the 16 packed bytes of each lane into four
+// int8 operands (code + 1, as in the large-T kernel; the epilogue removes the offset in int32) and
+// issues 4 (or 8) 32x32x32 int8 MFMAs.
+//
+// Two forms:
+//  - streaming (T <= 16): a wave's code stage is private (8 or 16 rows x 128 B), so the waves never
+//    meet at a barrier.  The K range of one row tile may be split over the 2 or 4 waves of a workgroup;
+//    their int32 accumulators are added through LDS at the end (exact).
+//  - shared (T <= 64): the four waves take four row tiles over one K range and share the code stage
+//    (32 or 64 rows x 128 B): one barrier per stage.  A K range split over workgroups leaves int32
+//    partial tiles that a second launch adds and dequantises.
+#include <stdlib.h>
+
+#include <atomic>
+
+#include "gemm_common.h"
+
+namespace hbl {
+namespace {
+
+using namespace gemm;
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// 16 packed weights -> four registers of four bytes, byte = code + 1 in {0, 1, 2}.
+__device__ __forceinline__ v4i expand_plus1(uint32_t p) {
+    v4i r;
+    r[0] = (int)(p & 0x03030303u);
+    r[1] = (int)((p >> 2) & 0x03030303u);
+    r[2] = (int)((p >> 4) & 0x03030303u);
+    r[3] = (int)((p >> 6) & 0x03030303u);
+    return r;
+}
+
+// The problem a workgroup belongs to: the last one whose first workgroup is not beyond it.
+template <typename BeginOf>
+__device__ __forceinline__ DecodeProblem select_problem(const DecodeArgs& args, int wg, BeginOf begin_of) {
+    DecodeProblem p = args.p[0];
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i)
+        if (i < args.n && wg >= begin_of(args.p[i])) p = args.p[i];
+    return p;
+}
+
+template <bool SHARE, int TT, int RQ, int D>
+__global__ __launch_bounds__(256, 2) void decode_gemm_kernel(const DecodeArgs args) {
+    constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;    // token rows of one code stage
+    constexpr int XB = ROWS * kBK;                    // bytes of one code stage
+    constexpr int XW = SHARE ? XB : 4 * XB;           // code bytes per stage in the workgroup
+    constexpr int STAGE = XW + 4 * 1024;              // + one packed weight tile per wave
+    constexpr int XL = SHARE ? TT : RQ;               // code copies per wave per stage
+    constexpr int PENDING = (D - 2) * (XL + 1);       // copies of later stages that may stay in flight
+    constexpr int NACC = TT == 1 ? 2 : TT;
+    static_assert(D >= 3 && (ROWS & (ROWS - 1)) == 0, "pipeline depth / row count");
+
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+
+    const DecodeProblem p = select_problem(args, (int)blockIdx.x, [](const DecodeProblem& q) { return q.wg_begin; });
+    const int w = (int)blockIdx.x - p.wg_begin;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kl = p.ksplit == 4 ? 2 : (p.ksplit == 2 ? 1 : 0);   // ksplit is 1, 2 or 4
+    const int nkb_total = p.K / kBK;
+    const int nkb = nkb_total >> kl;
+    int nt, ks;
+    if constexpr (SHARE) {
+        nt = 4 * (w >> kl) + wave;
+        ks = w & (p.ksplit - 1);
+    } else {
+        nt = w * (4 >> kl) + (wave >> kl);
+        ks = wave & (p.ksplit - 1);
+    }
+    const int nt_max = p.N / 32 - 1;
+    const bool live = nt <= nt_max;          // a wave past the last row tile streams that tile again, writes nothing
+    const int ntc = live ? nt : nt_max;
+    // K slices are interleaved tile by tile in the streaming form (the waves of a workgroup then read
+    // 4 KiB of consecutive weight tiles per stage), blocked in the shared form
+    const int kstep = (!SHARE && p.interleave) ? p.ksplit : 1;
+    const int kb0 = (!SHARE && p.interleave) ? ks : ks * nkb;
+
+    const char* wbase = reinterpret_cast<const char*>(p.packed) + ((size_t)ntc * nkb_total + kb0) * 1024;
+    const uint32_t wlane = lane * 16;
+    // code copy m of a stage covers rows 8q..8q+7: lane l -> row 8q + l/8, LDS slot l%8 of that row,
+    // global 16-byte chunk (l%8) ^ ((row/2) % 8); rows past T re-read the last token
+    const char* xbase = reinterpret_cast<const char*>(p.codes) + (size_t)kb0 * kBK;
+    uint32_t xlane[XL];
+#pragma unroll
+    for (int m = 0; m < XL; ++m) {
+        const int q = SHARE ? wave + 4 * m : m;
+        const int row = 8 * q + (lane >> 3);
+        const int t = row < p.T ? row : p.T - 1;
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        xlane[m] = (uint32_t)t * (uint32_t)p.K + c * 16;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+    const uint32_t xarea = SHARE ? 0 : wave * XB;
+
+    // Copies of stage kb into buffer `slot`.
+    auto issue = [&](int kb, int slot) {
+        const int kbc = kb * kstep;
+#pragma unroll
+        for (int m = 0; m < XL; ++m) {
+            const int q = SHARE ? wave + 4 * m : m;
+            lds_dma16(lds0 + slot * STAGE + xarea + q * 1024, xbase + (size_t)kbc * kBK, xlane[m]);
+        }
+        lds_dma16(lds0 + slot * STAGE + XW + wave * 1024, wbase + (size_t)kbc * 1024, wlane);
+    };
+
+    // operand reads: token row (lane & 31) of tile j (rows beyond the stage wrap onto loaded rows; their
+    // results are never written), 16-byte chunk 2*k4 + (lane >> 5), swizzled like the copy
+    const int r0 = (lane & 31) & (ROWS - 1);
+    int xoff[4];
+#pragma unroll
+    for (int k4 = 0; k4 < 4; ++k4) xoff[k4] = r0 * kBK + (((2 * k4 + (lane >> 5)) ^ ((r0 >> 1) & 7)) << 4);
+
+    v16i acc[NACC];
+#pragma unroll
+    for (int i = 0; i < NACC; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+
+    // Epilogue operands, requested before the stream starts: under a saturated memory system a load
+    // issued after the loop would add its whole latency to the workgroup's run time.
+    const bool write_partial = SHARE && p.ksplit > 1;
+    const bool writer = live && (SHARE || ks == 0);
+    float alpha = 0.0f, sd[TT];
+    int sx[TT];
+    v4i wsum[4];
+#pragma unroll
+    for (int j = 0; j < TT; ++j) {
+        sd[j] = 0.0f;
+        sx[j] = 0;
+    }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) wsum[g] = v4i{0, 0, 0, 0};
+    if (writer && !write_partial) {
+        alpha = p.w_scales[(nt * 32) / p.rows_per_group];
+#pragma unroll
+        for (int j = 0; j < TT; ++j) {
+            const int t = j * 32 + (lane & 31);
+            if (t < p.T) {
+                sd[j] = p.s_dequant[t];
+                sx[j] = p.code_sum[t];
+            }
+        }
+        if (p.code_offset != 0) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                wsum[g] = *reinterpret_cast<const v4i*>(p.w_row_sum + nt * 32 + 8 * g + 4 * (lane >> 5));
+        }
+    }
+
+    // Stage kb may be consumed once at most min(D - 2, nkb - 1 - kb) later stages are still in flight
+    // (copies return in order).  Nothing is requested past the end of the K range, so the count
+    // shrinks over the last D - 2 stages: those take the switch.
+    auto wait_stage = [&](int later) {
+        if (later >= D - 2) {
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 2) * (XL + 1)) : "memory");
+            return;
+        }
+        switch (later) {
+            case 0: asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); break;
+            case 1: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(1 * (XL + 1)) : "memory"); break;
+            case 2: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * (XL + 1)) : "memory"); break;
+            case 3: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(3 * (XL + 1)) : "memory"); break;
+            case 4: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(4 * (XL + 1)) : "memory"); break;
+            default: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(5 * (XL + 1)) : "memory"); break;
+        }
+    };
+    static_assert(D - 2 <= 6, "wait_stage covers up to 5 later stages below the steady state");
+
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s)
+        if (s < nkb) issue(s, s);
+
+    int slot = 0;
+    for (int kb = 0; kb < nkb; ++kb) {
+        // stage kb has landed (for every wave, if the code stage is shared); the buffer read in the
+        // previous iteration is free for stage kb + D - 1
+        wait_stage(nkb - 1 - kb);
+        if constexpr (SHARE) asm volatile("s_barrier" ::: "memory");
+        if (kb + D - 1 < nkb) issue(kb + D - 1, slot == 0 ? D - 1 : slot - 1);
+        const char* st = lds + slot * STAGE;
+        const v4i wpk = *reinterpret_cast<const v4i*>(st + XW + wave * 1024 + lane * 16);
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+            const v4i wop = expand_plus1((uint32_t)wpk[k4]);
+#pragma unroll
+            for (int j = 0; j < TT; ++j) {
+                const v4i xop = *reinterpret_cast<const v4i*>(st + xarea + xoff[k4] + j * 32 * kBK);
+                // TT == 1: two accumulators take turns so that consecutive MFMAs do not depend on each other
+                const int ai = TT == 1 ? (k4 & 1) : j;
+                acc[ai] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop, xop, acc[ai], 0, 0, 0);
+            }
+        }
+        slot = slot + 1 == D ? 0 : slot + 1;
+    }
+    if constexpr (TT == 1) acc[0] += acc[1];
+
+    if constexpr (!SHARE) {
+        if (p.ksplit > 1) {   // uniform over the workgroup
+            __syncthreads();  // every wave is done with the stage buffers
+            int* red = reinterpret_cast<int*>(lds);
+            if (ks != 0) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[0][r];
+            }
+            __syncthreads();
+            if (ks == 0) {
+                for (int kk = 1; kk < p.ksplit; ++kk)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[0][r] += red[((wave + kk) * 16 + r) * 64 + lane];
+            }
+        }
+        if (ks != 0) return;
+    }
+    if (!writer) return;
+
+    // lane holds token 32j + (lane & 31); register quad g holds features 8g + 4*(lane >> 5) + 0..3
+#pragma unroll
+    for (int j = 0; j < TT; ++j) {
+        const int t = j * 32 + (lane & 31);
+        if (t >= p.T) continue;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int n = nt * 32 + 8 * g + 4 * (lane >> 5);
+            v4i o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = acc[TT == 1 ? 0 : j][4 * g + r];
+            if (write_partial) {
+                *reinterpret_cast<v4i*>(p.partial + ((size_t)ks * p.T + t) * p.N + n) = o;
+            } else {
+                *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
+                    dequant_quad_sums(o, sx[j], sd[j], alpha, p.code_offset, wsum[g], p.K);
+            }
+        }
+    }
+}
+
+// Second launch of the shared form when some K range was split over workgroups: adds the int32 partial
+// tiles in fixed order (exact) and applies the dequantising epilogue.  The kernel boundary is what makes
+// the partials of workgroups on other XCDs visible.
+__global__ __launch_bounds__(256) void decode_reduce_kernel(const DecodeArgs args) {
+    const DecodeProblem p = select_problem(args, (int)blockIdx.x, [](const DecodeProblem& q) { return q.red_begin; });
+    const int quads = p.N / 4;
+    const int64_t idx = (int64_t)((int)blockIdx.x - p.red_begin) * 256 + threadIdx.x;
+    if (p.ksplit <= 1 || idx >= (int64_t)p.T * quads) return;
+    const int t = (int)(idx / quads);
+    const int n = (int)(idx % quads) * 4;
+    v4i sum = {0, 0, 0, 0};
+    for (int k = 0; k < p.ksplit; ++k)
+        sum += *reinterpret_cast<const v4i*>(p.partial + ((size_t)k * p.T + t) * p.N + n);
+    *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
+        dequant_quad(sum, p.code_sum[t], p.s_dequant[t], p.w_scales[n / p.rows_per_group], p.code_offset,
+                     p.w_row_sum + n, p.K);
+}
+
+template <bool SHARE, int TT, int RQ, int D>
+int launch_form(const DecodeArgs& a, int wgs, int red_wgs, hipStream_t stream) {
+    constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;
+    constexpr size_t lds = (size_t)D * ((SHARE ? 1 : 4) * ROWS * kBK + 4 * 1024);
+    auto kern = decode_gemm_kernel<SHARE, TT, RQ, D>;
+    static std::atomic<bool> attr_set{false};   // once per process (one device)
+    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return note_hip_error(e);
+        attr_set.store(true, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), lds, stream, a);
+    int rc = after_launch();
+    if (rc != HBL_OK || red_wgs == 0) return rc;
+    hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)red_wgs), dim3(256), 0, stream, a);
+    return after_launch();
+}
+
+// Workgroups a problem occupies in the GEMM grid for a given K split.
+int problem_wgs(const DecodeProblem& p, bool share) {
+    const int tiles = p.N / 32;
+    return share ? ((tiles + 3) / 4) * p.ksplit : (tiles * p.ksplit + 3) / 4;
+}
+
+
+// K split of every problem, then each problem's first workgroup in the GEMM and reduction grids.
+// About 32 weight tiles (32 KiB) per wave; while the grid is too small to occupy the chip (256 CUs x
+// 2 workgroups) split further, down to 8 tiles per wave.  The streaming form adds the slices inside a
+// workgroup, so a split is free; the shared form needs the partial buffer and a second launch, so it
+// splits further only when less than three quarters of the CUs would get a workgroup.
+void plan(DecodeArgs& a, bool share, int* wgs_out, int* red_out) {
+    static const int min_tiles = [] { const char* e = getenv("HBL_DECODE_MIN_TILES"); return e ? atoi(e) : 32; }();
+    static const int interleave = [] { const char* e = getenv("HBL_DECODE_INTERLEAVE"); return e ? atoi(e) : 0; }();
+    const int enough = share ? 192 : 384;
+    int total = 0;
+    for (int i = 0; i < a.n; ++i) {
+        DecodeProblem& p = a.p[i];
+        const int nkb = p.K / 128;
+        const bool may_split = !share || p.partial != nullptr;
+        p.ksplit = 1;
+        p.interleave = interleave;
+        const int mt = share ? 32 : min_tiles;
+        while (may_split && p.ksplit < kMaxDecodeSplit && nkb % (2 * p.ksplit) == 0 && nkb / (2 * p.ksplit) >= mt)
+            p.ksplit *= 2;
+        total += problem_wgs(p, share);
+    }
+    for (int pass = 0; pass < 2 && total < enough; ++pass) {
+        total = 0;
+        for (int i = 0; i < a.n; ++i) {
+            DecodeProblem& p = a.p[i];
+            const int nkb = p.K / 128;
+            const bool may_split = !share || p.partial != nullptr;
+            if (may_split && p.ksplit < kMaxDecodeSplit && nkb % (2 * p.ksplit) == 0 && nkb / (2 * p.ksplit) >= 8)
+                p.ksplit *= 2;
+            total += problem_wgs(p, share);
+        }
+    }
+    int wgs = 0, red = 0;
+    for (int i = 0; i < a.n; ++i) {
+        DecodeProblem& p = a.p[i];
+        p.wg_begin = wgs;
+        wgs += problem_wgs(p, share);
+        p.red_begin = red;
+        if (share && p.ksplit > 1) red += (int)(((int64_t)p.T * (p.N / 4) + 255) / 256);
+    }
+    *wgs_out = wgs;
+    *red_out = red;
+}
+
+}  // namespace
+
+bool decode_stream_preferred(int64_t T, int64_t K, int64_t N) {
+    if (T <= 0 || T > 16) return false;
+    DecodeArgs a = {};
+    a.n = 1;
+    a.p[0].T = (int)T;
+    a.p[0].K = (int)K;
+    a.p[0].N = (int)N;
+    int wgs, red;
+    plan(a, false, &wgs, &red);
+    // a wave's tiles are a serial chain: few workgroups with long chains leave most of the chip idle
+    return (K / 128) / a.p[0].ksplit <= 16 || wgs >= 256;
+}
+
+int launch_decode_gemm(DecodeArgs& a, hipStream_t stream) {
+    if (a.n <= 0) return HBL_OK;
+    int max_t = 0;
+    for (int i = 0; i < a.n; ++i) max_t = a.p[i].T > max_t ? a.p[i].T : max_t;
+    if (max_t > 64) return HBL_E_SHAPE;
+    int wgs, red;
+    plan(a, max_t > 16, &wgs, &red);
+    if (max_t <= 8) return launch_form<false, 1, 1, 8>(a, wgs, 0, stream);
+    if (max_t <= 16) return launch_form<false, 1, 2, 6>(a, wgs, 0, stream);
+    if (max_t <= 32) return launch_form<true, 1, 1, 8>(a, wgs, red, stream);
+    return launch_form<true, 2, 1, 6>(a, wgs, red, stream);
+}
+
+}  // namespace hbl

@@ -126,10 +126,12 @@ __device__ __forceinline__ void bf6_store_pair(int8_t* row_codes, int chunk8, ui
     }
 }
 
+// One token row per workgroup of 64*W threads; `row` and `tid` come from the caller so that the grouped
+// launch (several projections' rows in one grid) can run the same body.
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
-__global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restrict__ x, int8_t* __restrict__ codes,
-                                                            float* __restrict__ s_dequant,
-                                                            int32_t* __restrict__ code_sum, float eps, int code_offset) {
+__device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void* __restrict__ x,
+                                                int8_t* __restrict__ codes, float* __restrict__ s_dequant,
+                                                int32_t* __restrict__ code_sum, float eps, int code_offset) {
     constexpr int K = 1 << LOG2K;
     constexpr int NT = 64 * W;
     constexpr int E = K / NT;            // elements per thread
@@ -142,10 +144,8 @@ __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restri
     __shared__ int red_i[W];
     extern __shared__ float exch[];      // K floats when HADAMARD && W > 1
 
-    const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int64_t row = blockIdx.x;
     const int64_t row_off = row * (int64_t)K;
 
     float v[R][CH];
@@ -327,6 +327,14 @@ __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restri
 }
 
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
+__global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restrict__ x, int8_t* __restrict__ codes,
+                                                            float* __restrict__ s_dequant,
+                                                            int32_t* __restrict__ code_sum, float eps, int code_offset) {
+    fwht_quant_body<LOG2K, W, BITS, BF16, HADAMARD>(blockIdx.x, threadIdx.x, x, codes, s_dequant, code_sum, eps,
+                                                    code_offset);
+}
+
+template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
 int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, float eps,
                int code_offset, hipStream_t stream) {
     constexpr int K = 1 << LOG2K;
@@ -347,16 +355,15 @@ int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_
 // Plain BitLinear front end for K that is not a power of two (K % 128 == 0, K <= 16384): the same
 // quantiser with the row held as up to 8 chunks of 8 elements per thread of a 256-thread workgroup.
 template <int BITS, bool BF16>
-__global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restrict__ x, int K,
-                                                            int8_t* __restrict__ codes,
-                                                            float* __restrict__ s_dequant,
-                                                            int32_t* __restrict__ code_sum, float eps, int code_offset) {
+__device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const void* __restrict__ x, int K,
+                                                   int8_t* __restrict__ codes, float* __restrict__ s_dequant,
+                                                   int32_t* __restrict__ code_sum, float eps, int code_offset) {
     constexpr int MAXC = 8;
     __shared__ double red_d[4];
     __shared__ float red_f[4];
     __shared__ int red_i[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t row_off = (int64_t)blockIdx.x * K;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int64_t row_off = row * K;
     const int nchunks = K / 8;
     float v[MAXC][8];
 #pragma unroll
@@ -427,9 +434,17 @@ __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restri
     if (lane == 0) red_i[wave] = isum;
     __syncthreads();
     if (tid == 0) {
-        s_dequant[blockIdx.x] = s_d;
-        if (code_sum) code_sum[blockIdx.x] = red_i[0] + red_i[1] + red_i[2] + red_i[3];
+        s_dequant[row] = s_d;
+        if (code_sum) code_sum[row] = red_i[0] + red_i[1] + red_i[2] + red_i[3];
     }
+}
+
+template <int BITS, bool BF16>
+__global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restrict__ x, int K,
+                                                            int8_t* __restrict__ codes,
+                                                            float* __restrict__ s_dequant,
+                                                            int32_t* __restrict__ code_sum, float eps, int code_offset) {
+    quant_generic_body<BITS, BF16>(blockIdx.x, threadIdx.x, x, K, codes, s_dequant, code_sum, eps, code_offset);
 }
 
 int launch_generic(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int8_t* codes,
@@ -487,9 +502,9 @@ __host__ __device__ constexpr uint32_t swz16(uint32_t q) { return q ^ ((q >> 4) 
 // consecutive features a 32-byte record whose first 24 bytes hold the 32 codes as bf6 (e3m2) values,
 // feature i at bits [6i, 6i+6); every integer in [-8, 7] is exact in that format.
 template <int LOG2K, int BITS, bool BF16, bool BF6OUT>
-__global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
-    const void* __restrict__ x, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
-    int32_t* __restrict__ code_sum, float eps, int code_offset) {
+__device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid, const void* __restrict__ x,
+                                                       int8_t* __restrict__ codes, float* __restrict__ s_dequant,
+                                                       int32_t* __restrict__ code_sum, float eps, int code_offset) {
     constexpr int K = 1 << LOG2K;
     constexpr int NT = K / 64;
     constexpr int W = NT / 64;
@@ -501,9 +516,7 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
     __shared__ float red_f[W];
     __shared__ int red_i[W];
 
-    const uint32_t tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int64_t row = blockIdx.x;
     const int64_t row_off = row * (int64_t)K;
 
     float v[16][4];
@@ -695,6 +708,14 @@ __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
     if (tid == 0) s_dequant[row] = s_d;
 }
 
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT>
+__global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
+    const void* __restrict__ x, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
+    int32_t* __restrict__ code_sum, float eps, int code_offset) {
+    fwht_quant_bigrow_body<LOG2K, BITS, BF16, BF6OUT>(blockIdx.x, threadIdx.x, x, codes, s_dequant, code_sum, eps,
+                                                      code_offset);
+}
+
 template <int LOG2K, int BITS, bool BF16, bool BF6OUT = false>
 int launch_bigrow(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, float eps,
                   int code_offset, hipStream_t stream) {
@@ -742,7 +763,75 @@ int dispatch(const void* x, int x_dtype, int64_t T, int bits, float eps, bool ha
               : launch_one<LOG2K, W, 4, false, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
 }
 
+// Rows of several projections in one grid (small-batch path): workgroup -> (problem, row), then the
+// body the stand-alone launch would run for that problem.  A body that needs fewer than 256 threads
+// runs on the first waves only; the other waves end at once, and a workgroup barrier waits only for
+// waves that have not ended.
+template <int BITS, bool BF16>
+__global__ __launch_bounds__(256) void quant_grouped_kernel(const QuantGroupArgs a) {
+    QuantProblem p = a.p[0];
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i)
+        if (i < a.n && (int)blockIdx.x >= a.p[i].row_begin) p = a.p[i];
+    const int64_t row = (int)blockIdx.x - p.row_begin;
+    const int tid = threadIdx.x;
+    if (!p.hadamard) {
+        quant_generic_body<BITS, BF16>(row, tid, p.x, p.K, p.codes, p.s_dequant, p.code_sum, a.eps, p.code_offset);
+        return;
+    }
+#define HBL_SMALL_ROW(L2K)                                                                                    \
+    case 1 << L2K:                                                                                            \
+        if (tid < 64)                                                                                         \
+            fwht_quant_body<L2K, 1, BITS, BF16, true>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum, a.eps, \
+                                                      p.code_offset);                                         \
+        return;
+#define HBL_BIG_ROW(L2K)                                                                                      \
+    case 1 << L2K:                                                                                            \
+        if (tid < (1 << L2K) / 64)                                                                            \
+            fwht_quant_bigrow_body<L2K, BITS, BF16, false>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum,   \
+                                                           a.eps, p.code_offset);                             \
+        return;
+    switch (p.K) {
+        HBL_SMALL_ROW(7)
+        HBL_SMALL_ROW(8)
+        HBL_SMALL_ROW(9)
+        HBL_SMALL_ROW(10)
+        HBL_SMALL_ROW(11)
+        HBL_BIG_ROW(12)
+        HBL_BIG_ROW(13)
+        HBL_BIG_ROW(14)
+        default: return;
+    }
+#undef HBL_SMALL_ROW
+#undef HBL_BIG_ROW
+}
+
 }  // namespace
+
+int launch_quant_grouped(const QuantGroupArgs& args, int bits, int x_dtype, hipStream_t stream) {
+    int rows = 0;
+    size_t lds = 0;
+    for (int i = 0; i < args.n; ++i) {
+        rows += args.p[i].T;
+        if (args.p[i].hadamard && args.p[i].K >= 4096 && sizeof(float) * (size_t)args.p[i].K > lds)
+            lds = sizeof(float) * (size_t)args.p[i].K;
+    }
+    if (rows == 0) return HBL_OK;
+    const bool bf = x_dtype == HBL_BF16;
+    auto launch = [&](auto kern) -> int {
+        static std::atomic<bool> attr_set{false};   // per instantiation, once per process (one device)
+        if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+            if (e != hipSuccess) return note_hip_error(e);
+            attr_set.store(true, std::memory_order_release);
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(256), lds, stream, args);
+        return after_launch();
+    };
+    if (bits == 8) return bf ? launch(quant_grouped_kernel<8, true>) : launch(quant_grouped_kernel<8, false>);
+    return bf ? launch(quant_grouped_kernel<4, true>) : launch(quant_grouped_kernel<4, false>);
+}
 
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {

@@ -54,11 +54,11 @@ struct GemmArgs {
 
 // Outer factors of Eq. 1 and Eq. 5/6 on four consecutive output features of one token:
 // y = bf16(((float)(acc - corr) * s_d) * alpha), corr = sum_k q + code_offset * (sum_k c + K).
-__device__ __forceinline__ uint2 dequant_quad(v4i acc, int sx, float sd, float alpha, int code_offset,
-                                              const int32_t* w_row_sum, int K) {
+// (ws = the four features' sum_k c, already loaded; ignored when code_offset == 0)
+__device__ __forceinline__ uint2 dequant_quad_sums(v4i acc, int sx, float sd, float alpha, int code_offset, v4i ws,
+                                                   int K) {
     v4i corr = {sx, sx, sx, sx};
     if (code_offset != 0) {
-        const v4i ws = *reinterpret_cast<const v4i*>(w_row_sum);
 #pragma unroll
         for (int r = 0; r < 4; ++r) corr[r] += code_offset * (ws[r] + K);
     }
@@ -71,6 +71,12 @@ __device__ __forceinline__ uint2 dequant_quad(v4i acc, int sx, float sd, float a
     const bf16x2 lo = __builtin_convertvector((f32x2){v[0], v[1]}, bf16x2);
     const bf16x2 hi = __builtin_convertvector((f32x2){v[2], v[3]}, bf16x2);
     return make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+}
+__device__ __forceinline__ uint2 dequant_quad(v4i acc, int sx, float sd, float alpha, int code_offset,
+                                              const int32_t* w_row_sum, int K) {
+    v4i ws = {0, 0, 0, 0};
+    if (code_offset != 0) ws = *reinterpret_cast<const v4i*>(w_row_sum);
+    return dequant_quad_sums(acc, sx, sd, alpha, code_offset, ws, K);
 }
 
 // WAVES_N x WAVES_T waves; each wave owns TN x TT MFMA tiles (32 features x 32 tokens each).

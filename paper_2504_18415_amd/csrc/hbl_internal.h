@@ -84,6 +84,58 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
                              const float* s_dequant, const float* w_scales, int64_t n_scale_groups, void* y_bf16,
                              hipStream_t stream);
 
+// ---------------------------------------------------------------------------------------------
+// Grouped small-batch path: up to kMaxGroup independent projections (T <= 64 each) served by one
+// quantiser launch and one GEMM launch (plus one reduction launch if some K range was split over
+// workgroups).  The argument blocks travel by value as kernel arguments: no table in device memory.
+constexpr int kMaxGroup = 8;
+
+struct QuantProblem {
+    const void* x;        // [T, K] bf16 / fp32
+    int8_t* codes;        // [T, K] out
+    float* s_dequant;     // [T] out
+    int32_t* code_sum;    // [T] out
+    int T, K;
+    int hadamard;
+    int code_offset;
+    int row_begin;        // first workgroup (= row) of this problem in the grouped grid
+};
+struct QuantGroupArgs {
+    QuantProblem p[kMaxGroup];
+    int n;
+    float eps;
+};
+int launch_quant_grouped(const QuantGroupArgs& args, int bits, int x_dtype, hipStream_t stream);
+
+struct DecodeProblem {
+    const int8_t* codes;       // [T, K] stored as code + code_offset
+    const uint32_t* packed;    // int8-path weight tiles
+    const float* s_dequant;    // [T]
+    const int32_t* code_sum;   // [T]
+    const int32_t* w_row_sum;  // [N]
+    const float* w_scales;     // [groups]
+    uint16_t* y;               // [T, N] bf16
+    int32_t* partial;          // [ksplit][T][N] when the K range is split over workgroups, else unused
+    int T, K, N;
+    int rows_per_group;
+    int code_offset;
+    int ksplit;                // K slices per row tile
+    int interleave;            // streaming form: slice s takes tiles s, s + ksplit, ... instead of a block
+    int wg_begin;              // first workgroup of this problem in the GEMM grid
+    int red_begin;             // first workgroup of this problem in the reduction grid
+};
+struct DecodeArgs {
+    DecodeProblem p[kMaxGroup];
+    int n;
+};
+// Largest K split the grouped GEMM may choose (sizes the partial buffers).
+constexpr int kMaxDecodeSplit = 4;
+// Fills ksplit / wg_begin / red_begin and launches.  Every problem needs T <= 64.
+int launch_decode_gemm(DecodeArgs& args, hipStream_t stream);
+// Whether a single projection with T <= 16 is better served by the streaming form of that launch than
+// by the split-K pair of launch_ternary_gemm.
+bool decode_stream_preferred(int64_t T, int64_t K, int64_t N);
+
 // Packed weight buffer: N*K/4 bytes of 2-bit tiles for the int8 matrix-core path, N int32 row sums of
 // the ternary codes, then N*K/4 bytes of 2-bit tiles in the form the fp6 x fp4 path reads.
 inline size_t packed_tile_bytes(int64_t N, int64_t K) { return (size_t)N * (size_t)K / 4; }

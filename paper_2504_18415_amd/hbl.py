@@ -29,10 +29,18 @@ EXPORTS = [
     "hbl_strerror", "hbl_last_hip_error", "hbl_ternarize_workspace_bytes", "hbl_ternarize_weights_absmean",
     "hbl_packed_bytes", "hbl_pack_ternary_2bit", "hbl_unpack_ternary_2bit", "hbl_workspace_bytes",
     "hbl_hbitlinear_forward", "hbl_plain_bitlinear_forward", "hbl_fwht_quant", "hbl_gemm_i32",
-    "hbl_gemm_dequant_bf16",
+    "hbl_gemm_dequant_bf16", "hbl_grouped_workspace_bytes", "hbl_bitlinear_forward_grouped",
 ]
 
 _lib = None
+
+
+class Problem(ctypes.Structure):
+    """``hbl_problem`` of include/hbitlinear.h."""
+    _fields_ = [("x", ctypes.c_void_p), ("x_dtype", ctypes.c_int), ("bits", ctypes.c_int),
+                ("hadamard", ctypes.c_int), ("reserved", ctypes.c_int), ("T", ctypes.c_int64),
+                ("K", ctypes.c_int64), ("N", ctypes.c_int64), ("Wq_packed", ctypes.c_void_p),
+                ("w_scales", ctypes.c_void_p), ("n_scale_groups", ctypes.c_int64), ("y", ctypes.c_void_p)]
 
 
 class HblError(RuntimeError):
@@ -72,6 +80,9 @@ def lib():
         L.hbl_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, ci, vp, vp, vp, vp]
         L.hbl_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp, vp]
         L.hbl_gemm_dequant_bf16.argtypes = [vp, ci, vp, vp, i64, i64, vp, i64, vp, i64, vp, vp]
+        L.hbl_grouped_workspace_bytes.restype = sz
+        L.hbl_grouped_workspace_bytes.argtypes = [ctypes.POINTER(Problem), ci]
+        L.hbl_bitlinear_forward_grouped.argtypes = [ctypes.POINTER(Problem), ci, f32, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -211,3 +222,38 @@ def fwht_quant_into(x: torch.Tensor, bits: int, hadamard: bool, codes: torch.Ten
     T, K = x.shape
     _check(lib().hbl_fwht_quant(_ptr(x), _x_dtype(x), T, K, bits, eps, int(hadamard), code_offset, _ptr(codes),
                                 _ptr(s_dequant), _ptr(code_sum), _stream()), "fwht_quant")
+
+
+def make_problems(items) -> "ctypes.Array":
+    """items: iterable of (x, Wq_packed, N, w_scales, bits, hadamard, y) -> ``hbl_problem`` array."""
+    items = list(items)
+    arr = (Problem * max(len(items), 1))()
+    for i, (x, Wq_packed, N, w_scales, bits, hadamard, y) in enumerate(items):
+        _dev_check(x, Wq_packed, w_scales, y)
+        T, K = x.shape
+        arr[i] = Problem(_ptr(x), _x_dtype(x), bits, int(bool(hadamard)), 0, T, K, N, _ptr(Wq_packed),
+                         _ptr(w_scales), w_scales.numel(), _ptr(y))
+    return arr
+
+
+def grouped_workspace_bytes(problems, n: int) -> int:
+    return int(lib().hbl_grouped_workspace_bytes(problems, n))
+
+
+def bitlinear_forward_grouped(items, eps: float = EPS, workspace: Optional[torch.Tensor] = None,
+                              problems=None):
+    """Several independent projections in one call.  ``items`` as for :func:`make_problems`, with y
+    possibly None (allocated here); returns the list of y tensors.  Pass ``problems`` (from
+    :func:`make_problems`) and ``workspace`` to call again without marshalling or allocation."""
+    items = [list(it) for it in items]
+    for it in items:
+        if it[6] is None:
+            it[6] = torch.empty((it[0].shape[0], it[2]), dtype=torch.bfloat16, device=it[0].device)
+    if problems is None:
+        problems = make_problems(items)
+    n = len(items)
+    if workspace is None:
+        workspace = torch.empty(grouped_workspace_bytes(problems, n), dtype=torch.uint8, device="cuda")
+    _check(lib().hbl_bitlinear_forward_grouped(problems, n, eps, _ptr(workspace), workspace.numel(), _stream()),
+           "bitlinear_forward_grouped")
+    return [it[6] for it in items]

@@ -90,6 +90,36 @@ def test_argument_errors_before_any_launch(L):
     assert L.hbl_ternarize_weights_absmean(P, 4, 4, 1e-5, P, P, P, 0, None) == hbl.E_WORKSPACE
 
 
+def test_grouped_call_argument_errors_before_any_launch(L):
+    from paper_2504_18415_amd import hbl
+    P, NUL = 0x10000, 0
+
+    def prob(x=P, dt=hbl.BF16, bits=4, had=1, T=4, K=256, N=64, w=P, sc=P, g=1, y=P):
+        return hbl.Problem(x, dt, bits, had, 0, T, K, N, w, sc, g, y)
+
+    def call(ps, ws=P, wsb=1 << 30):
+        arr = (hbl.Problem * max(len(ps), 1))(*ps)
+        return L.hbl_bitlinear_forward_grouped(arr, len(ps), 1e-5, ctypes.c_void_p(ws), wsb, None)
+
+    assert call([]) == hbl.OK
+    assert L.hbl_bitlinear_forward_grouped(None, 2, 1e-5, ctypes.c_void_p(P), 1 << 30, None) == hbl.E_NULL
+    assert L.hbl_bitlinear_forward_grouped(None, -1, 1e-5, ctypes.c_void_p(P), 1 << 30, None) == hbl.E_SHAPE
+    assert call([prob(), prob(bits=3)]) == hbl.E_BITS
+    assert call([prob(), prob(dt=9)]) == hbl.E_DTYPE
+    assert call([prob(K=384)]) == hbl.E_SHAPE            # Hadamard needs a power of two
+    assert call([prob(K=384, had=0)], wsb=100) == hbl.E_WORKSPACE
+    assert call([prob(y=NUL)]) == hbl.E_NULL
+    assert call([prob()], ws=NUL) == hbl.E_NULL
+    assert call([prob()], ws=P + 16) == hbl.E_ALIGN
+    assert call([prob(x=P + 4)]) == hbl.E_ALIGN
+    assert call([prob(T=0, x=NUL, y=NUL)], ws=NUL, wsb=0) == hbl.OK     # nothing to do
+    arr = (hbl.Problem * 2)(prob(T=8, K=4096, N=4096), prob(T=200, K=1024, N=256))
+    need = L.hbl_grouped_workspace_bytes(arr, 2)
+    assert need >= 8 * 4096 + 200 * 1024 and need % 256 == 0
+    assert need >= L.hbl_workspace_bytes(8, 4096, 4096, 4) + L.hbl_workspace_bytes(200, 1024, 256, 4)
+    assert call(list(arr), wsb=need - 256) == hbl.E_WORKSPACE
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     from paper_2504_18415_amd import hbl
     monkeypatch.setattr(hbl, "_lib", None)

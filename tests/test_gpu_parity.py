@@ -496,3 +496,91 @@ def test_empty_batch_and_errors_on_device(hbl):
     with pytest.raises(hbl.HblError) as e:
         hbl.hbitlinear_forward(torch.zeros((4, 256), dtype=torch.bfloat16, device="cuda"), packed, 256, al, 6)
     assert e.value.status == hbl.E_BITS
+
+
+def run_group(hbl, sites, bits_list, expect_exact=True):
+    """One grouped call over `sites` against the oracle, problem by problem, and against the
+    stand-alone forward calls (must be bit-identical)."""
+    items, refs, singles = [], [], []
+    for site, bits in zip(sites, bits_list):
+        x = synth.make_x(site)
+        wc_ref, al_ref, wc_d, al_d, packed = setup_weights(hbl, site)
+        xd = dev_x(x)
+        items.append((xd, packed, site.N, al_d, bits, site.hadamard, None))
+        refs.append(O.bitlinear_forward(x, wc_ref, al_ref, bits, site.hadamard, EPS) if site.T else None)
+        fn = hbl.hbitlinear_forward if site.hadamard else hbl.plain_bitlinear_forward
+        singles.append(fn(xd, packed, site.N, al_d, bits, EPS))
+    ys = hbl.bitlinear_forward_grouped(items, EPS)
+    torch.cuda.synchronize()
+    for site, y, ref, single in zip(sites, ys, refs, singles):
+        assert y.shape == (site.T, site.N)
+        if site.T == 0:
+            continue
+        got = host_bf16_bits(y)
+        assert np.array_equal(got, host_bf16_bits(single)), f"{site.name}: grouped differs from the single call"
+        if expect_exact:
+            assert np.array_equal(got, ref), f"{site.name}: grouped differs from the oracle"
+        else:
+            mx, mean = rel_err(got, ref)
+            assert mx <= 1e-2 and mean <= 1e-3, (site.name, mx, mean)
+
+
+@pytest.mark.parametrize("batch", [1, 8, 16, 32, 64])
+def test_grouped_config5_decode_layer(hbl, batch):
+    """The four projections of the 7B decode layer in one grouped call."""
+    note(f"grouped config 5 batch={batch}")
+    sites = synth.config_sites(5, batch=batch)
+    run_group(hbl, sites, [4] * len(sites), expect_exact=False)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("x_dtype", [synth.BF16, synth.F32])
+def test_grouped_ragged_mix(hbl, bits, x_dtype):
+    """Mixed token counts, row counts that are no multiple of 128, a row length that is no power of
+    two, every Hadamard kernel family, an empty problem and scale groups - both small-batch forms."""
+    note(f"grouped ragged bits={bits} dtype={x_dtype}")
+    common = dict(outlier_frac=0.01, outlier_scale=30.0, x_dtype=x_dtype)
+    for tmax in (3, 13, 29, 64):
+        sites = [
+            synth.Site("g_plain640", tmax, 640, 96, hadamard=False, seed=31, **common),
+            synth.Site("g_h256", 1, 256, 32, hadamard=True, seed=32, **common),
+            synth.Site("g_h2048", max(tmax - 2, 1), 2048, 288, hadamard=True, seed=33, groups=3, **common),
+            synth.Site("g_empty", 0, 512, 64, hadamard=True, seed=34, **common),
+            synth.Site("g_h8192", tmax, 8192, 160, hadamard=True, seed=35, **common),
+            synth.Site("g_plain4096", 2, 4096, 544, hadamard=False, seed=36, **common),
+            synth.Site("g_h16384", tmax, 16384, 64, hadamard=True, seed=37, **common),
+        ]
+        run_group(hbl, sites, [bits] * len(sites))
+
+
+def test_grouped_single_problem_and_fallbacks(hbl):
+    """A group of one; a group with a large-T member, mixed bit widths or more than 8 problems runs
+    problem by problem and must give the same results."""
+    note("grouped single / fallbacks")
+    common = dict(outlier_frac=0.01, outlier_scale=30.0)
+    small = synth.Site("f_small", 5, 1024, 128, hadamard=True, seed=41, **common)
+    big = synth.Site("f_big", 100, 1024, 128, hadamard=True, seed=42, **common)
+    plain = synth.Site("f_plain", 7, 384, 64, hadamard=False, seed=43, **common)
+    run_group(hbl, [small], [4])
+    run_group(hbl, [small, big, plain], [4, 4, 4])
+    run_group(hbl, [small, plain], [4, 8])
+    run_group(hbl, [small, plain] * 5, [4] * 10)
+
+
+def test_grouped_argument_errors(hbl):
+    note("grouped errors")
+    x = torch.zeros((4, 256), dtype=torch.bfloat16, device="cuda")
+    packed = torch.zeros(hbl.packed_bytes(64, 256), dtype=torch.uint8, device="cuda")
+    al = torch.ones(1, dtype=torch.float32, device="cuda")
+    y = torch.empty((4, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(hbl.HblError) as e:
+        hbl.bitlinear_forward_grouped([(x, packed, 64, al, 5, True, y)])
+    assert e.value.status == hbl.E_BITS
+    with pytest.raises(hbl.HblError) as e:
+        hbl.bitlinear_forward_grouped([(x, packed, 64, al, 4, True, y)],
+                                      workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == hbl.E_WORKSPACE
+    with pytest.raises(hbl.HblError) as e:
+        hbl.bitlinear_forward_grouped([(x[:, :192].contiguous(), packed, 64, al, 4, True, y)])
+    assert e.value.status == hbl.E_SHAPE
+    assert hbl.bitlinear_forward_grouped([]) == []
