@@ -4,7 +4,7 @@
 //
 // A wave owns one 32-row weight tile at a time and walks its K range tile by tile (1 KiB of packed
 // weights = 32 rows x 128 features).  Weights and activation codes both arrive by direct global->LDS
-// copies, D stages deep per wave; per stage a wave expands the 16 packed bytes of each lane into four
+// copies, D stages deep per wave (D = 4); per stage a wave expands the 16 packed bytes of each lane into four
 // int8 operands (code + 1, as in the large-T kernel; the epilogue removes the offset in int32) and
 // issues 4 (or 8) 32x32x32 int8 MFMAs.
 //
@@ -79,10 +79,7 @@ __global__ __launch_bounds__(256, 2) void decode_gemm_kernel(const DecodeArgs ar
     const int nt_max = p.N / 32 - 1;
     const bool live = nt <= nt_max;          // a wave past the last row tile streams that tile again, writes nothing
     const int ntc = live ? nt : nt_max;
-    // K slices are interleaved tile by tile in the streaming form (the waves of a workgroup then read
-    // 4 KiB of consecutive weight tiles per stage), blocked in the shared form
-    const int kstep = (!SHARE && p.interleave) ? p.ksplit : 1;
-    const int kb0 = (!SHARE && p.interleave) ? ks : ks * nkb;
+    const int kb0 = ks * nkb;
 
     const char* wbase = reinterpret_cast<const char*>(p.packed) + ((size_t)ntc * nkb_total + kb0) * 1024;
     const uint32_t wlane = lane * 16;
@@ -103,7 +100,7 @@ __global__ __launch_bounds__(256, 2) void decode_gemm_kernel(const DecodeArgs ar
 
     // Copies of stage kb into buffer `slot`.
     auto issue = [&](int kb, int slot) {
-        const int kbc = kb * kstep;
+        const int kbc = kb;
 #pragma unroll
         for (int m = 0; m < XL; ++m) {
             const int q = SHARE ? wave + 4 * m : m;
@@ -293,8 +290,6 @@ int problem_wgs(const DecodeProblem& p, bool share) {
 // workgroup, so a split is free; the shared form needs the partial buffer and a second launch, so it
 // splits further only when less than three quarters of the CUs would get a workgroup.
 void plan(DecodeArgs& a, bool share, int* wgs_out, int* red_out) {
-    static const int min_tiles = [] { const char* e = getenv("HBL_DECODE_MIN_TILES"); return e ? atoi(e) : 32; }();
-    static const int interleave = [] { const char* e = getenv("HBL_DECODE_INTERLEAVE"); return e ? atoi(e) : 0; }();
     const int enough = share ? 192 : 384;
     int total = 0;
     for (int i = 0; i < a.n; ++i) {
@@ -302,9 +297,7 @@ void plan(DecodeArgs& a, bool share, int* wgs_out, int* red_out) {
         const int nkb = p.K / 128;
         const bool may_split = !share || p.partial != nullptr;
         p.ksplit = 1;
-        p.interleave = interleave;
-        const int mt = share ? 32 : min_tiles;
-        while (may_split && p.ksplit < kMaxDecodeSplit && nkb % (2 * p.ksplit) == 0 && nkb / (2 * p.ksplit) >= mt)
+        while (may_split && p.ksplit < kMaxDecodeSplit && nkb % (2 * p.ksplit) == 0 && nkb / (2 * p.ksplit) >= 32)
             p.ksplit *= 2;
         total += problem_wgs(p, share);
     }
@@ -353,10 +346,21 @@ int launch_decode_gemm(DecodeArgs& a, hipStream_t stream) {
     if (max_t > 64) return HBL_E_SHAPE;
     int wgs, red;
     plan(a, max_t > 16, &wgs, &red);
-    if (max_t <= 8) return launch_form<false, 1, 1, 8>(a, wgs, 0, stream);
-    if (max_t <= 16) return launch_form<false, 1, 2, 6>(a, wgs, 0, stream);
-    if (max_t <= 32) return launch_form<true, 1, 1, 8>(a, wgs, red, stream);
-    return launch_form<true, 2, 1, 6>(a, wgs, red, stream);
+    // Stages in flight per wave.  Shallow is best (measured 3..8): the memory-level parallelism comes from
+    // the 2048 waves of a full grid, and deeper rings only cost LDS and queueing.  HBL_DECODE_DEPTH overrides.
+    static const int depth = [] { const char* e = getenv("HBL_DECODE_DEPTH"); return e ? atoi(e) : 0; }();
+#define HBL_FORM(SH, TT_, RQ_, DEF)                                                        \
+    switch (depth ? depth : DEF) {                                                         \
+        case 3: return launch_form<SH, TT_, RQ_, 3>(a, wgs, SH ? red : 0, stream);         \
+        case 4: return launch_form<SH, TT_, RQ_, 4>(a, wgs, SH ? red : 0, stream);         \
+        case 6: return launch_form<SH, TT_, RQ_, 6>(a, wgs, SH ? red : 0, stream);         \
+        default: return launch_form<SH, TT_, RQ_, 8>(a, wgs, SH ? red : 0, stream);        \
+    }
+    if (max_t <= 8) HBL_FORM(false, 1, 1, 4)
+    if (max_t <= 16) HBL_FORM(false, 1, 2, 4)
+    if (max_t <= 32) HBL_FORM(true, 1, 1, 4)
+    HBL_FORM(true, 2, 1, 4)
+#undef HBL_FORM
 }
 
 }  // namespace hbl

@@ -120,7 +120,6 @@ struct DecodeProblem {
     int rows_per_group;
     int code_offset;
     int ksplit;                // K slices per row tile
-    int interleave;            // streaming form: slice s takes tiles s, s + ksplit, ... instead of a block
     int wg_begin;              // first workgroup of this problem in the GEMM grid
     int red_begin;             // first workgroup of this problem in the reduction grid
 };
