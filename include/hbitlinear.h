@@ -190,6 +190,16 @@ int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, f
                    void* stream);
 
 /*
+ * The transform by itself: out[t] = H_m x[t] (Eq. 3-4, same butterfly order and 1/sqrt(K) factor as
+ * the forward calls).  H_m is symmetric and orthogonal, so this is also the backward pass through
+ * the transform (Section 2.2, Eq. 8): with the straight-through estimator passing the gradient
+ * across the quantiser unchanged, dL/dx[t] = H_m (dL/dx_r[t]) - call it on the gradient rows.
+ *   x    [T, K] x_dtype, K a power of two in [128, 16384]
+ *   out  [T, K] out_dtype (HBL_F32, or HBL_BF16 rounded to nearest even); must not overlap x
+ */
+int hbl_fwht(const void* x, int x_dtype, int64_t T, int64_t K, void* out, int out_dtype, void* stream);
+
+/*
  * Integer contraction only: acc[t][o] = sum_k codes[t][k] * c[o][k] (int32, exact).
  *   codes [T, K] int8 (any values in [-128,127]);  acc [T, N] int32 out
  */

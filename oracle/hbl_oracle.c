@@ -25,6 +25,8 @@
  *   - butterfly stages run with ascending stride 1,2,4,...,n/2; means are
  *     accumulated in fp64 and rounded to fp32 once.
  *   - LN of Eq. 7 is outside this path: X is taken as already normalised.
+ *   - Eq. 8 (backward through the transform) is the same transform applied
+ *     to the gradient rows, in the same fp32 butterfly order.
  *   - X is a row vector per token, W is [N out x K in]: Y[T x N] = Xq * Wq^T.
  *
  * Pins (tests/test_oracle_*.py): H*H^T = I and the popcount closed form for
@@ -32,7 +34,10 @@
  * involution, Parseval, unit vectors for hblo_fwht_rows; a hand-derived n=4
  * example, range / boundary invariants and Gaussian closed forms for the
  * quantisers; int64 brute force for hblo_gemm_i32; an fp64 float reference
- * and a hand identity-weight case for the epilogue.
+ * and a hand identity-weight case for the epilogue; for
+ * hblo_hadamard_backward the adjoint identity <H x, y> = <x, H y> on exact
+ * integers, the gradient of a linear functional through the dense matrix
+ * (n <= 64) and an independent bf16 rounding.
  */
 #include <math.h>
 #include <stdint.h>
@@ -191,6 +196,40 @@ static void load_row_f32(const void* x, int x_dtype, int64_t t, int64_t K, float
         const uint16_t* p = (const uint16_t*)x + t * K;
         for (int64_t k = 0; k < K; ++k) dst[k] = bf16_to_f32(p[k]);
     }
+}
+
+/* ------------------------------------------------------------------------
+ * Backward pass through the transform (Section 2.2, Eq. 8): the gradient with
+ * respect to X is Hadamard() of the gradient with respect to Hadamard(X) -
+ * H_m is symmetric and orthogonal, so its transpose is itself.  The quantiser
+ * is bypassed (straight-through estimator), so this is the whole backward of
+ * the activation front end.  The same routine on X gives X_r of Eq. 3.
+ *   g    [T,n] fp32 or bf16 bit patterns (upstream gradient rows)
+ *   out  [T,n] fp32, or bf16 bit patterns rounded to nearest even
+ * ---------------------------------------------------------------------- */
+int hblo_hadamard_backward(const void* g, int g_dtype, int64_t T, int64_t n, void* out, int out_dtype) {
+    if (!g || !out || T < 0 || !is_pow2(n)) return HBLO_E_ARG;
+    if ((g_dtype != HBLO_F32 && g_dtype != HBLO_BF16) || (out_dtype != HBLO_F32 && out_dtype != HBLO_BF16))
+        return HBLO_E_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        float* u = (float*)malloc((size_t)n * sizeof(float));
+        if (!u) {
+            bad = 1;
+            continue;
+        }
+        load_row_f32(g, g_dtype, t, n, u);
+        fwht_row(u, n);
+        if (out_dtype == HBLO_F32) {
+            memcpy((float*)out + t * n, u, (size_t)n * sizeof(float));
+        } else {
+            uint16_t* o = (uint16_t*)out + t * n;
+            for (int64_t i = 0; i < n; ++i) o[i] = f32_to_bf16_rne(u[i]);
+        }
+        free(u);
+    }
+    return bad ? HBLO_E_ARG : HBLO_OK;
 }
 
 /* ------------------------------------------------------------------------

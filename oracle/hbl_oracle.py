@@ -48,6 +48,7 @@ def lib():
         _lib.hblo_ternarize_weights_absmean.argtypes = [vp, i64, i64, f32, vp, vp]
         _lib.hblo_hadamard_dense.argtypes = [ci, vp]
         _lib.hblo_fwht_rows.argtypes = [vp, i64, i64]
+        _lib.hblo_hadamard_backward.argtypes = [vp, ci, i64, i64, vp, ci]
         _lib.hblo_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, vp, vp, vp]
         _lib.hblo_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp]
         _lib.hblo_dequant_bf16.argtypes = [vp, i64, i64, vp, vp, i64, vp]
@@ -99,6 +100,17 @@ def fwht_rows(x: np.ndarray) -> np.ndarray:
     out = np.array(x, dtype=np.float32, order="C", copy=True)
     T, n = out.shape
     _check(lib().hblo_fwht_rows(_p(out), T, n), "fwht_rows")
+    return out
+
+
+def hadamard_backward(g: np.ndarray, out_bf16: bool = False) -> np.ndarray:
+    """Eq. 8: gradient w.r.t. X from the gradient w.r.t. Hadamard(X), row by row ([T,n] fp32 or bf16 bits).
+    Returns fp32, or bf16 bit patterns (uint16) if ``out_bf16``."""
+    g = np.ascontiguousarray(g)
+    T, n = g.shape
+    out = np.empty((T, n), dtype=np.uint16 if out_bf16 else np.float32)
+    _check(lib().hblo_hadamard_backward(_p(g), _x_dtype(g), T, n, _p(out), BF16 if out_bf16 else F32),
+           "hadamard_backward")
     return out
 
 

@@ -273,6 +273,17 @@ int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, f
                              static_cast<hipStream_t>(stream));
 }
 
+int hbl_fwht(const void* x, int x_dtype, int64_t T, int64_t K, void* out, int out_dtype, void* stream) {
+    if ((x_dtype != HBL_F32 && x_dtype != HBL_BF16) || (out_dtype != HBL_F32 && out_dtype != HBL_BF16))
+        return HBL_E_DTYPE;
+    int rc = check_gemm_shape(T, K, 32, true);
+    if (rc != HBL_OK) return rc;
+    if (T == 0) return HBL_OK;
+    if (!x || !out) return HBL_E_NULL;
+    if (!aligned16(x) || !aligned16(out)) return HBL_E_ALIGN;
+    return launch_fwht_only(x, x_dtype, T, K, out, out_dtype, static_cast<hipStream_t>(stream));
+}
+
 int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packed, int64_t N, int32_t* acc,
                  void* stream) {
     int rc = check_gemm_shape(T, K, N, false);

@@ -126,6 +126,37 @@ __device__ __forceinline__ void bf6_store_pair(int8_t* row_codes, int chunk8, ui
     }
 }
 
+// Transform-only output (BITS == 0 in the bodies below): N consecutive values of x_r as fp32 or, rounded
+// to nearest even, as bf16.
+template <int N>
+__device__ __forceinline__ void store_xr(void* out, int out_dtype, int64_t elem, const float* v) {
+    static_assert(N % 2 == 0, "pairs");
+    if (out_dtype == HBL_BF16) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        uint32_t h[N / 2];
+#pragma unroll
+        for (int i = 0; i < N / 2; ++i)
+            h[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){v[2 * i], v[2 * i + 1]}, bf16x2));
+        uint32_t* dst = reinterpret_cast<uint32_t*>(static_cast<uint16_t*>(out) + elem);
+        if constexpr (N == 2) dst[0] = h[0];
+        else if constexpr (N == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(h[0], h[1]);
+        else {
+#pragma unroll
+            for (int i = 0; i < N / 8; ++i)
+                reinterpret_cast<uint4*>(dst)[i] = make_uint4(h[4 * i], h[4 * i + 1], h[4 * i + 2], h[4 * i + 3]);
+        }
+    } else {
+        float* dst = static_cast<float*>(out) + elem;
+        if constexpr (N == 2) *reinterpret_cast<float2*>(dst) = make_float2(v[0], v[1]);
+        else {
+#pragma unroll
+            for (int i = 0; i < N / 4; ++i)
+                reinterpret_cast<float4*>(dst)[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+        }
+    }
+}
+
 // One token row per workgroup of 64*W threads; `row` and `tid` come from the caller so that the grouped
 // launch (several projections' rows in one grid) can run the same body.
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
@@ -227,6 +258,18 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int e = 0; e < CH; ++e) v[r][e] = v[r][e] * c_n;
+    }
+
+    if constexpr (BITS == 0) {
+        // transform only (Eq. 3-4 by themselves, and the backward pass of Eq. 8): `codes` is the output
+        // array and `code_offset` its element type
+        static_assert(CH >= 2, "transform-only rows hold at least two elements per lane");
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int g = exchanged ? (r % W) * R + (r / W) * W + wave : wave * R + r;
+            store_xr<CH>(codes, code_offset, row_off + (int64_t)(g * 64 + lane) * CH, v[r]);
+        }
+        return;
     }
 
     // per-token scale
@@ -605,12 +648,20 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
     // with every later rounding (max, fp64 sum, the gain product), so it is applied to the row
     // statistics and folded into the gain instead of costing one multiply per element.
     const float c_n = (float)(1.0 / sqrt((double)K));
-    constexpr bool FOLD = (LOG2K % 2) == 0;
+    constexpr bool FOLD = (LOG2K % 2) == 0 && BITS != 0;
     if constexpr (!FOLD) {
 #pragma unroll
         for (int j = 0; j < 16; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[j][e] = v[j][e] * c_n;
+    }
+
+    if constexpr (BITS == 0) {
+        // transform only: `codes` is the output array and `code_offset` its element type
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            store_xr<4>(codes, code_offset, row_off + (int64_t)((LC::qt(tid) ^ LC::qj(j)) << 2), v[j]);
+        return;
     }
 
     float gain, s_d;
@@ -655,7 +706,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
 
     constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
     constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
-    static_assert(!BF6OUT || BITS == 4, "bf6 records carry INT4 codes only");
+    static_assert(!BF6OUT || BITS == 4 || BITS == 0, "bf6 records carry INT4 codes only");
     if constexpr (BF6OUT) code_offset = 8;   // the table below is indexed by code + 8
     const float magic = kMagic + (float)code_offset;
     if constexpr (FOLD) gain = gain * c_n;
@@ -831,6 +882,33 @@ int launch_quant_grouped(const QuantGroupArgs& args, int bits, int x_dtype, hipS
     };
     if (bits == 8) return bf ? launch(quant_grouped_kernel<8, true>) : launch(quant_grouped_kernel<8, false>);
     return bf ? launch(quant_grouped_kernel<4, true>) : launch(quant_grouped_kernel<4, false>);
+}
+
+int launch_fwht_only(const void* x, int x_dtype, int64_t T, int64_t K, void* out, int out_dtype, hipStream_t stream) {
+    if (T == 0) return HBL_OK;
+    const bool bf = x_dtype == HBL_BF16;
+    int8_t* o = static_cast<int8_t*>(out);
+#define HBL_SMALL(L2K)                                                                                           \
+    case 1 << L2K:                                                                                               \
+        return bf ? launch_one<L2K, 1, 0, true, true>(x, T, o, nullptr, nullptr, 0.0f, out_dtype, stream)        \
+                  : launch_one<L2K, 1, 0, false, true>(x, T, o, nullptr, nullptr, 0.0f, out_dtype, stream);
+#define HBL_BIG(L2K)                                                                                             \
+    case 1 << L2K:                                                                                               \
+        return bf ? launch_bigrow<L2K, 0, true, false>(x, T, o, nullptr, nullptr, 0.0f, out_dtype, stream)       \
+                  : launch_bigrow<L2K, 0, false, false>(x, T, o, nullptr, nullptr, 0.0f, out_dtype, stream);
+    switch (K) {
+        HBL_SMALL(7)
+        HBL_SMALL(8)
+        HBL_SMALL(9)
+        HBL_SMALL(10)
+        HBL_SMALL(11)
+        HBL_BIG(12)
+        HBL_BIG(13)
+        HBL_BIG(14)
+        default: return HBL_E_SHAPE;
+    }
+#undef HBL_SMALL
+#undef HBL_BIG
 }
 
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,

@@ -71,6 +71,9 @@ inline bool bf6_path_supported(int64_t T, int64_t K, int bits, bool hadamard) {
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream);
 
+// Transform only: out[t] = Hadamard(x[t]) as fp32 or bf16 (K a power of two, 128..16384).
+int launch_fwht_only(const void* x, int x_dtype, int64_t T, int64_t K, void* out, int out_dtype, hipStream_t stream);
+
 // GEMM + epilogue. If acc_out != nullptr the raw int32 accumulators are written
 // (no scales, no code_sum needed); otherwise y (bf16) is written.
 int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,

@@ -29,7 +29,7 @@ EXPORTS = [
     "hbl_strerror", "hbl_last_hip_error", "hbl_ternarize_workspace_bytes", "hbl_ternarize_weights_absmean",
     "hbl_packed_bytes", "hbl_pack_ternary_2bit", "hbl_unpack_ternary_2bit", "hbl_workspace_bytes",
     "hbl_hbitlinear_forward", "hbl_plain_bitlinear_forward", "hbl_fwht_quant", "hbl_gemm_i32",
-    "hbl_gemm_dequant_bf16", "hbl_grouped_workspace_bytes", "hbl_bitlinear_forward_grouped",
+    "hbl_gemm_dequant_bf16", "hbl_grouped_workspace_bytes", "hbl_bitlinear_forward_grouped", "hbl_fwht",
 ]
 
 _lib = None
@@ -80,6 +80,7 @@ def lib():
         L.hbl_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, ci, vp, vp, vp, vp]
         L.hbl_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp, vp]
         L.hbl_gemm_dequant_bf16.argtypes = [vp, ci, vp, vp, i64, i64, vp, i64, vp, i64, vp, vp]
+        L.hbl_fwht.argtypes = [vp, ci, i64, i64, vp, ci, vp]
         L.hbl_grouped_workspace_bytes.restype = sz
         L.hbl_grouped_workspace_bytes.argtypes = [ctypes.POINTER(Problem), ci]
         L.hbl_bitlinear_forward_grouped.argtypes = [ctypes.POINTER(Problem), ci, f32, vp, sz, vp]
@@ -257,3 +258,13 @@ def bitlinear_forward_grouped(items, eps: float = EPS, workspace: Optional[torch
     _check(lib().hbl_bitlinear_forward_grouped(problems, n, eps, _ptr(workspace), workspace.numel(), _stream()),
            "bitlinear_forward_grouped")
     return [it[6] for it in items]
+
+
+def fwht(x: torch.Tensor, out_dtype: Optional[torch.dtype] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 3-4 alone (and the backward pass of Eq. 8 when x holds gradient rows): Hadamard(x) row by row."""
+    _dev_check(x, out)
+    T, K = x.shape
+    if out is None:
+        out = torch.empty((T, K), dtype=out_dtype or torch.float32, device=x.device)
+    _check(lib().hbl_fwht(_ptr(x), _x_dtype(x), T, K, _ptr(out), _x_dtype(out), _stream()), "fwht")
+    return out

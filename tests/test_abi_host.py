@@ -83,6 +83,10 @@ def test_argument_errors_before_any_launch(L):
     assert L.hbl_fwht_quant(P, hbl.BF16, 4, 256, 3, 1e-5, 1, 0, P, P, P, None) == hbl.E_BITS
     assert L.hbl_fwht_quant(P, hbl.BF16, 4, 256, 8, 1e-5, 1, 8, P, P, P, None) == hbl.E_BITS   # offset 8 is INT4 only
     assert L.hbl_fwht_quant(NUL, hbl.BF16, 4, 256, 4, 1e-5, 1, 0, P, P, P, None) == hbl.E_NULL
+    assert L.hbl_fwht(P, hbl.BF16, 4, 384, P, hbl.F32, None) == hbl.E_SHAPE     # power of two only
+    assert L.hbl_fwht(P, hbl.BF16, 4, 256, P, 5, None) == hbl.E_DTYPE
+    assert L.hbl_fwht(P, hbl.BF16, 4, 256, NUL, hbl.F32, None) == hbl.E_NULL
+    assert L.hbl_fwht(NUL, hbl.BF16, 0, 256, NUL, hbl.F32, None) == hbl.OK
     assert L.hbl_gemm_i32(P, 4, 100, P, 64, P, None) == hbl.E_SHAPE
     assert L.hbl_pack_ternary_2bit(P, 33, 256, P, None) == hbl.E_SHAPE
     assert L.hbl_pack_ternary_2bit(NUL, 32, 256, P, None) == hbl.E_NULL

@@ -584,3 +584,31 @@ def test_grouped_argument_errors(hbl):
         hbl.bitlinear_forward_grouped([(x[:, :192].contiguous(), packed, 64, al, 4, True, y)])
     assert e.value.status == hbl.E_SHAPE
     assert hbl.bitlinear_forward_grouped([]) == []
+
+
+@pytest.mark.parametrize("K", [128, 256, 512, 1024, 2048, 4096, 8192, 16384])
+@pytest.mark.parametrize("in_dtype", [synth.BF16, synth.F32])
+def test_fwht_only_forward_and_backward(hbl, K, in_dtype):
+    """The transform by itself (Eq. 3-4; Eq. 8 when applied to gradient rows): bit-exact against the
+    oracle in fp32 and in bf16 output, and applying it twice returns the input."""
+    note(f"fwht only K={K} in={in_dtype}")
+    site = synth.Site("g", 37, K, 32, x_dtype=in_dtype, outlier_frac=0.01, outlier_scale=30.0, seed=900 + K)
+    g = synth.make_x(site)
+    gd = dev_x(g)
+    want32 = O.hadamard_backward(g)
+    got32 = hbl.fwht(gd)
+    assert np.array_equal(got32.cpu().numpy().view(np.uint32), want32.view(np.uint32))
+    got16 = hbl.fwht(gd, out_dtype=torch.bfloat16)
+    assert np.array_equal(host_bf16_bits(got16), O.hadamard_backward(g, out_bf16=True))
+    twice = hbl.fwht(got32).cpu().numpy()
+    x32 = synth.bf16_bits_to_f32(g) if g.dtype == np.uint16 else g
+    assert np.abs(twice - x32).max() <= 1e-5 * np.abs(x32).max() * math.log2(K)
+
+
+def test_fwht_only_errors_and_empty(hbl):
+    note("fwht only errors")
+    x = torch.zeros((4, 384), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(hbl.HblError) as e:
+        hbl.fwht(x)
+    assert e.value.status == hbl.E_SHAPE
+    assert hbl.fwht(torch.zeros((0, 256), dtype=torch.float32, device="cuda")).shape == (0, 256)

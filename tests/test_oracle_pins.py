@@ -328,3 +328,54 @@ def test_hadamard_removes_outlier_damage():
     k1, e1 = stats(True)
     assert k0 > 20 and abs(k1) < 1.5
     assert e1 < 0.25 * e0
+
+
+# --- backward pass through the transform (Section 2.2, Eq. 8) -------------------------------------
+
+@pytest.mark.parametrize("n", [16, 256, 4096])
+def test_backward_adjoint_identity_on_exact_integers(n):
+    """<Hadamard(x), y> = <x, backward(y)> must hold exactly when every value is a small integer and
+    1/sqrt(n) a power of two (n a power of four): that is what "the gradient of the transform is the
+    transform" means, and a transposed or unnormalised backward fails it."""
+    rng = np.random.default_rng(n)
+    x = rng.integers(-8, 9, size=(3, n)).astype(np.float32)
+    y = rng.integers(-8, 9, size=(3, n)).astype(np.float32)
+    hx = O.fwht_rows(x).astype(np.float64)
+    by = O.hadamard_backward(y).astype(np.float64)
+    assert np.array_equal((hx * y).sum(1), (x * by).sum(1))
+
+
+@pytest.mark.parametrize("m", [1, 3, 6])
+def test_backward_is_gradient_of_linear_functional(m):
+    """L(x) = sum_i c_i * Hadamard(x)_i has dL/dx_j = sum_i c_i H[i][j]: the dense matrix (pinned on its
+    own by H H^T = I and the popcount form) gives the gradient in fp64, central differences confirm it."""
+    n = 1 << m
+    rng = np.random.default_rng(100 + m)
+    c = rng.standard_normal((1, n)).astype(np.float32)
+    H = O.hadamard_dense(m).astype(np.float64)
+    want = c.astype(np.float64) @ H                    # row vector times H = (H^T c)^T
+    got = O.hadamard_backward(c).astype(np.float64)
+    assert np.allclose(got, want, rtol=0, atol=4e-6 * np.abs(want).max())
+    x0 = rng.standard_normal(n)
+    L = lambda x: float((c[0].astype(np.float64) * (H @ x)).sum())
+    for j in range(min(n, 8)):
+        e = np.zeros(n)
+        e[j] = 1e-3
+        fd = (L(x0 + e) - L(x0 - e)) / 2e-3
+        assert abs(fd - got[0, j]) <= 1e-5 * max(1.0, abs(fd))
+
+
+def test_backward_undoes_forward_and_rounds_bf16_to_nearest_even():
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((5, 1024)).astype(np.float32)
+    back = O.hadamard_backward(O.fwht_rows(x))
+    assert np.abs(back - x).max() <= 5e-6 * np.abs(x).max() * math.log2(1024)
+    # bf16 in and out: equals widening, transforming in fp32 and an independent nearest-even narrowing
+    xb = synth.f32_to_bf16_bits(x)
+    want = synth.f32_to_bf16_bits(O.fwht_rows(synth.bf16_bits_to_f32(xb)))
+    assert np.array_equal(O.hadamard_backward(xb, out_bf16=True), want)
+    # a tie: 1 + 2^-8 is exactly half way between two bf16 values and must go to the even one (1.0)
+    tie = np.zeros((1, 4), np.float32)
+    tie[0, 0] = 2.0 * (1.0 + 2.0 ** -8)               # H_4 row sum / 2 keeps the value on entry 0..3
+    out = synth.bf16_bits_to_f32(O.hadamard_backward(tie, out_bf16=True))
+    assert np.array_equal(out, np.full((1, 4), 1.0, np.float32))
