@@ -139,6 +139,21 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Eq. 7 including its LN: y = Q_w(W) . Q_INT8/4(X_r), X_r = Hadamard(LN(X)) (hadamard != 0), or
+ * X_r = LN(X) for the plain BitLinear (hadamard == 0).  LN is the model's RMS normalisation
+ * (Section 2, first paragraph), fused into the quantiser launch so that the normalised row never
+ * touches HBM:
+ *     x_n[k] = (x[k] * r) * ln_gain[k],   r = (float)(1 / sqrt(mean_k x[k]^2 + ln_eps))
+ * with the mean of squares accumulated in fp64 and two fp32 multiplies per element.
+ *   ln_gain  device [K] fp32, 16-byte aligned;  ln_eps added to the mean of squares
+ * All other arguments, layouts and errors as hbl_hbitlinear_forward / hbl_plain_bitlinear_forward.
+ */
+int hbl_ln_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, const float* ln_gain,
+                             float ln_eps, int hadamard, const void* Wq_packed, int64_t N,
+                             const float* w_scales, int64_t n_scale_groups, int bits, float eps,
+                             void* y, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Several independent projections in one call (Eq. 7 applied to each): the result in every y is
  * bit-identical to hbl_hbitlinear_forward / hbl_plain_bitlinear_forward on that problem alone.
  * Meant for small batches (decode), where one projection's launches are too short to keep HBM
@@ -163,6 +178,8 @@ typedef struct hbl_problem {
     const float* w_scales;  /* device [n_scale_groups]                                 */
     int64_t n_scale_groups;
     void* y;                /* device [T, N] bf16 out                                  */
+    const float* ln_gain;   /* device [K] fp32: RMS-normalise x first (see hbl_ln_bitlinear_forward), or NULL */
+    float ln_eps;
 } hbl_problem;
 size_t hbl_grouped_workspace_bytes(const hbl_problem* problems, int n_problems);
 int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, float eps,
@@ -188,6 +205,11 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
 int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps,
                    int hadamard, int code_offset, int8_t* codes, float* s_dequant, int32_t* code_sum,
                    void* stream);
+
+/* hbl_fwht_quant with the RMS normalisation of hbl_ln_bitlinear_forward ahead of the transform. */
+int hbl_ln_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, const float* ln_gain, float ln_eps,
+                      int bits, float eps, int hadamard, int code_offset, int8_t* codes,
+                      float* s_dequant, int32_t* code_sum, void* stream);
 
 /*
  * The transform by itself: out[t] = H_m x[t] (Eq. 3-4, same butterfly order and 1/sqrt(K) factor as

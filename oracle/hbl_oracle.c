@@ -24,7 +24,8 @@
  *     Output order is the natural (Sylvester) order of the recursion.
  *   - butterfly stages run with ascending stride 1,2,4,...,n/2; means are
  *     accumulated in fp64 and rounded to fp32 once.
- *   - LN of Eq. 7 is outside this path: X is taken as already normalised.
+ *   - LN of Eq. 7 is a separate routine (hblo_rmsnorm, the model's RMS
+ *     normalisation); the forward routines take X as already normalised.
  *   - Eq. 8 (backward through the transform) is the same transform applied
  *     to the gradient rows, in the same fp32 butterfly order.
  *   - X is a row vector per token, W is [N out x K in]: Y[T x N] = Xq * Wq^T.
@@ -37,7 +38,9 @@
  * and a hand identity-weight case for the epilogue; for
  * hblo_hadamard_backward the adjoint identity <H x, y> = <x, H y> on exact
  * integers, the gradient of a linear functional through the dense matrix
- * (n <= 64) and an independent bf16 rounding.
+ * (n <= 64) and an independent bf16 rounding; for hblo_rmsnorm hand cases
+ * with power-of-two factors, unit mean square, scale invariance, the
+ * placement of ln_eps and an fp64 reference.
  */
 #include <math.h>
 #include <stdint.h>
@@ -196,6 +199,33 @@ static void load_row_f32(const void* x, int x_dtype, int64_t t, int64_t K, float
         const uint16_t* p = (const uint16_t*)x + t * K;
         for (int64_t k = 0; k < K; ++k) dst[k] = bf16_to_f32(p[k]);
     }
+}
+
+/* ------------------------------------------------------------------------
+ * LN of Eq. 7, read as the model's RMS normalisation (Section 2, first
+ * paragraph: LLaMA-like components, RMS normalisation, no bias):
+ *   x_n[k] = x[k] / sqrt( mean_k x[k]^2 + ln_eps ) * g[k]
+ * Evaluation order taken here (the paper is silent): the mean of squares in
+ * fp64, r = (float)(1 / sqrt(ms + ln_eps)) rounded to fp32 once, then
+ * x_n[k] = (x[k] * r) * g[k] as two fp32 multiplies.
+ *   x    [T,K] fp32 or bf16 bit patterns;  g [K] fp32;  out [T,K] fp32
+ * ---------------------------------------------------------------------- */
+int hblo_rmsnorm(const void* x, int x_dtype, int64_t T, int64_t K, const float* g, float ln_eps, float* out) {
+    if (!x || !g || !out || T < 0 || K <= 0) return HBLO_E_ARG;
+    if (x_dtype != HBLO_F32 && x_dtype != HBLO_BF16) return HBLO_E_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        float* u = out + t * K;
+        load_row_f32(x, x_dtype, t, K, u);
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) ss += (double)u[k] * (double)u[k];
+        const float r = (float)(1.0 / sqrt(ss / (double)K + (double)ln_eps));
+        for (int64_t k = 0; k < K; ++k) {
+            const float scaled = u[k] * r;
+            u[k] = scaled * g[k];
+        }
+    }
+    return HBLO_OK;
 }
 
 /* ------------------------------------------------------------------------

@@ -48,6 +48,7 @@ def lib():
         _lib.hblo_ternarize_weights_absmean.argtypes = [vp, i64, i64, f32, vp, vp]
         _lib.hblo_hadamard_dense.argtypes = [ci, vp]
         _lib.hblo_fwht_rows.argtypes = [vp, i64, i64]
+        _lib.hblo_rmsnorm.argtypes = [vp, ci, i64, i64, vp, f32, vp]
         _lib.hblo_hadamard_backward.argtypes = [vp, ci, i64, i64, vp, ci]
         _lib.hblo_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, vp, vp, vp]
         _lib.hblo_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp]
@@ -100,6 +101,17 @@ def fwht_rows(x: np.ndarray) -> np.ndarray:
     out = np.array(x, dtype=np.float32, order="C", copy=True)
     T, n = out.shape
     _check(lib().hblo_fwht_rows(_p(out), T, n), "fwht_rows")
+    return out
+
+
+def rmsnorm(x: np.ndarray, gain: np.ndarray, ln_eps: float) -> np.ndarray:
+    """LN of Eq. 7 as RMS normalisation: x [T,K] fp32 / bf16 bits, gain [K] fp32 -> fp32 [T,K]."""
+    x = np.ascontiguousarray(x)
+    gain = np.ascontiguousarray(gain, dtype=np.float32)
+    T, K = x.shape
+    assert gain.shape == (K,)
+    out = np.empty((T, K), dtype=np.float32)
+    _check(lib().hblo_rmsnorm(_p(x), _x_dtype(x), T, K, _p(gain), ln_eps, _p(out)), "rmsnorm")
     return out
 
 

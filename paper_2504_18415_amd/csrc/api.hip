@@ -69,7 +69,8 @@ void fill_decode_problem(DecodeProblem& dp, const Workspace& ws, int32_t* partia
 
 int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
             const float* w_scales, int64_t groups, int bits, float eps, void* y, void* workspace,
-            size_t workspace_bytes, void* stream, bool hadamard) {
+            size_t workspace_bytes, void* stream, bool hadamard, const float* ln_gain = nullptr,
+            float ln_eps = 0.0f) {
     int rc = check_forward_args(x, x_dtype, T, K, Wq_packed, N, w_scales, groups, bits, y, workspace, hadamard);
     if (rc != HBL_OK) return rc;
     if (T == 0) return HBL_OK;
@@ -80,13 +81,15 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     // MFMA rate).  HBL_NO_F6F4=1 keeps everything on the int8 path.
     static const bool no_f6f4 = getenv("HBL_NO_F6F4") != nullptr;
     if (!no_f6f4 && bf6_path_supported(T, K, bits, hadamard)) {
-        rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, kCodesBf6, s);
+        rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, kCodesBf6, s,
+                               ln_gain, ln_eps);
         if (rc != HBL_OK) return rc;
         return launch_ternary_gemm_f6f4(ws.codes, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, s);
     }
     // otherwise INT4 codes travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs
     const int code_offset = bits == 4 ? 8 : 0;
-    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, code_offset, s);
+    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, code_offset, s,
+                           ln_gain, ln_eps);
     if (rc != HBL_OK) return rc;
     static const bool no_stream = getenv("HBL_NO_DECODE_STREAM") != nullptr;
     if (!no_stream && decode_stream_preferred(T, K, N)) {   // a handful of tokens: one weight-streaming launch
@@ -205,6 +208,7 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
         const int rc = check_forward_args(q.x, q.x_dtype, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups,
                                           q.bits, q.y, workspace, q.hadamard != 0);
         if (rc != HBL_OK) return rc;
+        if (q.ln_gain && (reinterpret_cast<uintptr_t>(q.ln_gain) & 15u) != 0) return HBL_E_ALIGN;
         if (q.T > 64 || q.bits != problems[0].bits || q.x_dtype != problems[0].x_dtype) grouped = false;
         any_rows = any_rows || q.T > 0;
     }
@@ -218,7 +222,7 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
             const hbl_problem& q = problems[i];
             const size_t region = group_region_bytes(q);
             const int rc = forward(q.x, q.x_dtype, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups, q.bits, eps,
-                                   q.y, base, region, stream, q.hadamard != 0);
+                                   q.y, base, region, stream, q.hadamard != 0, q.ln_gain, q.ln_eps);
             if (rc != HBL_OK) return rc;
             base += region;
         }
@@ -245,6 +249,8 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
             qp.hadamard = q.hadamard != 0;
             qp.code_offset = code_offset;
             qp.row_begin = rows;
+            qp.ln_gain = q.ln_gain;
+            qp.ln_eps = q.ln_eps;
             rows += (int)q.T;
             fill_decode_problem(da.p[da.n++], ws, partial, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups,
                                 code_offset, q.y);
@@ -255,6 +261,33 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
     const int rc = launch_quant_grouped(qa, problems[0].bits, problems[0].x_dtype, s);
     if (rc != HBL_OK) return rc;
     return launch_decode_gemm(da, s);
+}
+
+int hbl_ln_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, const float* ln_gain, float ln_eps,
+                             int hadamard, const void* Wq_packed, int64_t N, const float* w_scales,
+                             int64_t n_scale_groups, int bits, float eps, void* y, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    if (T > 0 && !ln_gain) return HBL_E_NULL;
+    if (!aligned16(ln_gain)) return HBL_E_ALIGN;
+    return forward(x, x_dtype, T, K, Wq_packed, N, w_scales, n_scale_groups, bits, eps, y, workspace,
+                   workspace_bytes, stream, hadamard != 0, ln_gain, ln_eps);
+}
+
+int hbl_ln_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, const float* ln_gain, float ln_eps, int bits,
+                      float eps, int hadamard, int code_offset, int8_t* codes, float* s_dequant, int32_t* code_sum,
+                      void* stream) {
+    if (code_offset != HBL_CODES_INT8 && !((code_offset == HBL_CODES_UINT4_PLUS8 || code_offset == HBL_CODES_BF6) && bits == 4))
+        return HBL_E_BITS;
+    if (code_offset == HBL_CODES_BF6 && K < 512) return HBL_E_SHAPE;
+    if (bits != 4 && bits != 8) return HBL_E_BITS;
+    if (x_dtype != HBL_F32 && x_dtype != HBL_BF16) return HBL_E_DTYPE;
+    int rc = check_gemm_shape(T, K, 32, hadamard != 0);
+    if (rc != HBL_OK) return rc;
+    if (T == 0) return HBL_OK;
+    if (!x || !codes || !s_dequant || !ln_gain) return HBL_E_NULL;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(ln_gain)) return HBL_E_ALIGN;
+    return launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard != 0, codes, s_dequant, code_sum, code_offset,
+                             static_cast<hipStream_t>(stream), ln_gain, ln_eps);
 }
 
 int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int hadamard,

@@ -126,6 +126,33 @@ __device__ __forceinline__ void bf6_store_pair(int8_t* row_codes, int chunk8, ui
     }
 }
 
+// Per-row scalars of the front end: the quantiser's epsilon and, if ln_gain != nullptr, the RMS
+// normalisation that precedes the transform in Eq. 7 (LN; the model's norm is RMSNorm, Section 2):
+//   x_n[k] = (x[k] * r) * ln_gain[k],  r = (float)(1 / sqrt(mean_k x[k]^2 + ln_eps)),
+// mean of squares accumulated in fp64 (each square is exact there), r rounded to fp32 once, two fp32
+// multiplies per element.
+struct RowParams {
+    float eps;
+    const float* ln_gain;   // [K] fp32 or nullptr
+    float ln_eps;
+};
+
+// r of the row from this thread's partial sum of squares `ss`: wave butterfly, then a fixed-order
+// combine of the NW per-wave sums through `red` (NW doubles of LDS; one barrier).
+template <int NW>
+__device__ __forceinline__ float rms_factor(double ss, double* red, int lane, int wave, int K, float ln_eps) {
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) ss += __shfl_xor(ss, sft, 64);
+    if constexpr (NW > 1) {
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+        ss = red[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) ss += red[w];
+    }
+    return (float)(1.0 / sqrt(ss / (double)K + (double)ln_eps));
+}
+
 // Transform-only output (BITS == 0 in the bodies below): N consecutive values of x_r as fp32 or, rounded
 // to nearest even, as bf16.
 template <int N>
@@ -162,7 +189,7 @@ __device__ __forceinline__ void store_xr(void* out, int out_dtype, int64_t elem,
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
 __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void* __restrict__ x,
                                                 int8_t* __restrict__ codes, float* __restrict__ s_dequant,
-                                                int32_t* __restrict__ code_sum, float eps, int code_offset) {
+                                                int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
     constexpr int K = 1 << LOG2K;
     constexpr int NT = 64 * W;
     constexpr int E = K / NT;            // elements per thread
@@ -182,6 +209,23 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
     float v[R][CH];
 #pragma unroll
     for (int r = 0; r < R; ++r) load_chunk<CH, BF16>(x, row_off + (int64_t)((wave * R + r) * 64 + lane) * CH, v[r]);
+
+    if (rp.ln_gain) {   // uniform: RMS normalisation ahead of the transform
+        __shared__ double red_n[W];
+        double ss = 0.0;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < CH; ++e) ss += (double)v[r][e] * (double)v[r][e];
+        const float rn = rms_factor<W>(ss, red_n, lane, wave, K, rp.ln_eps);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float gv[CH];
+            load_chunk<CH, false>(rp.ln_gain, (int64_t)((wave * R + r) * 64 + lane) * CH, gv);
+#pragma unroll
+            for (int e = 0; e < CH; ++e) v[r][e] = (v[r][e] * rn) * gv[e];
+        }
+    }
 
     bool exchanged = false;  // register slot r holds chunk g = wave*R + r until the LDS exchange
 
@@ -289,7 +333,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
 #pragma unroll
             for (int w = 1; w < W; ++w) m = fmaxf(m, red_f[w]);
         }
-        gain = 127.0f / (m + eps);
+        gain = 127.0f / (m + rp.eps);
         s_d = m / 127.0f;
     } else {
         double s = 0.0;
@@ -307,7 +351,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
             for (int w = 1; w < W; ++w) s += red_d[w];
         }
         const float beta = (float)(s / (double)K);
-        gain = kRoot7 / (beta + eps);
+        gain = kRoot7 / (beta + rp.eps);
         s_d = beta / kRoot7;
     }
 
@@ -372,13 +416,13 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
 __global__ __launch_bounds__(64 * W) void fwht_quant_kernel(const void* __restrict__ x, int8_t* __restrict__ codes,
                                                             float* __restrict__ s_dequant,
-                                                            int32_t* __restrict__ code_sum, float eps, int code_offset) {
-    fwht_quant_body<LOG2K, W, BITS, BF16, HADAMARD>(blockIdx.x, threadIdx.x, x, codes, s_dequant, code_sum, eps,
+                                                            int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
+    fwht_quant_body<LOG2K, W, BITS, BF16, HADAMARD>(blockIdx.x, threadIdx.x, x, codes, s_dequant, code_sum, rp,
                                                     code_offset);
 }
 
 template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
-int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, float eps,
+int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, RowParams rp,
                int code_offset, hipStream_t stream) {
     constexpr int K = 1 << LOG2K;
     const size_t lds = (HADAMARD && W > 1) ? sizeof(float) * K : 0;
@@ -390,7 +434,7 @@ int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_
         if (e != hipSuccess) return note_hip_error(e);
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, eps, code_offset);
+    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, rp, code_offset);
     return after_launch();
 }
 
@@ -400,7 +444,7 @@ int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_
 template <int BITS, bool BF16>
 __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const void* __restrict__ x, int K,
                                                    int8_t* __restrict__ codes, float* __restrict__ s_dequant,
-                                                   int32_t* __restrict__ code_sum, float eps, int code_offset) {
+                                                   int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
     constexpr int MAXC = 8;
     __shared__ double red_d[4];
     __shared__ float red_f[4];
@@ -419,6 +463,25 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
             for (int e = 0; e < 8; ++e) v[c][e] = 0.0f;
         }
     }
+    if (rp.ln_gain) {   // uniform: RMS normalisation of the row (chunks past the row hold zeros)
+        __shared__ double red_n[4];
+        double ss = 0.0;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += (double)v[c][e] * (double)v[c][e];
+        const float rn = rms_factor<4>(ss, red_n, lane, wave, K, rp.ln_eps);
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int ch = c * 256 + tid;
+            if (ch < nchunks) {
+                float gv[8];
+                load_chunk<8, false>(rp.ln_gain, (int64_t)ch * 8, gv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[c][e] = (v[c][e] * rn) * gv[e];
+            }
+        }
+    }
     float gain, s_d;
     if constexpr (BITS == 8) {
         float m = 0.0f;
@@ -431,7 +494,7 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
         if (lane == 0) red_f[wave] = m;
         __syncthreads();
         m = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
-        gain = 127.0f / (m + eps);
+        gain = 127.0f / (m + rp.eps);
         s_d = m / 127.0f;
     } else {
         double s = 0.0;
@@ -445,7 +508,7 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
         __syncthreads();
         s = ((red_d[0] + red_d[1]) + red_d[2]) + red_d[3];
         const float beta = (float)(s / (double)K);
-        gain = kRoot7 / (beta + eps);
+        gain = kRoot7 / (beta + rp.eps);
         s_d = beta / kRoot7;
     }
     constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
@@ -486,20 +549,20 @@ template <int BITS, bool BF16>
 __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restrict__ x, int K,
                                                             int8_t* __restrict__ codes,
                                                             float* __restrict__ s_dequant,
-                                                            int32_t* __restrict__ code_sum, float eps, int code_offset) {
-    quant_generic_body<BITS, BF16>(blockIdx.x, threadIdx.x, x, K, codes, s_dequant, code_sum, eps, code_offset);
+                                                            int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
+    quant_generic_body<BITS, BF16>(blockIdx.x, threadIdx.x, x, K, codes, s_dequant, code_sum, rp, code_offset);
 }
 
-int launch_generic(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int8_t* codes,
+int launch_generic(const void* x, int x_dtype, int64_t T, int64_t K, int bits, RowParams rp, int8_t* codes,
                    float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     const dim3 grid((unsigned)T), block(256);
     const bool bf = x_dtype == HBL_BF16;
     if (bits == 8) {
-        if (bf) hipLaunchKernelGGL((quant_generic_kernel<8, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps, code_offset);
-        else    hipLaunchKernelGGL((quant_generic_kernel<8, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps, code_offset);
+        if (bf) hipLaunchKernelGGL((quant_generic_kernel<8, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, rp, code_offset);
+        else    hipLaunchKernelGGL((quant_generic_kernel<8, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, rp, code_offset);
     } else {
-        if (bf) hipLaunchKernelGGL((quant_generic_kernel<4, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps, code_offset);
-        else    hipLaunchKernelGGL((quant_generic_kernel<4, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, eps, code_offset);
+        if (bf) hipLaunchKernelGGL((quant_generic_kernel<4, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, rp, code_offset);
+        else    hipLaunchKernelGGL((quant_generic_kernel<4, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, rp, code_offset);
     }
     return after_launch();
 }
@@ -544,10 +607,13 @@ __host__ __device__ constexpr uint32_t swz16(uint32_t q) { return q ^ ((q >> 4) 
 // BF6OUT (INT4 only): instead of one byte per code, write the form the fp6 x fp4 GEMM reads - per 32
 // consecutive features a 32-byte record whose first 24 bytes hold the 32 codes as bf6 (e3m2) values,
 // feature i at bits [6i, 6i+6); every integer in [-8, 7] is exact in that format.
-template <int LOG2K, int BITS, bool BF16, bool BF6OUT>
+// NORM: compiled with the RMS-normalisation prologue (taken when rp.ln_gain is set).  A template switch
+// rather than the run-time test alone: the prologue's presence changes the register allocation of the
+// whole body, and the plain prefill path should not pay for it.
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
 __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid, const void* __restrict__ x,
                                                        int8_t* __restrict__ codes, float* __restrict__ s_dequant,
-                                                       int32_t* __restrict__ code_sum, float eps, int code_offset) {
+                                                       int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
     constexpr int K = 1 << LOG2K;
     constexpr int NT = K / 64;
     constexpr int W = NT / 64;
@@ -582,6 +648,25 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
         for (int j = 0; j < 16; ++j) {
             const float4 raw = src[j];
             v[j][0] = raw.x; v[j][1] = raw.y; v[j][2] = raw.z; v[j][3] = raw.w;
+        }
+    }
+
+    if (NORM && rp.ln_gain) {   // uniform: RMS normalisation ahead of the transform (layout A: elements tid*64 + 4j + e)
+        __shared__ double red_n[W];
+        double ss = 0.0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ss += (double)v[j][e] * (double)v[j][e];
+        const float rn = rms_factor<W>(ss, red_n, lane, wave, K, rp.ln_eps);
+        const float4* gsrc = reinterpret_cast<const float4*>(rp.ln_gain + tid * 64);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float4 gq = gsrc[j];
+            v[j][0] = (v[j][0] * rn) * gq.x;
+            v[j][1] = (v[j][1] * rn) * gq.y;
+            v[j][2] = (v[j][2] * rn) * gq.z;
+            v[j][3] = (v[j][3] * rn) * gq.w;
         }
     }
 
@@ -681,7 +766,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
             for (int w = 1; w < W; ++w) m = fmaxf(m, red_f[w]);
         }
         if constexpr (FOLD) m = m * c_n;
-        gain = 127.0f / (m + eps);
+        gain = 127.0f / (m + rp.eps);
         s_d = m / 127.0f;
     } else {
         double s = 0.0;
@@ -700,7 +785,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
         }
         if constexpr (FOLD) s = s * (double)c_n;
         const float beta = (float)(s / (double)K);
-        gain = kRoot7 / (beta + eps);
+        gain = kRoot7 / (beta + rp.eps);
         s_d = beta / kRoot7;
     }
 
@@ -759,20 +844,36 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
     if (tid == 0) s_dequant[row] = s_d;
 }
 
-template <int LOG2K, int BITS, bool BF16, bool BF6OUT>
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
 __global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
     const void* __restrict__ x, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
-    int32_t* __restrict__ code_sum, float eps, int code_offset) {
-    fwht_quant_bigrow_body<LOG2K, BITS, BF16, BF6OUT>(blockIdx.x, threadIdx.x, x, codes, s_dequant, code_sum, eps,
-                                                      code_offset);
+    int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
+    fwht_quant_bigrow_body<LOG2K, BITS, BF16, BF6OUT, NORM>(blockIdx.x, threadIdx.x, x, codes, s_dequant, code_sum,
+                                                            rp, code_offset);
 }
 
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
+int launch_bigrow_form(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, RowParams rp,
+                       int code_offset, hipStream_t stream);
+
 template <int LOG2K, int BITS, bool BF16, bool BF6OUT = false>
-int launch_bigrow(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, float eps,
+int launch_bigrow(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, RowParams rp,
                   int code_offset, hipStream_t stream) {
+    if constexpr (BITS != 0) {
+        if (rp.ln_gain)
+            return launch_bigrow_form<LOG2K, BITS, BF16, BF6OUT, true>(x, T, codes, s_dequant, code_sum, rp, code_offset,
+                                                                       stream);
+    }
+    return launch_bigrow_form<LOG2K, BITS, BF16, BF6OUT, false>(x, T, codes, s_dequant, code_sum, rp, code_offset,
+                                                                stream);
+}
+
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
+int launch_bigrow_form(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, RowParams rp,
+                       int code_offset, hipStream_t stream) {
     constexpr int K = 1 << LOG2K;
     constexpr size_t lds = sizeof(float) * K;
-    auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16, BF6OUT>;
+    auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16, BF6OUT, NORM>;
     static std::atomic<bool> attr_set{false};   // once per process (one device)
     if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -780,38 +881,38 @@ int launch_bigrow(const void* x, int64_t T, int8_t* codes, float* s_dequant, int
         if (e != hipSuccess) return note_hip_error(e);
         attr_set.store(true, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(K / 64), lds, stream, x, codes, s_dequant, code_sum, eps,
+    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(K / 64), lds, stream, x, codes, s_dequant, code_sum, rp,
                        code_offset);
     return after_launch();
 }
 
 template <int LOG2K>
-int dispatch_bigrow(const void* x, int x_dtype, int64_t T, int bits, float eps, int8_t* codes, float* s_dequant,
+int dispatch_bigrow(const void* x, int x_dtype, int64_t T, int bits, RowParams rp, int8_t* codes, float* s_dequant,
                     int32_t* code_sum, int code_offset, hipStream_t stream) {
     const bool bf = x_dtype == HBL_BF16;
     if (code_offset == kCodesBf6)
-        return bf ? launch_bigrow<LOG2K, 4, true, true>(x, T, codes, s_dequant, code_sum, eps, 8, stream)
-                  : launch_bigrow<LOG2K, 4, false, true>(x, T, codes, s_dequant, code_sum, eps, 8, stream);
-    if (bits == 8) return bf ? launch_bigrow<LOG2K, 8, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
-                             : launch_bigrow<LOG2K, 8, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
-    return bf ? launch_bigrow<LOG2K, 4, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
-              : launch_bigrow<LOG2K, 4, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
+        return bf ? launch_bigrow<LOG2K, 4, true, true>(x, T, codes, s_dequant, code_sum, rp, 8, stream)
+                  : launch_bigrow<LOG2K, 4, false, true>(x, T, codes, s_dequant, code_sum, rp, 8, stream);
+    if (bits == 8) return bf ? launch_bigrow<LOG2K, 8, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream)
+                             : launch_bigrow<LOG2K, 8, false>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream);
+    return bf ? launch_bigrow<LOG2K, 4, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream)
+              : launch_bigrow<LOG2K, 4, false>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream);
 }
 
 template <int LOG2K, int W>
-int dispatch(const void* x, int x_dtype, int64_t T, int bits, float eps, bool hadamard, int8_t* codes,
+int dispatch(const void* x, int x_dtype, int64_t T, int bits, RowParams rp, bool hadamard, int8_t* codes,
              float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     const bool bf = x_dtype == HBL_BF16;
     if (hadamard) {
-        if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
-                                 : launch_one<LOG2K, W, 8, false, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
-        return bf ? launch_one<LOG2K, W, 4, true, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
-                  : launch_one<LOG2K, W, 4, false, true>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
+        if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream)
+                                 : launch_one<LOG2K, W, 8, false, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream);
+        return bf ? launch_one<LOG2K, W, 4, true, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream)
+                  : launch_one<LOG2K, W, 4, false, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream);
     }
-    if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
-                             : launch_one<LOG2K, W, 8, false, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
-    return bf ? launch_one<LOG2K, W, 4, true, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream)
-              : launch_one<LOG2K, W, 4, false, false>(x, T, codes, s_dequant, code_sum, eps, code_offset, stream);
+    if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, false>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream)
+                             : launch_one<LOG2K, W, 8, false, false>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream);
+    return bf ? launch_one<LOG2K, W, 4, true, false>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream)
+              : launch_one<LOG2K, W, 4, false, false>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream);
 }
 
 // Rows of several projections in one grid (small-batch path): workgroup -> (problem, row), then the
@@ -827,20 +928,20 @@ __global__ __launch_bounds__(256) void quant_grouped_kernel(const QuantGroupArgs
     const int64_t row = (int)blockIdx.x - p.row_begin;
     const int tid = threadIdx.x;
     if (!p.hadamard) {
-        quant_generic_body<BITS, BF16>(row, tid, p.x, p.K, p.codes, p.s_dequant, p.code_sum, a.eps, p.code_offset);
+        quant_generic_body<BITS, BF16>(row, tid, p.x, p.K, p.codes, p.s_dequant, p.code_sum, RowParams{a.eps, p.ln_gain, p.ln_eps}, p.code_offset);
         return;
     }
 #define HBL_SMALL_ROW(L2K)                                                                                    \
     case 1 << L2K:                                                                                            \
         if (tid < 64)                                                                                         \
-            fwht_quant_body<L2K, 1, BITS, BF16, true>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum, a.eps, \
+            fwht_quant_body<L2K, 1, BITS, BF16, true>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum, RowParams{a.eps, p.ln_gain, p.ln_eps}, \
                                                       p.code_offset);                                         \
         return;
 #define HBL_BIG_ROW(L2K)                                                                                      \
     case 1 << L2K:                                                                                            \
         if (tid < (1 << L2K) / 64)                                                                            \
-            fwht_quant_bigrow_body<L2K, BITS, BF16, false>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum,   \
-                                                           a.eps, p.code_offset);                             \
+            fwht_quant_bigrow_body<L2K, BITS, BF16, false, true>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum,   \
+                                                           RowParams{a.eps, p.ln_gain, p.ln_eps}, p.code_offset);                             \
         return;
     switch (p.K) {
         HBL_SMALL_ROW(7)
@@ -890,12 +991,12 @@ int launch_fwht_only(const void* x, int x_dtype, int64_t T, int64_t K, void* out
     int8_t* o = static_cast<int8_t*>(out);
 #define HBL_SMALL(L2K)                                                                                           \
     case 1 << L2K:                                                                                               \
-        return bf ? launch_one<L2K, 1, 0, true, true>(x, T, o, nullptr, nullptr, 0.0f, out_dtype, stream)        \
-                  : launch_one<L2K, 1, 0, false, true>(x, T, o, nullptr, nullptr, 0.0f, out_dtype, stream);
+        return bf ? launch_one<L2K, 1, 0, true, true>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f}, out_dtype, stream)        \
+                  : launch_one<L2K, 1, 0, false, true>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f}, out_dtype, stream);
 #define HBL_BIG(L2K)                                                                                             \
     case 1 << L2K:                                                                                               \
-        return bf ? launch_bigrow<L2K, 0, true, false>(x, T, o, nullptr, nullptr, 0.0f, out_dtype, stream)       \
-                  : launch_bigrow<L2K, 0, false, false>(x, T, o, nullptr, nullptr, 0.0f, out_dtype, stream);
+        return bf ? launch_bigrow<L2K, 0, true, false>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f}, out_dtype, stream)       \
+                  : launch_bigrow<L2K, 0, false, false>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f}, out_dtype, stream);
     switch (K) {
         HBL_SMALL(7)
         HBL_SMALL(8)
@@ -912,24 +1013,26 @@ int launch_fwht_only(const void* x, int x_dtype, int64_t T, int64_t K, void* out
 }
 
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
-                      int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
+                      int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream,
+                      const float* ln_gain, float ln_eps) {
     if (T == 0) return HBL_OK;
+    const RowParams rp = {eps, ln_gain, ln_eps};
     if (code_offset == kCodesBf6 && (bits != 4 || K < 512)) return HBL_E_SHAPE;   // records need 8-element chunks
-    if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
+    if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
     if (hadamard && (code_offset == kCodesBf6 || !getenv("HBL_FWHT_OLD"))) {
-        if (K == 4096) return dispatch_bigrow<12>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
-        if (K == 8192) return dispatch_bigrow<13>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
-        if (K == 16384) return dispatch_bigrow<14>(x, x_dtype, T, bits, eps, codes, s_dequant, code_sum, code_offset, stream);
+        if (K == 4096) return dispatch_bigrow<12>(x, x_dtype, T, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
+        if (K == 8192) return dispatch_bigrow<13>(x, x_dtype, T, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
+        if (K == 16384) return dispatch_bigrow<14>(x, x_dtype, T, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
     }
     switch (K) {
-        case 128:   return dispatch<7, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 256:   return dispatch<8, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 512:   return dispatch<9, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 1024:  return dispatch<10, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 2048:  return dispatch<11, 1>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 4096:  return dispatch<12, 2>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 8192:  return dispatch<13, 4>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 16384: return dispatch<14, 4>(x, x_dtype, T, bits, eps, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 128:   return dispatch<7, 1>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 256:   return dispatch<8, 1>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 512:   return dispatch<9, 1>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 1024:  return dispatch<10, 1>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 2048:  return dispatch<11, 1>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 4096:  return dispatch<12, 2>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 8192:  return dispatch<13, 4>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 16384: return dispatch<14, 4>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
         default:    return HBL_E_SHAPE;
     }
 }

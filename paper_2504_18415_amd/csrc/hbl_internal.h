@@ -68,8 +68,10 @@ inline bool bf6_path_supported(int64_t T, int64_t K, int bits, bool hadamard) {
     (void)hadamard;
     return bits == 4 && T > 64 && K >= 512;
 }
+// ln_gain != nullptr: RMS-normalise each row with that gain vector [K] and ln_eps first (LN of Eq. 7).
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
-                      int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream);
+                      int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream,
+                      const float* ln_gain = nullptr, float ln_eps = 0.0f);
 
 // Transform only: out[t] = Hadamard(x[t]) as fp32 or bf16 (K a power of two, 128..16384).
 int launch_fwht_only(const void* x, int x_dtype, int64_t T, int64_t K, void* out, int out_dtype, hipStream_t stream);
@@ -102,6 +104,8 @@ struct QuantProblem {
     int hadamard;
     int code_offset;
     int row_begin;        // first workgroup (= row) of this problem in the grouped grid
+    const float* ln_gain; // [K] RMS-norm gain ahead of the transform, or nullptr
+    float ln_eps;
 };
 struct QuantGroupArgs {
     QuantProblem p[kMaxGroup];

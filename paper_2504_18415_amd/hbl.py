@@ -30,6 +30,7 @@ EXPORTS = [
     "hbl_packed_bytes", "hbl_pack_ternary_2bit", "hbl_unpack_ternary_2bit", "hbl_workspace_bytes",
     "hbl_hbitlinear_forward", "hbl_plain_bitlinear_forward", "hbl_fwht_quant", "hbl_gemm_i32",
     "hbl_gemm_dequant_bf16", "hbl_grouped_workspace_bytes", "hbl_bitlinear_forward_grouped", "hbl_fwht",
+    "hbl_ln_bitlinear_forward", "hbl_ln_fwht_quant",
 ]
 
 _lib = None
@@ -40,7 +41,8 @@ class Problem(ctypes.Structure):
     _fields_ = [("x", ctypes.c_void_p), ("x_dtype", ctypes.c_int), ("bits", ctypes.c_int),
                 ("hadamard", ctypes.c_int), ("reserved", ctypes.c_int), ("T", ctypes.c_int64),
                 ("K", ctypes.c_int64), ("N", ctypes.c_int64), ("Wq_packed", ctypes.c_void_p),
-                ("w_scales", ctypes.c_void_p), ("n_scale_groups", ctypes.c_int64), ("y", ctypes.c_void_p)]
+                ("w_scales", ctypes.c_void_p), ("n_scale_groups", ctypes.c_int64), ("y", ctypes.c_void_p),
+                ("ln_gain", ctypes.c_void_p), ("ln_eps", ctypes.c_float)]
 
 
 class HblError(RuntimeError):
@@ -81,6 +83,8 @@ def lib():
         L.hbl_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp, vp]
         L.hbl_gemm_dequant_bf16.argtypes = [vp, ci, vp, vp, i64, i64, vp, i64, vp, i64, vp, vp]
         L.hbl_fwht.argtypes = [vp, ci, i64, i64, vp, ci, vp]
+        L.hbl_ln_bitlinear_forward.argtypes = [vp, ci, i64, i64, vp, f32, ci, vp, i64, vp, i64, ci, f32, vp, vp, sz, vp]
+        L.hbl_ln_fwht_quant.argtypes = [vp, ci, i64, i64, vp, f32, ci, f32, ci, ci, vp, vp, vp, vp]
         L.hbl_grouped_workspace_bytes.restype = sz
         L.hbl_grouped_workspace_bytes.argtypes = [ctypes.POINTER(Problem), ci]
         L.hbl_bitlinear_forward_grouped.argtypes = [ctypes.POINTER(Problem), ci, f32, vp, sz, vp]
@@ -226,14 +230,16 @@ def fwht_quant_into(x: torch.Tensor, bits: int, hadamard: bool, codes: torch.Ten
 
 
 def make_problems(items) -> "ctypes.Array":
-    """items: iterable of (x, Wq_packed, N, w_scales, bits, hadamard, y) -> ``hbl_problem`` array."""
+    """items: iterable of (x, Wq_packed, N, w_scales, bits, hadamard, y[, ln_gain, ln_eps]) -> ``hbl_problem`` array."""
     items = list(items)
     arr = (Problem * max(len(items), 1))()
-    for i, (x, Wq_packed, N, w_scales, bits, hadamard, y) in enumerate(items):
-        _dev_check(x, Wq_packed, w_scales, y)
+    for i, it in enumerate(items):
+        x, Wq_packed, N, w_scales, bits, hadamard, y = it[:7]
+        ln_gain, ln_eps = (it[7], it[8]) if len(it) > 7 else (None, 0.0)
+        _dev_check(x, Wq_packed, w_scales, y, ln_gain)
         T, K = x.shape
         arr[i] = Problem(_ptr(x), _x_dtype(x), bits, int(bool(hadamard)), 0, T, K, N, _ptr(Wq_packed),
-                         _ptr(w_scales), w_scales.numel(), _ptr(y))
+                         _ptr(w_scales), w_scales.numel(), _ptr(y), _ptr(ln_gain), ln_eps)
     return arr
 
 
@@ -268,3 +274,32 @@ def fwht(x: torch.Tensor, out_dtype: Optional[torch.dtype] = None, out: Optional
         out = torch.empty((T, K), dtype=out_dtype or torch.float32, device=x.device)
     _check(lib().hbl_fwht(_ptr(x), _x_dtype(x), T, K, _ptr(out), _x_dtype(out), _stream()), "fwht")
     return out
+
+
+def ln_bitlinear_forward(x: torch.Tensor, ln_gain: torch.Tensor, ln_eps: float, hadamard: bool,
+                         Wq_packed: torch.Tensor, N: int, w_scales: torch.Tensor, bits: int = 4, eps: float = EPS,
+                         y: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 7 with its LN (RMS normalisation with gain ``ln_gain`` [K] fp32) fused into the quantiser launch."""
+    _dev_check(x, ln_gain, Wq_packed, w_scales, y, workspace)
+    T, K = x.shape
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=x.device)
+    if workspace is None:
+        workspace = alloc_workspace(T, K, N, bits, x.device)
+    _check(lib().hbl_ln_bitlinear_forward(_ptr(x), _x_dtype(x), T, K, _ptr(ln_gain), ln_eps, int(bool(hadamard)),
+                                          _ptr(Wq_packed), N, _ptr(w_scales), w_scales.numel(), bits, eps, _ptr(y),
+                                          _ptr(workspace), workspace.numel(), _stream()), "ln_bitlinear_forward")
+    return y
+
+
+def ln_fwht_quant(x: torch.Tensor, ln_gain: torch.Tensor, ln_eps: float, bits: int, hadamard: bool = True,
+                  eps: float = EPS, code_offset: int = 0):
+    """RMS normalisation + Eq. 3-6 -> (codes, s_dequant, code_sum) as :func:`fwht_quant`."""
+    _dev_check(x, ln_gain)
+    T, K = x.shape
+    codes = torch.empty((T, K), dtype=torch.int8, device=x.device)
+    sd = torch.empty(T, dtype=torch.float32, device=x.device)
+    cs = torch.empty(T, dtype=torch.int32, device=x.device)
+    _check(lib().hbl_ln_fwht_quant(_ptr(x), _x_dtype(x), T, K, _ptr(ln_gain), ln_eps, bits, eps, int(hadamard),
+                                   code_offset, _ptr(codes), _ptr(sd), _ptr(cs), _stream()), "ln_fwht_quant")
+    return codes, sd, cs

@@ -83,6 +83,14 @@ def test_argument_errors_before_any_launch(L):
     assert L.hbl_fwht_quant(P, hbl.BF16, 4, 256, 3, 1e-5, 1, 0, P, P, P, None) == hbl.E_BITS
     assert L.hbl_fwht_quant(P, hbl.BF16, 4, 256, 8, 1e-5, 1, 8, P, P, P, None) == hbl.E_BITS   # offset 8 is INT4 only
     assert L.hbl_fwht_quant(NUL, hbl.BF16, 4, 256, 4, 1e-5, 1, 0, P, P, P, None) == hbl.E_NULL
+    ln = lambda g=P, had=1, K=256, bits=4: L.hbl_ln_bitlinear_forward(P, hbl.BF16, 4, K, g, 1e-6, had, P, 64, P, 1, bits,
+                                                                    1e-5, P, P, ok_ws, None)
+    assert ln(g=NUL) == hbl.E_NULL
+    assert ln(g=ctypes.c_void_p(0x10004)) == hbl.E_ALIGN
+    assert ln(K=384) == hbl.E_SHAPE
+    assert ln(K=384, had=0, bits=7) == hbl.E_BITS
+    assert L.hbl_ln_fwht_quant(P, hbl.BF16, 4, 256, NUL, 1e-6, 4, 1e-5, 1, 0, P, P, P, None) == hbl.E_NULL
+    assert L.hbl_ln_fwht_quant(P, hbl.BF16, 4, 256, P, 1e-6, 8, 1e-5, 1, 8, P, P, P, None) == hbl.E_BITS
     assert L.hbl_fwht(P, hbl.BF16, 4, 384, P, hbl.F32, None) == hbl.E_SHAPE     # power of two only
     assert L.hbl_fwht(P, hbl.BF16, 4, 256, P, 5, None) == hbl.E_DTYPE
     assert L.hbl_fwht(P, hbl.BF16, 4, 256, NUL, hbl.F32, None) == hbl.E_NULL

@@ -612,3 +612,56 @@ def test_fwht_only_errors_and_empty(hbl):
         hbl.fwht(x)
     assert e.value.status == hbl.E_SHAPE
     assert hbl.fwht(torch.zeros((0, 256), dtype=torch.float32, device="cuda")).shape == (0, 256)
+
+
+def ln_gain_for(K, seed):
+    """RMS-norm gains around 1 with a few large channels (the gains are where trained models park outliers)."""
+    rng = np.random.default_rng(seed)
+    g = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float32)
+    g[rng.integers(0, K, 3)] *= 8.0
+    return g
+
+
+@pytest.mark.parametrize("K,hadamard", [(128, True), (512, True), (2048, True), (4096, True), (8192, True),
+                                        (16384, True), (4096, False), (1536, False), (640, False)])
+@pytest.mark.parametrize("bits", [4, 8])
+def test_ln_fwht_quant_parity(hbl, K, hadamard, bits):
+    """LN of Eq. 7 (RMS normalisation) fused ahead of the transform: codes and scales against the
+    oracle's rmsnorm -> fwht_quant chain, every quantiser kernel family, both input types."""
+    note(f"ln fwht_quant K={K} hadamard={hadamard} bits={bits}")
+    g = ln_gain_for(K, K + bits)
+    for dtype in (synth.BF16, synth.F32):
+        site = synth.Site("a", 21, K, 32, hadamard=hadamard, x_dtype=dtype, outlier_frac=0.01, outlier_scale=30.0,
+                          seed=K + 7 * bits)
+        x = synth.make_x(site)
+        xn = O.rmsnorm(x, g, 1e-6)
+        c_ref, s_ref = O.fwht_quant(xn, bits, hadamard=hadamard, eps=EPS)
+        codes, sd, cs = hbl.ln_fwht_quant(dev_x(x), torch.from_numpy(g).cuda(), 1e-6, bits, hadamard, EPS)
+        check_codes(codes.cpu().numpy(), c_ref)
+        assert np.array_equal(codes.cpu().numpy(), c_ref)
+        assert np.array_equal(sd.cpu().numpy(), s_ref)
+        assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
+
+
+@pytest.mark.parametrize("T,K,N,hadamard,bits", [(150, 4096, 288, True, 4), (150, 2048, 96, False, 4),
+                                                 (40, 1024, 128, True, 8), (5, 4096, 544, False, 4),
+                                                 (9, 16384, 64, True, 4)])
+def test_ln_bitlinear_forward_and_grouped(hbl, T, K, N, hadamard, bits):
+    """Whole call with the fused normalisation, on the prefill (fp6 x fp4 / int8) and small-batch
+    paths, alone and as a member of a grouped call."""
+    note(f"ln forward T={T} K={K} N={N} hadamard={hadamard} bits={bits}")
+    site = synth.Site("a", T, K, N, hadamard=hadamard, outlier_frac=0.01, outlier_scale=30.0, seed=T + K)
+    x = synth.make_x(site)
+    g = ln_gain_for(K, T + K)
+    wc_ref, al_ref, wc_d, al_d, packed = setup_weights(hbl, site)
+    y_ref = O.bitlinear_forward(O.rmsnorm(x, g, 1e-6), wc_ref, al_ref, bits, hadamard, EPS)
+    gd = torch.from_numpy(g).cuda()
+    y = hbl.ln_bitlinear_forward(dev_x(x), gd, 1e-6, hadamard, packed, N, al_d, bits, EPS)
+    assert np.array_equal(host_bf16_bits(y), y_ref)
+    other = synth.Site("b", min(T, 64), 512, 64, hadamard=True, outlier_frac=0.01, outlier_scale=30.0, seed=77)
+    xo = synth.make_x(other)
+    wo_ref, ao_ref, _, ao_d, po = setup_weights(hbl, other)
+    ys = hbl.bitlinear_forward_grouped([(dev_x(x), packed, N, al_d, bits, hadamard, None, gd, 1e-6),
+                                        (dev_x(xo), po, other.N, ao_d, bits, True, None)], EPS)
+    assert np.array_equal(host_bf16_bits(ys[0]), y_ref)
+    assert np.array_equal(host_bf16_bits(ys[1]), O.bitlinear_forward(xo, wo_ref, ao_ref, bits, True, EPS))

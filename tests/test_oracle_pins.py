@@ -379,3 +379,43 @@ def test_backward_undoes_forward_and_rounds_bf16_to_nearest_even():
     tie[0, 0] = 2.0 * (1.0 + 2.0 ** -8)               # H_4 row sum / 2 keeps the value on entry 0..3
     out = synth.bf16_bits_to_f32(O.hadamard_backward(tie, out_bf16=True))
     assert np.array_equal(out, np.full((1, 4), 1.0, np.float32))
+
+
+# --- LN of Eq. 7 as RMS normalisation ---------------------------------------------------------------
+
+@pytest.mark.parametrize("case", ["rmsnorm_power_of_two", "rmsnorm_eps_placement"])
+def test_rmsnorm_hand_examples(golden, case):
+    c = golden[case]
+    gain = np.array(c["gain"], np.float32)
+    for i in range(2):
+        if f"x{i}" not in c:
+            continue
+        x = np.array([c[f"x{i}"]], np.float32)
+        got = O.rmsnorm(x, gain, c["ln_eps"][0])
+        assert np.array_equal(got, np.array([c[f"y{i}"]], np.float32))
+        got_b = O.rmsnorm(synth.f32_to_bf16_bits(x), gain, c["ln_eps"][0])      # bf16 input, same values
+        assert np.array_equal(got_b, got)
+
+
+def test_rmsnorm_invariants_and_fp64_reference():
+    rng = np.random.default_rng(21)
+    K = 1536                                           # not a power of two: the plain projections allow it
+    x = (rng.standard_normal((9, K)) * rng.uniform(0.1, 30, (9, 1))).astype(np.float32)
+    ones = np.ones(K, np.float32)
+    y = O.rmsnorm(x, ones, 0.0).astype(np.float64)
+    assert np.allclose((y ** 2).mean(1), 1.0, rtol=0, atol=2e-6)          # unit mean square
+    # scaling a row by a power of two changes nothing when ln_eps = 0 (every step scales exactly)
+    assert np.array_equal(O.rmsnorm(x * np.float32(8.0), ones, 0.0), O.rmsnorm(x, ones, 0.0))
+    # gain multiplies element-wise; an fp64 evaluation of the definition agrees to fp32 rounding
+    g = rng.standard_normal(K).astype(np.float32)
+    eps = 1e-5
+    want = x.astype(np.float64) / np.sqrt((x.astype(np.float64) ** 2).mean(1, keepdims=True) + eps) * g
+    got = O.rmsnorm(x, g, eps)
+    assert np.abs(got - want).max() <= 3e-7 * np.abs(want).max()
+    assert np.abs(got - want).max() > 0                                    # fp32 result, not fp64 passed through
+    # zero row: finite (ln_eps keeps the root away from zero), and zero out
+    z = O.rmsnorm(np.zeros((1, 8), np.float32), np.ones(8, np.float32), 1e-6)
+    assert np.array_equal(z, np.zeros((1, 8), np.float32))
+    # constant row: |c| / sqrt(c^2) = 1, sign kept
+    c = O.rmsnorm(np.full((1, 16), -3.0, np.float32), np.ones(16, np.float32), 0.0)
+    assert np.allclose(c, -1.0, rtol=0, atol=1e-7)
