@@ -228,6 +228,16 @@ def bench_decode(args, hbl, synth, torch, np):
             "batch": res}
 
 
+def measured_traffic(site_name, int8_path):
+    """HBM bytes one GEMM launch moves, from the rocprofv3 --pmc passes recorded in
+    profiles/hbm_traffic_counters.txt (FETCH_SIZE scaled by the copy-kernel factor 2.000, WRITE_SIZE by
+    1.000).  Only the workload those passes covered has a figure; counters cannot be read from inside
+    this process."""
+    if site_name == "wdown_7b" and not int8_path:
+        return int(196824 * 2.000 * 1024 + 65536 * 1.000 * 1024)
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -259,7 +269,10 @@ def main():
         "roofline": {"kernel": "ternary_gemm_kernel (int8 MFMA)" if int8_path
                                else "ternary_gemm_f6f4_kernel (fp6 x fp4 MFMA, GEMM + dequant epilogue)",
                      "bound": "mfma", "achieved": pre["tops_gemm"], "peak": gemm_peak, "unit": "TOP/s",
-                     "frac": pre["tops_gemm"] / gemm_peak, "traffic": None, "avg_kernel_ms": pre["ms_gemm"],
+                     "frac": pre["tops_gemm"] / gemm_peak, "traffic": measured_traffic(site.name, int8_path),
+                     "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, profiles/hbm_traffic_counters.txt)",
+                     "algorithmic_bytes": site.T * site.K + site.N * site.K // 4 + 2 * site.T * site.N,
+                     "avg_kernel_ms": pre["ms_gemm"],
                      "frac_of_int8_mfma_peak": pre["tops_gemm"] / INT8_MFMA_PEAK_TOPS},
         "fwht_quant": {"avg_kernel_ms": pre["ms_fwht_quant"], "bound": "hbm", "achieved": pre["fwht_quant_gbs"],
                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pre["fwht_quant_gbs"] / HBM_PEAK_GBS},
