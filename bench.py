@@ -120,7 +120,7 @@ def cpu_baseline(site, x_host, W_host, synth, np, budget_s=15.0):
     """The oracle as it stands, on a bounded sample of token rows of the same workload."""
     from oracle import hbl_oracle as O
     wc, alpha = O.ternarize_weights_absmean(W_host, 1e-5)
-    rows = 8
+    rows = 4 * O.num_threads()   # probe: a few rows per thread, so that the estimate sees every core busy
     t0 = time.perf_counter()
     O.bitlinear_forward(np.ascontiguousarray(x_host[:rows]), wc, alpha, 4, site.hadamard, 1e-5)
     dt = time.perf_counter() - t0
@@ -220,8 +220,46 @@ def bench_decode(args, hbl, synth, torch, np):
             gbs = (w_bytes + io_bytes) / (us_layer * 1e-6) / 1e9
             entry[mode] = {"us_per_layer": us_layer, "us_per_layer_eager": us_layer_eager, "GBps": gbs,
                            "frac_hbm_peak": gbs / HBM_PEAK_GBS}
+        # each projection by itself (one forward call per layer's weights)
+        per_site = {}
+        for i, s in enumerate(sites):
+            fn = hbl.hbitlinear_forward if s.hadamard else hbl.plain_bitlinear_forward
+
+            def one_site():
+                for l in range(layers):
+                    fn(xs[i], packed[l][i], s.N, alphas[i], bits, eps, y=ys[i], workspace=wss[i])
+
+            one_site()
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    one_site()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (5 * layers)
+            nbytes = s.N * s.K // 4 + 4 * s.N + 2 * B * s.K + 2 * B * s.N
+            per_site[s.name] = {"us": us, "GBps": nbytes / (us * 1e-6) / 1e9}
+        entry["per_projection"] = per_site
         res[str(B)] = entry
-    return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes,
+    best = max(res, key=lambda b: res[b]["grouped"]["GBps"])
+    roofline = {"kernel": "quant_grouped_kernel + decode_gemm_kernel (one grouped call per layer, batch %s)" % best,
+                "bound": "hbm", "achieved": res[best]["grouped"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": res[best]["grouped"]["GBps"] / HBM_PEAK_GBS,
+                # FETCH_SIZE + WRITE_SIZE of the layer's GEMM launch at batch <= 8 (profiles/hbm_traffic_counters.txt)
+                "traffic": int(33431 * 2.000 * 1024 + 378 * 1024),
+                "note": "call level: both launches of the grouped call; the GEMM launch alone streams the layer's "
+                        "67.1 MB in 15 us (profiles/decode_layer_kernels_config5.txt)"}
+    return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes, "roofline": roofline,
             "launch": "one HIP graph of all layers; sequential = four forward calls per layer in model order "
                       "(2-3 kernel nodes each), grouped = one hbl_bitlinear_forward_grouped call per layer "
                       "(one quantiser launch, one weight-streaming GEMM launch, one reduction launch for batch > 16)",
