@@ -665,3 +665,43 @@ def test_ln_bitlinear_forward_and_grouped(hbl, T, K, N, hadamard, bits):
                                         (dev_x(xo), po, other.N, ao_d, bits, True, None)], EPS)
     assert np.array_equal(host_bf16_bits(ys[0]), y_ref)
     assert np.array_equal(host_bf16_bits(ys[1]), O.bitlinear_forward(xo, wo_ref, ao_ref, bits, True, EPS))
+
+
+def test_grouped_call_in_a_hip_graph_replays_exactly(hbl):
+    """The grouped call captured into a HIP graph (kernel nodes only: its argument blocks travel as
+    kernel arguments) and replayed with fresh inputs between replays, eager work and
+    synchronisations in between: every replay must equal the eager result on the same inputs."""
+    note("grouped call under graph replay")
+    common = dict(outlier_frac=0.01, outlier_scale=30.0)
+    sites = [synth.Site("r_h", 8, 4096, 256, hadamard=True, seed=51, **common),
+             synth.Site("r_p", 8, 1536, 160, hadamard=False, seed=52, groups=1, **common),
+             synth.Site("r_big", 8, 16384, 64, hadamard=True, seed=53, **common)]
+    packs = [setup_weights(hbl, s) for s in sites]
+    xs = [dev_x(synth.make_x(s)) for s in sites]
+    ys = [torch.empty((s.T, s.N), dtype=torch.bfloat16, device="cuda") for s in sites]
+    items = [(xs[i], packs[i][4], s.N, packs[i][3], 4, s.hadamard, ys[i]) for i, s in enumerate(sites)]
+    probs = hbl.make_problems(items)
+    ws = torch.empty(hbl.grouped_workspace_bytes(probs, len(items)), dtype=torch.uint8, device="cuda")
+    hbl.bitlinear_forward_grouped(items, EPS, workspace=ws, problems=probs)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            hbl.bitlinear_forward_grouped(items, EPS, workspace=ws, problems=probs)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for i, s in enumerate(sites):      # new inputs in place (same buffers the graph captured)
+            xs[i].copy_(dev_x(synth.make_x(synth.Site(s.name, s.T, s.K, s.N, hadamard=s.hadamard, seed=60 + rep, **common))))
+        torch.cuda.synchronize()
+        eager = [fn(xs[i], packs[i][4], s.N, packs[i][3], 4, EPS)
+                 for i, s in enumerate(sites)
+                 for fn in [hbl.hbitlinear_forward if s.hadamard else hbl.plain_bitlinear_forward]]
+        torch.cuda.synchronize()
+        for y in ys:
+            y.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for y, e, s in zip(ys, eager, sites):
+            assert torch.equal(y.view(torch.int16), e.view(torch.int16)), f"replay {rep}: {s.name}"
