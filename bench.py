@@ -108,8 +108,19 @@ def bench_prefill(args, hbl, synth, torch, np):
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t2) * 1e3 / args.steps
 
+    # INT8 activations (the paper's first training stage) on the same site, for reference: int8 matrix cores
+    for _ in range(3):
+        hbl.hbitlinear_forward(x, packed, N, alphas, 8, eps, y=y, workspace=ws)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    for _ in range(args.steps):
+        hbl.hbitlinear_forward(x, packed, N, alphas, 8, eps, y=y, workspace=ws)
+    torch.cuda.synchronize()
+    ms_int8 = (time.perf_counter() - t3) * 1e3 / args.steps
+
     ops = 2.0 * T * K * N
     out = {
+        "ms_per_step_int8_acts": ms_int8, "tops_end_to_end_int8_acts": ops / (ms_int8 * 1e-3) / 1e12,
         "T": T, "K": K, "N": N, "ms_per_step": ms_per_step, "ms_split_calls": ms_split,
         "ms_fwht_quant": t_quant, "ms_gemm": t_gemm,
         "tops_end_to_end": ops / (ms_per_step * 1e-3) / 1e12,
@@ -319,6 +330,8 @@ def main():
                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pre["fwht_quant_gbs"] / HBM_PEAK_GBS},
         # the stage-level calls with three event records per step (where the per-kernel durations come from)
         "ms_split_calls_with_events": pre["ms_split_calls"],
+        "int8_activations": {"ms_per_step": pre["ms_per_step_int8_acts"], "TOPS": pre["tops_end_to_end_int8_acts"],
+                             "frac_int8_mfma_peak": pre["tops_end_to_end_int8_acts"] / INT8_MFMA_PEAK_TOPS},
     }
     if not args.no_decode:
         torch.cuda.empty_cache()

@@ -4,9 +4,9 @@
 //
 // A wave owns one 32-row weight tile at a time and walks its K range tile by tile (1 KiB of packed
 // weights = 32 rows x 128 features).  Weights and activation codes both arrive by direct global->LDS
-// copies, D stages deep per wave (D = 4); per stage a wave expands the 16 packed bytes of each lane into four
-// int8 operands (code + 1, as in the large-T kernel; the epilogue removes the offset in int32) and
-// issues 4 (or 8) 32x32x32 int8 MFMAs.
+// copies, D = 4 stages deep per wave; per stage a wave expands the 16 packed bytes of each lane into
+// four int8 operands (code + 1, as in the large-T kernel; the epilogue removes the offset in int32)
+// and issues 4 (or 8) 32x32x32 int8 MFMAs.
 //
 // Two forms:
 //  - streaming (T <= 16): a wave's code stage is private (8 or 16 rows x 128 B), so the waves never
@@ -54,7 +54,6 @@ __global__ __launch_bounds__(256, 2) void decode_gemm_kernel(const DecodeArgs ar
     constexpr int XW = SHARE ? XB : 4 * XB;           // code bytes per stage in the workgroup
     constexpr int STAGE = XW + 4 * 1024;              // + one packed weight tile per wave
     constexpr int XL = SHARE ? TT : RQ;               // code copies per wave per stage
-    constexpr int PENDING = (D - 2) * (XL + 1);       // copies of later stages that may stay in flight
     constexpr int NACC = TT == 1 ? 2 : TT;
     static_assert(D >= 3 && (ROWS & (ROWS - 1)) == 0, "pipeline depth / row count");
 
@@ -100,13 +99,12 @@ __global__ __launch_bounds__(256, 2) void decode_gemm_kernel(const DecodeArgs ar
 
     // Copies of stage kb into buffer `slot`.
     auto issue = [&](int kb, int slot) {
-        const int kbc = kb;
 #pragma unroll
         for (int m = 0; m < XL; ++m) {
             const int q = SHARE ? wave + 4 * m : m;
-            lds_dma16(lds0 + slot * STAGE + xarea + q * 1024, xbase + (size_t)kbc * kBK, xlane[m]);
+            lds_dma16(lds0 + slot * STAGE + xarea + q * 1024, xbase + (size_t)kb * kBK, xlane[m]);
         }
-        lds_dma16(lds0 + slot * STAGE + XW + wave * 1024, wbase + (size_t)kbc * 1024, wlane);
+        lds_dma16(lds0 + slot * STAGE + XW + wave * 1024, wbase + (size_t)kb * 1024, wlane);
     };
 
     // operand reads: token row (lane & 31) of tile j (rows beyond the stage wrap onto loaded rows; their

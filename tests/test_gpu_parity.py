@@ -705,3 +705,20 @@ def test_grouped_call_in_a_hip_graph_replays_exactly(hbl):
         torch.cuda.synchronize()
         for y, e, s in zip(ys, eager, sites):
             assert torch.equal(y.view(torch.int16), e.view(torch.int16)), f"replay {rep}: {s.name}"
+
+
+def test_weight_and_activation_rotation_variant(hbl):
+    """The ablation's variant that rotates the weights too (offline): Q_w(W H) . Q(H x).  Built from
+    the library's own pieces - hbl_fwht on the weight rows, then ternarise / pack, then the ordinary
+    H-BitLinear forward - and equal, bit for bit, to the same chain in the oracle."""
+    note("weight + activation rotation")
+    site = synth.Site("rot", 70, 1024, 96, hadamard=True, outlier_frac=0.01, outlier_scale=30.0, seed=71)
+    x, W = synth.make_x(site), synth.make_w(site)
+    Wr_ref = O.fwht_rows(W)
+    wc_ref, a_ref = O.ternarize_weights_absmean(Wr_ref, EPS)
+    y_ref = O.hbitlinear_forward(x, wc_ref, np.array([a_ref], np.float32), 4, EPS)
+    Wr = hbl.fwht(torch.from_numpy(W).cuda())
+    assert np.array_equal(Wr.cpu().numpy().view(np.uint32), Wr_ref.view(np.uint32))
+    wc, alpha = hbl.ternarize_weights_absmean(Wr, EPS)
+    y = hbl.hbitlinear_forward(dev_x(x), hbl.pack_ternary_2bit(wc), site.N, alpha, 4, EPS)
+    assert np.array_equal(host_bf16_bits(y), y_ref)

@@ -419,3 +419,16 @@ def test_rmsnorm_invariants_and_fp64_reference():
     # constant row: |c| / sqrt(c^2) = 1, sign kept
     c = O.rmsnorm(np.full((1, 16), -3.0, np.float32), np.ones(16, np.float32), 0.0)
     assert np.allclose(c, -1.0, rtol=0, atol=1e-7)
+
+
+def test_rotating_weights_and_activations_cancels():
+    """The ablation's weight-and-activation variant multiplies W H by H x: H H = I, so without the
+    quantisers the product is W x again.  Pins that the transform is its own inverse *as a matrix*
+    applied on the feature axis of both operands (a transform along the wrong axis fails)."""
+    rng = np.random.default_rng(11)
+    K = 256
+    W = rng.standard_normal((24, K)).astype(np.float32)
+    x = rng.standard_normal((5, K)).astype(np.float32)
+    got = O.fwht_rows(x).astype(np.float64) @ O.fwht_rows(W).astype(np.float64).T
+    want = x.astype(np.float64) @ W.astype(np.float64).T
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
