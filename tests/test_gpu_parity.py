@@ -722,3 +722,31 @@ def test_weight_and_activation_rotation_variant(hbl):
     wc, alpha = hbl.ternarize_weights_absmean(Wr, EPS)
     y = hbl.hbitlinear_forward(dev_x(x), hbl.pack_ternary_2bit(wc), site.N, alpha, 4, EPS)
     assert np.array_equal(host_bf16_bits(y), y_ref)
+
+
+def _random_site(rng, i, t_max):
+    hadamard = bool(rng.integers(0, 2))
+    K = int(rng.choice([128, 256, 512, 1024, 2048, 4096, 8192])) if hadamard else 128 * int(rng.integers(1, 40))
+    groups = int(rng.choice([1, 1, 2, 3]))
+    N = 32 * groups * int(rng.integers(1, 7))
+    T = int(rng.integers(1, t_max + 1))
+    dtype = synth.BF16 if rng.integers(0, 4) else synth.F32
+    return synth.Site(f"rnd{i}", T, K, N, hadamard=hadamard, groups=groups, x_dtype=dtype, outlier_frac=0.01,
+                      outlier_scale=float(rng.choice([1.0, 30.0])), seed=1000 + i)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_single_and_grouped(hbl, seed):
+    """Seeded random shapes (token counts on both sides of every path switch, ragged feature counts,
+    scale groups, both input types and bit widths): every single call and one grouped call per
+    draw, bit for bit against the oracle."""
+    rng = np.random.default_rng(4242 + seed)
+    bits = int(rng.choice([4, 8]))
+    sites = [_random_site(rng, 10 * seed + i, t_max=[4, 16, 40, 64, 130, 300][seed]) for i in range(5)]
+    note(f"random shapes seed={seed} bits={bits}: " + ", ".join(f"{s.T}x{s.K}->{s.N}{'H' if s.hadamard else 'P'}" for s in sites))
+    # a grouped call needs one input type: group the bf16 sites, run the others alone
+    main = [s for s in sites if s.x_dtype == synth.BF16]
+    run_group(hbl, main, [bits] * len(main))
+    for s in sites:
+        if s.x_dtype != synth.BF16:
+            run_group(hbl, [s], [bits])
