@@ -268,44 +268,88 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
         kstep_last(kb, slot);
         slot = slot + 1 == NSTAGE ? 0 : slot + 1;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the clamped tail loads before the LDS is released
+    // drain the clamped tail loads, and wait until every wave is done with the stage buffers: the bf16
+    // epilogue reuses them
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     // epilogue: lane holds token t = ..+(lane&31); register quad g holds features 8g + 4*(lane>>5) + 0..3
     const bool write_partial = SPLIT && a.split_k > 1;
+    if (RAW || write_partial) {   // int32 tiles (debug export / split-K partials): stored from where they are
 #pragma unroll
-    for (int j = 0; j < TT; ++j) {
-        const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
-        if (t >= a.T) continue;
-        float sd = 0.0f;
-        int sx = 0;
-        if constexpr (!RAW) {
-            sd = a.s_dequant[t];
-            sx = a.code_sum[t];
-        }
+        for (int j = 0; j < TT; ++j) {
+            const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
+            if (t >= a.T) continue;
 #pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            // one accumulator tile at a time: without this fence the compiler reads all TN*TT*16
-            // accumulators out of the AGPRs up front and spills
-            __builtin_amdgcn_sched_barrier(0);
-            const int nb = n0 + (wn * TN + i) * 32;
-            if (nb >= a.N) continue;
-            float alpha = 0.0f;
-            if constexpr (!RAW) alpha = a.w_scales[nb / a.rows_per_group];
+            for (int i = 0; i < TN; ++i) {
+                // one accumulator tile at a time: without this fence the compiler reads all TN*TT*16
+                // accumulators out of the AGPRs up front and spills
+                __builtin_amdgcn_sched_barrier(0);
+                const int nb = n0 + (wn * TN + i) * 32;
+                if (nb >= a.N) continue;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = nb + 8 * g + 4 * (lane >> 5);
-                v4i o;
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + 8 * g + 4 * (lane >> 5);
+                    v4i o;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = acc[i][j][4 * g + r];
-                if constexpr (RAW) {
-                    *reinterpret_cast<v4i*>(a.acc_out + (size_t)t * a.N + n) = o;
-                } else if (write_partial) {
-                    *reinterpret_cast<v4i*>(a.partial + ((size_t)ks * a.T + t) * a.N + n) = o;
-                } else {
-                    *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) =
-                        dequant_quad(o, sx, sd, alpha, a.code_offset, a.w_row_sum + n, a.K);
+                    for (int r = 0; r < 4; ++r) o[r] = acc[i][j][4 * g + r];
+                    if constexpr (RAW) *reinterpret_cast<v4i*>(a.acc_out + (size_t)t * a.N + n) = o;
+                    else *reinterpret_cast<v4i*>(a.partial + ((size_t)ks * a.T + t) * a.N + n) = o;
                 }
             }
+        }
+        return;
+    }
+    if constexpr (!RAW) {
+        // bf16 output.  Stored from the accumulator layout, every instruction would touch 32 token rows
+        // with 16 bytes each, and the output burst at the end of each round of workgroups is bound by the
+        // number of such partial-line writes.  So the dequantised tiles go through the wave's share of the
+        // LDS and leave as whole rows: TN*64 contiguous bytes per token, 16 bytes per lane.
+        constexpr int ROWB = TN * 64 + 16;       // padded LDS row: 16-byte chunks stay aligned, rows shift by 4 banks
+        constexpr int JG = TT < 2 ? TT : 2;      // token tiles per pass through the LDS
+        constexpr int CPR = TN * 4;              // 16-byte chunks per row
+        constexpr int RPI = 64 / CPR;            // rows per read instruction
+        static_assert(NW * JG * 32 * ROWB <= NSTAGE * STAGE && 64 % CPR == 0 && TT % JG == 0, "epilogue staging");
+        char* obuf = lds + wave * (JG * 32 * ROWB);
+#pragma unroll
+        for (int jg = 0; jg < TT; jg += JG) {
+#pragma unroll
+            for (int jj = 0; jj < JG; ++jj) {
+                const int j = jg + jj;
+                const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
+                const float sd = t < a.T ? a.s_dequant[t] : 0.0f;
+                const int sx = t < a.T ? a.code_sum[t] : 0;
+#pragma unroll
+                for (int i = 0; i < TN; ++i) {
+                    __builtin_amdgcn_sched_barrier(0);   // one accumulator tile at a time (register pressure)
+                    const int nb = n0 + (wn * TN + i) * 32;
+                    const bool in_n = nb < a.N;
+                    const float alpha = in_n ? a.w_scales[nb / a.rows_per_group] : 0.0f;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = nb + 8 * g + 4 * (lane >> 5);
+                        v4i o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = acc[i][j][4 * g + r];
+                        v4i ws = {0, 0, 0, 0};
+                        if (a.code_offset != 0 && in_n) ws = *reinterpret_cast<const v4i*>(a.w_row_sum + n);
+                        *reinterpret_cast<uint2*>(obuf + (jj * 32 + (lane & 31)) * ROWB +
+                                                  (i * 32 + 8 * g + 4 * (lane >> 5)) * 2) =
+                            dequant_quad_sums(o, sx, sd, alpha, a.code_offset, ws, a.K);
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // a wave's LDS accesses execute in order: no barrier between its own writes and reads
+#pragma unroll
+            for (int r = 0; r < JG * 32; r += RPI) {
+                const int row = r + lane / CPR;
+                const int c = lane % CPR;
+                const uint4 val = *reinterpret_cast<const uint4*>(obuf + row * ROWB + c * 16);
+                const int t = t0 + (wt * TT + jg + row / 32) * 32 + (row & 31);
+                const int n = n0 + wn * TN * 32 + c * 8;
+                if (t < a.T && n < a.N) *reinterpret_cast<uint4*>(a.y + (size_t)t * a.N + n) = val;
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -373,17 +417,12 @@ int choose(const GemmArgs& a, hipStream_t stream) {
     else if (a.T <= 64) cfg = 1;
     else if (big_tiles >= 200) cfg = 3;
     else cfg = 2;
-    if (tile_override() >= 0 && cfg < 6) cfg = tile_override();
+    if (tile_override() >= 0 && tile_override() <= 3 && cfg < 6) cfg = tile_override();
     switch (cfg) {
         case 0: return launch_cfg<4, 1, 2, 1, 4, RAW>(a, stream);   // 256 features x 32 tokens, 4 waves
         case 1: return launch_cfg<4, 1, 2, 2, 4, RAW>(a, stream);   // 256 x 64, 4 waves
         case 2: return launch_cfg<2, 2, 2, 2, 4, RAW>(a, stream);   // 128 x 128, 4 waves
         case 3: return launch_cfg<2, 2, 4, 4, 3, RAW>(a, stream);   // 256 x 256, 4 waves of 128 x 128
-        case 4: return launch_cfg<2, 4, 4, 2, 3, RAW>(a, stream);   // 256 x 256, 8 waves of 128 x 64
-        case 5: return launch_cfg<4, 2, 2, 4, 3, RAW>(a, stream);   // 256 x 256, 8 waves of 64 x 128
-        case 8: return launch_cfg<2, 2, 2, 4, 2, RAW, false, 2>(a, stream);   // 128 x 256, two workgroups per CU
-        case 9: return launch_cfg<2, 2, 4, 2, 3, RAW, false, 2>(a, stream);   // 256 x 128, two workgroups per CU
-        case 10: return launch_cfg<2, 2, 4, 2, 2, RAW, false, 2>(a, stream);  // 256 x 128, 2 stages
         case 6: if constexpr (!RAW) return launch_cfg<4, 1, 1, 1, 4, false, true>(a, stream);   // 128 x 32, split-K
         case 7: if constexpr (!RAW) return launch_cfg<4, 1, 1, 2, 4, false, true>(a, stream);   // 128 x 64, split-K
         default: return HBL_E_SHAPE;

@@ -235,35 +235,62 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
         kstep_last(kb, slot);
         slot = slot + 1 == NSTAGE ? 0 : slot + 1;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the clamped tail copies before the LDS is released
+    // drain the clamped tail copies, and wait until every wave is done with the stage buffers: the
+    // epilogue reuses them
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    // epilogue: lane holds token t = ..+(lane&31); register quad g holds features 8g + 4*(lane>>5) + 0..3.
+    // Epilogue.  A lane holds token (lane & 31) of a 32 x 32 tile, register quad g holding features
+    // 8g + 4*(lane >> 5) + 0..3: stored from there, every instruction would touch 32 token rows with
+    // 16 bytes each, and the output burst at the end of each round of workgroups (all of them finish
+    // together) is bound by the number of such partial-line writes, not by bytes (measured: a third of
+    // the run time at K = 4096).  So the dequantised bf16 tiles go through the wave's share of the LDS
+    // and leave as whole rows: TN*64 contiguous bytes per token, 16 bytes per lane.
     // The accumulators are integers held in fp32: y = bf16((acc * s_d) * alpha) as on the int8 path.
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     typedef float f32x2 __attribute__((ext_vector_type(2)));
+    constexpr int ROWB = TN * 64 + 16;       // padded LDS row: 16-byte chunks stay aligned, rows shift by 4 banks
+    constexpr int JG = TT < 2 ? TT : 2;      // token tiles per pass through the LDS
+    constexpr int CPR = TN * 4;              // 16-byte chunks per row
+    constexpr int RPI = 64 / CPR;            // rows per read instruction
+    static_assert(NW * JG * 32 * ROWB <= NSTAGE * STAGE && 64 % CPR == 0 && TT % JG == 0, "epilogue staging");
+    char* obuf = lds + wave * (JG * 32 * ROWB);
 #pragma unroll
-    for (int j = 0; j < TT; ++j) {
-        const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
-        if (t >= a.T) continue;
-        const float sd = a.s_dequant[t];
+    for (int jg = 0; jg < TT; jg += JG) {
 #pragma unroll
-        for (int i = 0; i < TN; ++i) {
-            __builtin_amdgcn_sched_barrier(0);   // one accumulator tile at a time (register pressure)
-            const int nb = n0 + (wn * TN + i) * 32;
-            if (nb >= a.N) continue;
-            const float alpha = a.w_scales[nb / a.rows_per_group];
+        for (int jj = 0; jj < JG; ++jj) {
+            const int j = jg + jj;
+            const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
+            const float sd = t < a.T ? a.s_dequant[t] : 0.0f;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = nb + 8 * g + 4 * (lane >> 5);
-                float v[4];
+            for (int i = 0; i < TN; ++i) {
+                __builtin_amdgcn_sched_barrier(0);   // one accumulator tile at a time (register pressure)
+                const int nb = n0 + (wn * TN + i) * 32;
+                const float alpha = nb < a.N ? a.w_scales[nb / a.rows_per_group] : 0.0f;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = (acc[i][j][4 * g + r] * sd) * alpha;
-                const bf16x2 lo = __builtin_convertvector((f32x2){v[0], v[1]}, bf16x2);
-                const bf16x2 hi = __builtin_convertvector((f32x2){v[2], v[3]}, bf16x2);
-                *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) =
-                    make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+                for (int g = 0; g < 4; ++g) {
+                    float v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = (acc[i][j][4 * g + r] * sd) * alpha;
+                    const bf16x2 lo = __builtin_convertvector((f32x2){v[0], v[1]}, bf16x2);
+                    const bf16x2 hi = __builtin_convertvector((f32x2){v[2], v[3]}, bf16x2);
+                    *reinterpret_cast<uint2*>(obuf + (jj * 32 + (lane & 31)) * ROWB +
+                                              (i * 32 + 8 * g + 4 * (lane >> 5)) * 2) =
+                        make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+                }
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        // a wave's LDS accesses execute in order: no barrier between its own writes and reads
+#pragma unroll
+        for (int r = 0; r < JG * 32; r += RPI) {
+            const int row = r + lane / CPR;
+            const int c = lane % CPR;
+            const uint4 val = *reinterpret_cast<const uint4*>(obuf + row * ROWB + c * 16);
+            const int t = t0 + (wt * TT + jg + row / 32) * 32 + (row & 31);
+            const int n = n0 + wn * TN * 32 + c * 8;
+            if (t < a.T && n < a.N) *reinterpret_cast<uint4*>(a.y + (size_t)t * a.N + n) = val;
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
