@@ -441,11 +441,12 @@ int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_
 
 // Plain BitLinear front end for K that is not a power of two (K % 128 == 0, K <= 16384): the same
 // quantiser with the row held as up to 8 chunks of 8 elements per thread of a 256-thread workgroup.
-template <int BITS, bool BF16>
+// MAXC = chunk slots per thread (K <= 2048 * MAXC): the launcher picks the smallest that covers the row, so
+// that short rows do not walk empty slots; every MAXC performs the same arithmetic in the same order.
+template <int BITS, bool BF16, int MAXC = 8>
 __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const void* __restrict__ x, int K,
                                                    int8_t* __restrict__ codes, float* __restrict__ s_dequant,
                                                    int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
-    constexpr int MAXC = 8;
     __shared__ double red_d[4];
     __shared__ float red_f[4];
     __shared__ int red_i[4];
@@ -545,24 +546,38 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
     }
 }
 
-template <int BITS, bool BF16>
+template <int BITS, bool BF16, int MAXC>
 __global__ __launch_bounds__(256) void quant_generic_kernel(const void* __restrict__ x, int K,
                                                             int8_t* __restrict__ codes,
                                                             float* __restrict__ s_dequant,
                                                             int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
-    quant_generic_body<BITS, BF16>(blockIdx.x, threadIdx.x, x, K, codes, s_dequant, code_sum, rp, code_offset);
+    quant_generic_body<BITS, BF16, MAXC>(blockIdx.x, threadIdx.x, x, K, codes, s_dequant, code_sum, rp, code_offset);
+}
+
+template <int BITS, bool BF16>
+void launch_generic_slots(const void* x, int64_t T, int64_t K, RowParams rp, int8_t* codes, float* s_dequant,
+                          int32_t* code_sum, int code_offset, hipStream_t stream) {
+    const dim3 grid((unsigned)T), block(256);
+    const int64_t per_thread = (K / 8 + 255) / 256;   // 8-element chunks per thread
+#define HBL_GENERIC(MAXC)                                                                                     \
+    hipLaunchKernelGGL((quant_generic_kernel<BITS, BF16, MAXC>), grid, block, 0, stream, x, (int)K, codes, s_dequant, \
+                       code_sum, rp, code_offset)
+    if (per_thread <= 1) HBL_GENERIC(1);
+    else if (per_thread <= 2) HBL_GENERIC(2);
+    else if (per_thread <= 4) HBL_GENERIC(4);
+    else HBL_GENERIC(8);
+#undef HBL_GENERIC
 }
 
 int launch_generic(const void* x, int x_dtype, int64_t T, int64_t K, int bits, RowParams rp, int8_t* codes,
                    float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
-    const dim3 grid((unsigned)T), block(256);
     const bool bf = x_dtype == HBL_BF16;
     if (bits == 8) {
-        if (bf) hipLaunchKernelGGL((quant_generic_kernel<8, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, rp, code_offset);
-        else    hipLaunchKernelGGL((quant_generic_kernel<8, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, rp, code_offset);
+        if (bf) launch_generic_slots<8, true>(x, T, K, rp, codes, s_dequant, code_sum, code_offset, stream);
+        else    launch_generic_slots<8, false>(x, T, K, rp, codes, s_dequant, code_sum, code_offset, stream);
     } else {
-        if (bf) hipLaunchKernelGGL((quant_generic_kernel<4, true>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, rp, code_offset);
-        else    hipLaunchKernelGGL((quant_generic_kernel<4, false>), grid, block, 0, stream, x, (int)K, codes, s_dequant, code_sum, rp, code_offset);
+        if (bf) launch_generic_slots<4, true>(x, T, K, rp, codes, s_dequant, code_sum, code_offset, stream);
+        else    launch_generic_slots<4, false>(x, T, K, rp, codes, s_dequant, code_sum, code_offset, stream);
     }
     return after_launch();
 }
