@@ -151,6 +151,41 @@ def cpu_baseline(site, x_host, W_host, synth, np, budget_s=15.0):
     }
 
 
+def bench_prefill_layer(args, hbl, synth, torch, np):
+    """All four projections of the 7B layer at the prefill batch (T = 8192): the two H-BitLinear sites of
+    configuration 4 plus the plain QKV and up/gate projections with configuration 5's shapes."""
+    T, bits, eps = 8192, 4, hbl.EPS
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    out, total_ms, total_ops = {}, 0.0, 0.0
+    for s in synth.config_sites(5, batch=T):
+        x = torch.randn((T, s.K), device="cuda", generator=g).to(torch.bfloat16)
+        c = torch.randint(-1, 2, (s.N, s.K), dtype=torch.int8, device="cuda", generator=g)
+        packed = hbl.pack_ternary_2bit(c)
+        del c
+        al = torch.full((s.groups,), 0.016, dtype=torch.float32, device="cuda")
+        y = torch.empty((T, s.N), dtype=torch.bfloat16, device="cuda")
+        ws = hbl.alloc_workspace(T, s.K, s.N, bits)
+        fn = hbl.hbitlinear_forward if s.hadamard else hbl.plain_bitlinear_forward
+        for _ in range(3):
+            fn(x, packed, s.N, al, bits, eps, y=y, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            fn(x, packed, s.N, al, bits, eps, y=y, workspace=ws)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / 10
+        ops = 2.0 * T * s.K * s.N
+        out[s.name.replace("dec_", "")] = {"K": s.K, "N": s.N, "hadamard": s.hadamard, "ms": ms,
+                                           "TOPS": ops / (ms * 1e-3) / 1e12}
+        total_ms += ms
+        total_ops += ops
+        del x, packed, y, ws
+    out["layer"] = {"ms": total_ms, "TOPS": total_ops / (total_ms * 1e-3) / 1e12,
+                    "frac_int8_mfma_peak": total_ops / (total_ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS}
+    return out
+
+
 def bench_decode(args, hbl, synth, torch, np):
     """Configuration 5: one 7B decoder layer's four projections, weights cycled over `layers`
     independent copies (1.6 GB at 24) so that they stream from HBM rather than from cache."""
@@ -334,6 +369,8 @@ def main():
                              "frac_int8_mfma_peak": pre["tops_end_to_end_int8_acts"] / INT8_MFMA_PEAK_TOPS},
     }
     if not args.no_decode:
+        torch.cuda.empty_cache()
+        result["prefill_layer_7b"] = bench_prefill_layer(args, hbl, synth, torch, np)
         torch.cuda.empty_cache()
         result["decode"] = bench_decode(args, hbl, synth, torch, np)
     if not args.no_cpu_baseline:
