@@ -750,3 +750,28 @@ def test_random_shapes_single_and_grouped(hbl, seed):
     for s in sites:
         if s.x_dtype != synth.BF16:
             run_group(hbl, [s], [bits])
+
+
+def test_offsets_beyond_two_to_the_31(hbl):
+    """T * K = 2.3e9 elements: any 32-bit element offset in a kernel would wrap.  Inputs are drawn on the
+    GPU (4.6 GB of bf16); the oracle checks sampled rows around the wrap points and at both ends."""
+    note("offsets beyond 2^31")
+    T, K, N = 140000, 16384, 64
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    x = torch.randn((T, K), device="cuda", generator=g).to(torch.bfloat16)
+    W = (np.random.default_rng(5).standard_normal((N, K)) * 0.02).astype(np.float32)
+    wc_ref, a_ref = O.ternarize_weights_absmean(W, EPS)
+    wc, alpha = hbl.ternarize_weights_absmean(torch.from_numpy(W).cuda(), EPS)
+    packed = hbl.pack_ternary_2bit(wc)
+    rows = np.r_[0:40, 65530:65560, 131060:131090, T - 40:T]
+    rows_d = torch.from_numpy(rows).cuda()
+    xs = x[rows_d].view(torch.int16).cpu().numpy().view(np.uint16)
+    for bits, hadamard in ((4, True), (8, False)):
+        fn = hbl.hbitlinear_forward if hadamard else hbl.plain_bitlinear_forward
+        y = fn(x, packed, N, alpha, bits, EPS)
+        ref = O.bitlinear_forward(xs, wc_ref, np.array([a_ref], np.float32), bits, hadamard, EPS)
+        assert np.array_equal(host_bf16_bits(y[rows_d]), ref), (bits, hadamard)
+        del y
+    del x
+    torch.cuda.empty_cache()
