@@ -128,6 +128,17 @@ int main() {
     CHECK(hipMemset(dst, 0, bytes));
     const float r = time_ms([&] { read_kernel<<<4096, 256>>>(src, bytes / 16, dst); }, 5);
     printf("%-48s %8.1f GB/s\n", "HBM read stream, 2 GiB", bytes / r / 1e6);
+    // the same read stream cut into launches of one decode layer's size (64 MiB each, 24 distinct chunks per
+    // pass so that nothing is served from cache): what launch ramp and drain leave of the stream rate
+    for (int wgs : {512, 1024, 2048, 4096}) {
+        const size_t chunk = (size_t)64 << 20;
+        const float t = time_ms([&] {
+            for (int i = 0; i < 24; ++i)
+                read_kernel<<<wgs, 256>>>(src + i * (chunk / 16), chunk / 16, dst);
+        }, 3) / 24;
+        printf("HBM read, 64 MiB per launch, %4d workgroups      %8.1f GB/s (%.1f us per launch)\n", wgs,
+               chunk / t / 1e6, t * 1e3);
+    }
     const float c = time_ms([&] { copy_kernel<<<4096, 256>>>(src, dst, bytes / 16); }, 5);
     printf("%-48s %8.1f GB/s (read + write)\n", "HBM copy, 2 GiB -> 2 GiB", 2.0 * bytes / c / 1e6);
     return 0;
