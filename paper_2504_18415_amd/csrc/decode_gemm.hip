@@ -261,13 +261,8 @@ int launch_form(const DecodeArgs& a, int wgs, int red_wgs, hipStream_t stream) {
     constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;
     constexpr size_t lds = (size_t)D * ((SHARE ? 1 : 4) * ROWS * kBK + 4 * 1024);
     auto kern = decode_gemm_kernel<SHARE, TT, RQ, D>;
-    static std::atomic<bool> attr_set{false};   // once per process (one device)
-    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return note_hip_error(e);
-        attr_set.store(true, std::memory_order_release);
-    }
+    static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
+    if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
     hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), lds, stream, a);
     int rc = after_launch();
     if (rc != HBL_OK || red_wgs == 0) return rc;

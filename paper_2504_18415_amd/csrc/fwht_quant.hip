@@ -427,13 +427,8 @@ int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_
     constexpr int K = 1 << LOG2K;
     const size_t lds = (HADAMARD && W > 1) ? sizeof(float) * K : 0;
     auto kern = fwht_quant_kernel<LOG2K, W, BITS, BF16, HADAMARD>;
-    static std::atomic<bool> attr_set{false};   // once per process (one device)
-    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return note_hip_error(e);
-        attr_set.store(true, std::memory_order_release);
-    }
+    static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
+    if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
     hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, rp, code_offset);
     return after_launch();
 }
@@ -889,13 +884,8 @@ int launch_bigrow_form(const void* x, int64_t T, int8_t* codes, float* s_dequant
     constexpr int K = 1 << LOG2K;
     constexpr size_t lds = sizeof(float) * K;
     auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16, BF6OUT, NORM>;
-    static std::atomic<bool> attr_set{false};   // once per process (one device)
-    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return note_hip_error(e);
-        attr_set.store(true, std::memory_order_release);
-    }
+    static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
+    if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
     hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(K / 64), lds, stream, x, codes, s_dequant, code_sum, rp,
                        code_offset);
     return after_launch();
@@ -986,13 +976,8 @@ int launch_quant_grouped(const QuantGroupArgs& args, int bits, int x_dtype, hipS
     if (rows == 0) return HBL_OK;
     const bool bf = x_dtype == HBL_BF16;
     auto launch = [&](auto kern) -> int {
-        static std::atomic<bool> attr_set{false};   // per instantiation, once per process (one device)
-        if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
-            if (e != hipSuccess) return note_hip_error(e);
-            attr_set.store(true, std::memory_order_release);
-        }
+        static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
+        if (const int rc = allow_dynamic_lds(kern, 64 * 1024, lds_allowed); rc != HBL_OK) return rc;
         hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(256), lds, stream, args);
         return after_launch();
     };

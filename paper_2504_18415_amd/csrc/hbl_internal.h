@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "hbitlinear.h"
 
 namespace hbl {
@@ -15,6 +17,23 @@ int note_hip_error(hipError_t e);
 inline int after_launch() {
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? HBL_OK : note_hip_error(e);
+}
+
+// Allow `kern` more than 48 KiB of dynamic LDS.  The attribute belongs to the (function, device) pair: set
+// once per device this process launches on (`done` is the caller's per-instantiation mask of devices, bit =
+// device ordinal mod 64).
+template <typename Kernel>
+inline int allow_dynamic_lds(Kernel kern, size_t bytes, std::atomic<uint64_t>& done) {
+    if (bytes <= 48 * 1024) return HBL_OK;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return note_hip_error(e);
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return HBL_OK;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return note_hip_error(e);
+    done.fetch_or(bit, std::memory_order_release);
+    return HBL_OK;
 }
 
 inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }

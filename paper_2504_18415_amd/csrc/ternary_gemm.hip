@@ -381,13 +381,8 @@ int launch_cfg(GemmArgs a, hipStream_t stream) {
     a.tiles_t = (a.T + BT - 1) / BT;
     if (!SPLIT) a.split_k = 1;
     auto kern = ternary_gemm_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, RAW, SPLIT, OCC>;
-    static std::atomic<bool> attr_set{false};   // once per process (one device)
-    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return note_hip_error(e);
-        attr_set.store(true, std::memory_order_release);
-    }
+    static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
+    if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
     hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t * a.split_k)), dim3(64 * WAVES_N * WAVES_T), lds,
                        stream, a);
     int rc = after_launch();

@@ -302,13 +302,8 @@ int launch_cfg(GemmArgs a, hipStream_t stream) {
     a.tiles_n = (a.N + BN - 1) / BN;
     a.tiles_t = (a.T + BT - 1) / BT;
     auto kern = ternary_gemm_f6f4_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE>;
-    static std::atomic<bool> attr_set{false};   // once per process (one device)
-    if (lds > 48 * 1024 && !attr_set.load(std::memory_order_acquire)) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return note_hip_error(e);
-        attr_set.store(true, std::memory_order_release);
-    }
+    static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
+    if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
     hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t)), dim3(64 * WAVES_N * WAVES_T), lds, stream, a);
     return after_launch();
 }
