@@ -185,6 +185,18 @@ size_t hbl_grouped_workspace_bytes(const hbl_problem* problems, int n_problems);
 int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, float eps,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Diagnostic, host only (no launch, no device access): the plan the small-batch GEMM launch of a
+ * grouped call would use for these problems (every T in 1..64, n_problems <= 8; only T, K, N and
+ * hadamard are read).
+ *   ksplit[i]              K slices per 32-row weight tile of problem i (inside a workgroup when every
+ *                          T <= 16, over workgroups plus a reduction launch otherwise)
+ *   gemm_workgroups        grid size of the GEMM launch;  reduce_workgroups  of the reduction (0 = none)
+ *   single_call_streams[i] 1 if a single forward call on problem i uses the weight-streaming kernel
+ */
+int hbl_debug_grouped_plan(const hbl_problem* problems, int n_problems, int* ksplit, int* gemm_workgroups,
+                           int* reduce_workgroups, int* single_call_streams);
+
 /* ---------------------------------------------------------------------------
  * Stage-level entry points (parity checks and profiling; same kernels)
  * ------------------------------------------------------------------------- */

@@ -290,6 +290,30 @@ int hbl_ln_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, const fl
                              static_cast<hipStream_t>(stream), ln_gain, ln_eps);
 }
 
+int hbl_debug_grouped_plan(const hbl_problem* problems, int n_problems, int* ksplit, int* gemm_workgroups,
+                           int* reduce_workgroups, int* single_call_streams) {
+    if (!problems || !ksplit || !gemm_workgroups || !reduce_workgroups || !single_call_streams) return HBL_E_NULL;
+    if (n_problems < 1 || n_problems > kMaxGroup) return HBL_E_SHAPE;
+    DecodeArgs da = {};
+    static int32_t dummy_partial;
+    for (int i = 0; i < n_problems; ++i) {
+        const hbl_problem& q = problems[i];
+        if (q.T < 1 || q.T > 64) return HBL_E_SHAPE;
+        const int rc = check_gemm_shape(q.T, q.K, q.N, q.hadamard != 0);
+        if (rc != HBL_OK) return rc;
+        DecodeProblem& dp = da.p[da.n++];
+        dp.T = (int)q.T;
+        dp.K = (int)q.K;
+        dp.N = (int)q.N;
+        dp.partial = &dummy_partial;   // the grouped call always brings a partial buffer
+        single_call_streams[i] = decode_stream_preferred(q.T, q.K, q.N) ? 1 : 0;
+    }
+    const int rc = decode_plan_for_tests(da, gemm_workgroups, reduce_workgroups);
+    if (rc != HBL_OK) return rc;
+    for (int i = 0; i < n_problems; ++i) ksplit[i] = da.p[i].ksplit;
+    return HBL_OK;
+}
+
 int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int hadamard,
                    int code_offset, int8_t* codes, float* s_dequant, int32_t* code_sum, void* stream) {
     if (code_offset != HBL_CODES_INT8 && !((code_offset == HBL_CODES_UINT4_PLUS8 || code_offset == HBL_CODES_BF6) && bits == 4))

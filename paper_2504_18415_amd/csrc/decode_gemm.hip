@@ -332,6 +332,14 @@ bool decode_stream_preferred(int64_t T, int64_t K, int64_t N) {
     return (K / 128) / a.p[0].ksplit <= 16 || wgs >= 256;
 }
 
+int decode_plan_for_tests(DecodeArgs& a, int* wgs, int* red_wgs) {
+    int max_t = 0;
+    for (int i = 0; i < a.n; ++i) max_t = a.p[i].T > max_t ? a.p[i].T : max_t;
+    if (a.n <= 0 || max_t > 64) return HBL_E_SHAPE;
+    plan(a, max_t > 16, wgs, red_wgs);
+    return HBL_OK;
+}
+
 int launch_decode_gemm(DecodeArgs& a, hipStream_t stream) {
     if (a.n <= 0) return HBL_OK;
     int max_t = 0;

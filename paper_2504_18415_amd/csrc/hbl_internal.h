@@ -157,6 +157,8 @@ struct DecodeArgs {
 constexpr int kMaxDecodeSplit = 4;
 // Fills ksplit / wg_begin / red_begin and launches.  Every problem needs T <= 64.
 int launch_decode_gemm(DecodeArgs& args, hipStream_t stream);
+// The launch plan launch_decode_gemm would use (K splits, grid sizes), without launching: host logic only.
+int decode_plan_for_tests(DecodeArgs& args, int* wgs, int* red_wgs);
 // Whether a single projection with T <= 16 is better served by the streaming form of that launch than
 // by the split-K pair of launch_ternary_gemm.
 bool decode_stream_preferred(int64_t T, int64_t K, int64_t N);

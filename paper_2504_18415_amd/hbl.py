@@ -30,7 +30,7 @@ EXPORTS = [
     "hbl_packed_bytes", "hbl_pack_ternary_2bit", "hbl_unpack_ternary_2bit", "hbl_workspace_bytes",
     "hbl_hbitlinear_forward", "hbl_plain_bitlinear_forward", "hbl_fwht_quant", "hbl_gemm_i32",
     "hbl_gemm_dequant_bf16", "hbl_grouped_workspace_bytes", "hbl_bitlinear_forward_grouped", "hbl_fwht",
-    "hbl_ln_bitlinear_forward", "hbl_ln_fwht_quant",
+    "hbl_ln_bitlinear_forward", "hbl_ln_fwht_quant", "hbl_debug_grouped_plan",
 ]
 
 _lib = None
@@ -83,6 +83,8 @@ def lib():
         L.hbl_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp, vp]
         L.hbl_gemm_dequant_bf16.argtypes = [vp, ci, vp, vp, i64, i64, vp, i64, vp, i64, vp, vp]
         L.hbl_fwht.argtypes = [vp, ci, i64, i64, vp, ci, vp]
+        ip = ctypes.POINTER(ci)
+        L.hbl_debug_grouped_plan.argtypes = [ctypes.POINTER(Problem), ci, ip, ip, ip, ip]
         L.hbl_ln_bitlinear_forward.argtypes = [vp, ci, i64, i64, vp, f32, ci, vp, i64, vp, i64, ci, f32, vp, vp, sz, vp]
         L.hbl_ln_fwht_quant.argtypes = [vp, ci, i64, i64, vp, f32, ci, f32, ci, ci, vp, vp, vp, vp]
         L.hbl_grouped_workspace_bytes.restype = sz
@@ -303,3 +305,15 @@ def ln_fwht_quant(x: torch.Tensor, ln_gain: torch.Tensor, ln_eps: float, bits: i
     _check(lib().hbl_ln_fwht_quant(_ptr(x), _x_dtype(x), T, K, _ptr(ln_gain), ln_eps, bits, eps, int(hadamard),
                                    code_offset, _ptr(codes), _ptr(sd), _ptr(cs), _stream()), "ln_fwht_quant")
     return codes, sd, cs
+
+
+def grouped_plan(shapes):
+    """Host-only: launch plan of the small-batch GEMM for [(T, K, N, hadamard), ...] ->
+    (ksplit list, gemm workgroups, reduce workgroups, list of "single call streams" flags)."""
+    n = len(shapes)
+    arr = (Problem * n)(*[Problem(0, BF16, 4, int(bool(h)), 0, T, K, N, 0, 0, 1, 0) for (T, K, N, h) in shapes])
+    ks = (ctypes.c_int * n)()
+    st = (ctypes.c_int * n)()
+    wgs, red = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().hbl_debug_grouped_plan(arr, n, ks, ctypes.byref(wgs), ctypes.byref(red), st), "grouped_plan")
+    return list(ks), wgs.value, red.value, [bool(v) for v in st]

@@ -138,3 +138,28 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(hbl, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(ImportError):
         hbl.lib()
+
+
+def test_small_batch_launch_plan(L):
+    """Host logic of the decode path: K splits and grid sizes for the 7B layer and a few odd shapes."""
+    from paper_2504_18415_amd import hbl
+    layer = lambda B: [(B, 4096, 12288, False), (B, 4096, 4096, True), (B, 4096, 32768, False), (B, 16384, 4096, True)]
+    # batch <= 16: streaming form; 2048 wave-units of 32 weight tiles = 512 workgroups = two per CU, no reduction
+    for B in (1, 8, 16):
+        ks, wgs, red, single = hbl.grouped_plan(layer(B))
+        assert ks == [1, 1, 1, 4] and wgs == 96 + 32 + 256 + 128 and red == 0
+        assert single == [True, True, True, False]        # W_down alone keeps the split-K pair of launches
+    # batch > 16: shared form; only the K = 16384 problem is split, over workgroups, and needs the reduction
+    ks, wgs, red, single = hbl.grouped_plan(layer(64))
+    assert ks == [1, 1, 1, 4] and wgs == 512 and red == 64 * 4096 // 4 // 256 and single == [False] * 4
+    # a single small problem is split down to 8 tiles per wave to reach more CUs
+    ks, wgs, red, _ = hbl.grouped_plan([(4, 4096, 4096, True)])
+    assert ks == [4] and wgs == 128 and red == 0
+    ks, wgs, red, _ = hbl.grouped_plan([(4, 128, 96, False)])        # one K block: nothing to split
+    assert ks == [1] and wgs == 1 and red == 0
+    ks, wgs, red, _ = hbl.grouped_plan([(40, 8192, 160, True)])      # shared form, few rows: split over workgroups
+    assert ks == [4] and wgs == 2 * 4 and red == (40 * 160 // 4 + 255) // 256
+    with pytest.raises(hbl.HblError):
+        hbl.grouped_plan([(65, 4096, 4096, True)])
+    with pytest.raises(hbl.HblError):
+        hbl.grouped_plan([(4, 4096 + 128, 4096, True)])
