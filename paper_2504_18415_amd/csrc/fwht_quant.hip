@@ -620,10 +620,34 @@ __host__ __device__ constexpr uint32_t swz16(uint32_t q) { return q ^ ((q >> 4) 
 // NORM: compiled with the RMS-normalisation prologue (taken when rp.ln_gain is set).  A template switch
 // rather than the run-time test alone: the prologue's presence changes the register allocation of the
 // whole body, and the plain prefill path should not pay for it.
-template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
-__device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid, const void* __restrict__ x,
+// One row's input as loaded, layout A: 64 contiguous elements per thread (8 or 16 16-byte loads).
+template <bool BF16>
+struct BigRowRaw {
+    uint4 q[BF16 ? 8 : 16];
+};
+template <int LOG2K, bool BF16>
+__device__ __forceinline__ void bigrow_load(const void* __restrict__ x, int64_t row, uint32_t tid, BigRowRaw<BF16>& raw) {
+    constexpr int K = 1 << LOG2K;
+    const int64_t first = row * (int64_t)K + tid * 64;
+    const uint4* src = BF16 ? reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(x) + first)
+                            : reinterpret_cast<const uint4*>(static_cast<const float*>(x) + first);
+#pragma unroll
+    for (int i = 0; i < (BF16 ? 8 : 16); ++i) raw.q[i] = src[i];
+}
+
+// `before_tail` is called once, by every thread, after the last exchange through LDS and ahead of the last
+// butterfly stages, the row statistics and the quantiser: the place from which a caller that walks several
+// rows starts the loads of its next row (few registers are live there besides the row itself).
+struct NoPrefetch {
+    __device__ void operator()() const {}
+};
+// ROWLOOP: the caller runs this body for one row after another, so the row buffer still has readers from
+// the previous row until every thread has passed a barrier.
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM, bool ROWLOOP = false, typename BeforeTail = NoPrefetch>
+__device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid, const BigRowRaw<BF16>& raw,
                                                        int8_t* __restrict__ codes, float* __restrict__ s_dequant,
-                                                       int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
+                                                       int32_t* __restrict__ code_sum, RowParams rp, int code_offset,
+                                                       BeforeTail before_tail = BeforeTail{}) {
     constexpr int K = 1 << LOG2K;
     constexpr int NT = K / 64;
     constexpr int W = NT / 64;
@@ -639,13 +663,10 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
     const int64_t row_off = row * (int64_t)K;
 
     float v[16][4];
-    // layout A: 64 contiguous elements per thread
     if constexpr (BF16) {
-        const uint4* src = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(x) + row_off + tid * 64);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const uint4 raw = src[i];
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+            const uint32_t w[4] = {raw.q[i].x, raw.q[i].y, raw.q[i].z, raw.q[i].w};
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 v[2 * i + h / 2][2 * (h % 2)] = as_f(w[h] << 16);
@@ -653,11 +674,9 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
             }
         }
     } else {
-        const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(x) + row_off + tid * 64);
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const float4 raw = src[j];
-            v[j][0] = raw.x; v[j][1] = raw.y; v[j][2] = raw.z; v[j][3] = raw.w;
+            v[j][0] = as_f(raw.q[j].x); v[j][1] = as_f(raw.q[j].y); v[j][2] = as_f(raw.q[j].z); v[j][3] = as_f(raw.q[j].w);
         }
     }
 
@@ -729,14 +748,15 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
 
     stages_e();
     stages_j(4);              // index bits 2-5
+    if constexpr (ROWLOOP) __syncthreads();   // after this row's first stages: the wait is mostly over by then
     lds_write(LA{});
     __syncthreads();
     lds_read(LB{});
     stages_j(4);              // index bits 6-9
-    __syncthreads();          // everyone has read before the buffer is rewritten
-    lds_write(LB{});
+    lds_write(LB{});          // to the very addresses this thread has just read: no barrier needed before it
     __syncthreads();
     lds_read(LC{});
+    before_tail();
     stages_j(LC::stages());   // index bits 10..m-1
 
     // c_n = (float)(1/sqrt(K)).  For even log2 K it is a power of two: scaling by it commutes exactly
@@ -802,44 +822,74 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
     constexpr float lo = BITS == 8 ? -128.0f : -8.0f;
     constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
     static_assert(!BF6OUT || BITS == 4 || BITS == 0, "bf6 records carry INT4 codes only");
-    if constexpr (BF6OUT) code_offset = 8;   // the table below is indexed by code + 8
-    const float magic = kMagic + (float)code_offset;
+    const float magic = kMagic + (float)code_offset;   // byte forms: the low byte of t + magic is code + offset
     if constexpr (FOLD) gain = gain * c_n;
     int isum = 0;
     int8_t* out = codes + row_off + (LC::qt(tid) << 2);
     uint32_t* c24 = reinterpret_cast<uint32_t*>(row_lds);   // BF6OUT: 24 bits of bf6 per chunk, by chunk number
     const uint32_t cbase = LC::qt(tid);
+    if constexpr (!BF6OUT) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        uint32_t packed = 0;
+        for (int j = 0; j < 16; ++j) {
+            uint32_t packed = 0;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float t = __builtin_amdgcn_fmed3f(v[j][e] * gain, lo, hi);
-            const uint32_t bits = as_u(t + magic);
-            packed |= (bits & 0xFFu) << (8 * e);
-        }
-        if (code_sum) isum = __builtin_amdgcn_sdot4((int)packed, 0x01010101, isum, false);   // += the 4 stored bytes
-        if constexpr (!BF6OUT) {
+            for (int e = 0; e < 4; ++e) {
+                const float t = __builtin_amdgcn_fmed3f(v[j][e] * gain, lo, hi);
+                const uint32_t bits = as_u(t + magic);
+                packed |= (bits & 0xFFu) << (8 * e);
+            }
+            if (code_sum) isum = __builtin_amdgcn_sdot4((int)packed, 0x01010101, isum, false);   // += the 4 stored bytes
             *reinterpret_cast<uint32_t*>(out + (LC::qj(j) << 2)) = packed;
-        } else {
-            c24[cbase ^ LC::qj(j)] = bf6_pack4(packed);
         }
-    }
-    if constexpr (BF6OUT) {
-        // regroup through LDS: four consecutive chunks (16 features, 96 bits) become three dwords
+        isum -= 64 * code_offset;
+    } else {
+        // The codes as fp32 integers (round to nearest even by adding and removing 1.5 * 2^23, which
+        // also turns -0 into +0), then the hardware's 32-value fp32 -> bf6 conversion: exact for
+        // integers in [-8, 7].  Its result holds source pair i (one value from each operand) at bits
+        // [12i, 12i+12), so with the even elements of 8 chunks in one operand and the odd ones in the
+        // other, chunk c of the 8 lands in order at bits [24c, 24c+24) of the six result dwords.
+        typedef float v16f __attribute__((ext_vector_type(16)));
+        typedef uint32_t v6u __attribute__((ext_vector_type(6)));
+        float fsum = 0.0f;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            v16f ev, od;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) {
+                float q[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    q[e] = (__builtin_amdgcn_fmed3f(v[8 * half + jj][e] * gain, lo, hi) + kMagic) - kMagic;
+                ev[2 * jj] = q[0]; od[2 * jj] = q[1];
+                ev[2 * jj + 1] = q[2]; od[2 * jj + 1] = q[3];
+            }
+            if (code_sum) {   // uniform, and off on the forward path: small integers, exact in any order
+#pragma unroll
+                for (int i = 0; i < 16; ++i) fsum += ev[i] + od[i];
+            }
+            const v6u r = __builtin_amdgcn_cvt_scalef32_2xpk16_bf6_f32(ev, od, 1.0f);
+            // one dword per chunk into LDS by chunk number; bits 24-31 of it are not meaningful
+            const uint32_t piece[8] = {r[0], __builtin_amdgcn_alignbit(r[1], r[0], 24),
+                                       __builtin_amdgcn_alignbit(r[2], r[1], 16), r[2] >> 8,
+                                       r[3], __builtin_amdgcn_alignbit(r[4], r[3], 24),
+                                       __builtin_amdgcn_alignbit(r[5], r[4], 16), r[5] >> 8};
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) c24[cbase ^ LC::qj(8 * half + jj)] = piece[jj];
+        }
+        isum = (int)fsum;
+        // regroup through LDS: four consecutive chunks (16 features, 12 bytes) become three dwords
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t quad = tid + NT * i;
             const uint4 c = *reinterpret_cast<const uint4*>(c24 + 4 * quad);
             uint32_t* dst = reinterpret_cast<uint32_t*>(codes + row_off + 32 * (quad >> 1) + 12 * (quad & 1));
-            dst[0] = c.x | (c.y << 24);
-            dst[1] = (c.y >> 8) | (c.z << 16);
-            dst[2] = (c.z >> 16) | (c.w << 8);
+            dst[0] = __builtin_amdgcn_perm(c.y, c.x, 0x04020100u);   // x0 x1 x2 y0
+            dst[1] = __builtin_amdgcn_perm(c.z, c.y, 0x05040201u);   // y1 y2 z0 z1
+            dst[2] = __builtin_amdgcn_perm(c.w, c.z, 0x06050402u);   // z2 w0 w1 w2
         }
     }
     if (code_sum) {   // uniform: the fp6 x fp4 GEMM needs no code sum
-        isum -= 64 * code_offset;
 #pragma unroll
         for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
         if constexpr (W > 1) {
@@ -854,12 +904,31 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
     if (tid == 0) s_dequant[row] = s_d;
 }
 
+// Each workgroup walks rows blockIdx.x, blockIdx.x + gridDim.x, ...; the grid is sized to what the chip holds
+// at once (the LDS row buffer allows only a few workgroups per CU), and the next row's loads are issued
+// under the tail of the current row's arithmetic so that their latency is not exposed once per row.
 template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
-__global__ __launch_bounds__((1 << LOG2K) / 64) void fwht_quant_bigrow_kernel(
-    const void* __restrict__ x, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
+__global__ __launch_bounds__((1 << LOG2K) / 64, 2) void fwht_quant_bigrow_kernel(
+    const void* __restrict__ x, int64_t T, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
     int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
-    fwht_quant_bigrow_body<LOG2K, BITS, BF16, BF6OUT, NORM>(blockIdx.x, threadIdx.x, x, codes, s_dequant, code_sum,
-                                                            rp, code_offset);
+    int64_t row = blockIdx.x;
+    BigRowRaw<BF16> cur;
+    bigrow_load<LOG2K, BF16>(x, row, threadIdx.x, cur);
+    if constexpr (BITS == 0) {   // transform only: one row per workgroup (the row loop costs it registers it lacks)
+        fwht_quant_bigrow_body<LOG2K, BITS, BF16, BF6OUT, NORM>(row, threadIdx.x, cur, codes, s_dequant, code_sum, rp,
+                                                                code_offset);
+        return;
+    }
+    for (;;) {
+        const int64_t next = row + gridDim.x;
+        BigRowRaw<BF16> ahead;
+        fwht_quant_bigrow_body<LOG2K, BITS, BF16, BF6OUT, NORM, true>(
+            row, threadIdx.x, cur, codes, s_dequant, code_sum, rp, code_offset,
+            [&]() { if (next < T) bigrow_load<LOG2K, BF16>(x, next, threadIdx.x, ahead); });
+        if (next >= T) break;
+        cur = ahead;
+        row = next;
+    }
 }
 
 template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
@@ -886,7 +955,11 @@ int launch_bigrow_form(const void* x, int64_t T, int8_t* codes, float* s_dequant
     auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16, BF6OUT, NORM>;
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(K / 64), lds, stream, x, codes, s_dequant, code_sum, rp,
+    static std::atomic<int> resident[64];          // per device: workgroups the chip holds at once
+    int grid = 0;
+    if (const int rc = resident_workgroups(kern, K / 64, lds, resident, &grid); rc != HBL_OK) return rc;
+    if ((int64_t)grid > T || BITS == 0) grid = (int)T;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(K / 64), lds, stream, x, T, codes, s_dequant, code_sum, rp,
                        code_offset);
     return after_launch();
 }
@@ -944,9 +1017,12 @@ __global__ __launch_bounds__(256) void quant_grouped_kernel(const QuantGroupArgs
         return;
 #define HBL_BIG_ROW(L2K)                                                                                      \
     case 1 << L2K:                                                                                            \
-        if (tid < (1 << L2K) / 64)                                                                            \
-            fwht_quant_bigrow_body<L2K, BITS, BF16, false, true>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum,   \
-                                                           RowParams{a.eps, p.ln_gain, p.ln_eps}, p.code_offset);                             \
+        if (tid < (1 << L2K) / 64) {                                                                          \
+            BigRowRaw<BF16> raw;                                                                              \
+            bigrow_load<L2K, BF16>(p.x, row, tid, raw);                                                       \
+            fwht_quant_bigrow_body<L2K, BITS, BF16, false, true>(row, tid, raw, p.codes, p.s_dequant, p.code_sum, \
+                                                                 RowParams{a.eps, p.ln_gain, p.ln_eps}, p.code_offset); \
+        }                                                                                                     \
         return;
     switch (p.K) {
         HBL_SMALL_ROW(7)

@@ -36,6 +36,29 @@ inline int allow_dynamic_lds(Kernel kern, size_t bytes, std::atomic<uint64_t>& d
     return HBL_OK;
 }
 
+// Number of workgroups of `kern` (threads per workgroup, dynamic LDS bytes) that the current device holds at
+// once: occupancy per CU times the CU count, asked once per (kernel, device).  `cache` is the caller's
+// per-instantiation table of 64 zero-initialised slots (device ordinal mod 64).
+template <typename Kernel>
+inline int resident_workgroups(Kernel kern, int threads, size_t lds_bytes, std::atomic<int>* cache, int* out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return note_hip_error(e);
+    std::atomic<int>& slot = cache[dev & 63];
+    int n = slot.load(std::memory_order_acquire);
+    if (n == 0) {
+        int per_cu = 0, cus = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void*>(kern), threads, lds_bytes);
+        if (e != hipSuccess) return note_hip_error(e);
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return note_hip_error(e);
+        n = (per_cu < 1 ? 1 : per_cu) * (cus < 1 ? 1 : cus);
+        slot.store(n, std::memory_order_release);
+    }
+    *out = n;
+    return HBL_OK;
+}
+
 inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
