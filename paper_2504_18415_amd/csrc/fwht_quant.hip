@@ -51,6 +51,73 @@ __device__ __forceinline__ float lane_xor(float v) {
     }
 }
 
+// Whole-wave reductions whose result every lane receives; all 64 lanes must be active.
+// Form 1, data-parallel moves: inside a row of 16 lanes two quad permutes, then the half-row and row mirrors
+// (each step adds the same two partial results in both lanes of a pair, so all lanes of the row agree); the
+// four row results are then read lane by lane and combined in a fixed order.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint64_t r = (uint64_t)dpp_move<CTRL>((uint32_t)u) | ((uint64_t)dpp_move<CTRL>((uint32_t)(u >> 32)) << 32);
+    return __builtin_bit_cast(double, r);
+}
+__device__ __forceinline__ uint32_t read_lane(uint32_t v, int lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+__device__ __forceinline__ double read_lane(double v, int lane) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint64_t r = (uint64_t)read_lane((uint32_t)u, lane) | ((uint64_t)read_lane((uint32_t)(u >> 32), lane) << 32);
+    return __builtin_bit_cast(double, r);
+}
+__device__ __forceinline__ double wave_sum_dpp(double s) {
+    s += dpp_move<0xB1>(s);    // quad_perm [1,0,3,2]
+    s += dpp_move<0x4E>(s);    // quad_perm [2,3,0,1]
+    s += dpp_move<0x141>(s);   // row_half_mirror
+    s += dpp_move<0x140>(s);   // row_mirror
+    return ((read_lane(s, 0) + read_lane(s, 16)) + read_lane(s, 32)) + read_lane(s, 48);
+}
+__device__ __forceinline__ int wave_sum_dpp(int value) {   // modulo 2^32
+    uint32_t s = (uint32_t)value;
+    s += dpp_move<0xB1>(s);
+    s += dpp_move<0x4E>(s);
+    s += dpp_move<0x141>(s);
+    s += dpp_move<0x140>(s);
+    return (int)(read_lane(s, 0) + read_lane(s, 16) + read_lane(s, 32) + read_lane(s, 48));
+}
+__device__ __forceinline__ float wave_max_dpp(float m) {
+    m = fmaxf(m, as_f(dpp_move<0xB1>(as_u(m))));
+    m = fmaxf(m, as_f(dpp_move<0x4E>(as_u(m))));
+    m = fmaxf(m, as_f(dpp_move<0x141>(as_u(m))));
+    m = fmaxf(m, as_f(dpp_move<0x140>(as_u(m))));
+    return fmaxf(fmaxf(as_f(read_lane(as_u(m), 0)), as_f(read_lane(as_u(m), 16))),
+                 fmaxf(as_f(read_lane(as_u(m), 32)), as_f(read_lane(as_u(m), 48))));
+}
+// Form 2, six xor-shuffle rounds through the LDS crossbar: long dependent latency but no vector-ALU work.
+// A launch that keeps every SIMD busy with other waves runs faster with these (5 % on 8192 rows of 16384); a
+// launch of a few rows runs faster with form 1 (1.5 us per decode layer).  `few_rows` is uniform.
+__device__ __forceinline__ double wave_sum(double s, int few_rows) {
+    if (few_rows) return wave_sum_dpp(s);
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+    return s;
+}
+__device__ __forceinline__ int wave_sum(int s, int few_rows) {
+    if (few_rows) return wave_sum_dpp(s);
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+    return s;
+}
+__device__ __forceinline__ float wave_max(float m, int few_rows) {
+    if (few_rows) return wave_max_dpp(m);
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) m = fmaxf(m, __shfl_xor(m, sft, 64));
+    return m;
+}
+
 template <int MASK, int R, int CH>
 __device__ __forceinline__ void lane_stage(float (&v)[R][CH], int lane) {
     // lanes with the bit clear compute a + b, lanes with it set compute a - b = partner - own
@@ -135,14 +202,15 @@ struct RowParams {
     float eps;
     const float* ln_gain;   // [K] fp32 or nullptr
     float ln_eps;
+    int few_rows;           // a launch of at most 64 rows: latency matters, not throughput (reduction form)
 };
 
 // r of the row from this thread's partial sum of squares `ss`: wave butterfly, then a fixed-order
 // combine of the NW per-wave sums through `red` (NW doubles of LDS; one barrier).
 template <int NW>
-__device__ __forceinline__ float rms_factor(double ss, double* red, int lane, int wave, int K, float ln_eps) {
-#pragma unroll
-    for (int sft = 1; sft < 64; sft <<= 1) ss += __shfl_xor(ss, sft, 64);
+__device__ __forceinline__ float rms_factor(double ss, double* red, int lane, int wave, int K, float ln_eps,
+                                            int few_rows) {
+    ss = wave_sum(ss, few_rows);
     if constexpr (NW > 1) {
         if (lane == 0) red[wave] = ss;
         __syncthreads();
@@ -190,6 +258,7 @@ template <int LOG2K, int W, int BITS, bool BF16, bool HADAMARD>
 __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void* __restrict__ x,
                                                 int8_t* __restrict__ codes, float* __restrict__ s_dequant,
                                                 int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
+    const int few_rows = rp.few_rows;
     constexpr int K = 1 << LOG2K;
     constexpr int NT = 64 * W;
     constexpr int E = K / NT;            // elements per thread
@@ -217,7 +286,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int e = 0; e < CH; ++e) ss += (double)v[r][e] * (double)v[r][e];
-        const float rn = rms_factor<W>(ss, red_n, lane, wave, K, rp.ln_eps);
+        const float rn = rms_factor<W>(ss, red_n, lane, wave, K, rp.ln_eps, few_rows);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float gv[CH];
@@ -324,8 +393,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int e = 0; e < CH; ++e) m = fmaxf(m, fabsf(v[r][e]));
-#pragma unroll
-        for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+        m = wave_max(m, few_rows);
         if constexpr (W > 1) {
             if (lane == 0) red_f[wave] = m;
             __syncthreads();
@@ -341,8 +409,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int e = 0; e < CH; ++e) s += (double)fabsf(v[r][e]);
-#pragma unroll
-        for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+        s = wave_sum(s, few_rows);
         if constexpr (W > 1) {
             if (lane == 0) red_d[wave] = s;
             __syncthreads();
@@ -398,8 +465,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
         }
     }
     isum = (int)((uint32_t)isum - (uint32_t)E * as_u(magic));  // remove the constant's bit pattern (mod 2^32)
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
+    isum = wave_sum(isum, few_rows);
     if constexpr (W > 1) {
         if (lane == 0) red_i[wave] = isum;
         __syncthreads();
@@ -442,6 +508,7 @@ template <int BITS, bool BF16, int MAXC = 8>
 __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const void* __restrict__ x, int K,
                                                    int8_t* __restrict__ codes, float* __restrict__ s_dequant,
                                                    int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
+    const int few_rows = rp.few_rows;
     __shared__ double red_d[4];
     __shared__ float red_f[4];
     __shared__ int red_i[4];
@@ -466,7 +533,7 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
         for (int c = 0; c < MAXC; ++c)
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss += (double)v[c][e] * (double)v[c][e];
-        const float rn = rms_factor<4>(ss, red_n, lane, wave, K, rp.ln_eps);
+        const float rn = rms_factor<4>(ss, red_n, lane, wave, K, rp.ln_eps, few_rows);
 #pragma unroll
         for (int c = 0; c < MAXC; ++c) {
             const int ch = c * 256 + tid;
@@ -485,8 +552,7 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
         for (int c = 0; c < MAXC; ++c)
 #pragma unroll
             for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(v[c][e]));
-#pragma unroll
-        for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+        m = wave_max(m, few_rows);
         if (lane == 0) red_f[wave] = m;
         __syncthreads();
         m = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
@@ -498,8 +564,7 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
         for (int c = 0; c < MAXC; ++c)
 #pragma unroll
             for (int e = 0; e < 8; ++e) s += (double)fabsf(v[c][e]);
-#pragma unroll
-        for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+        s = wave_sum(s, few_rows);
         if (lane == 0) red_d[wave] = s;
         __syncthreads();
         s = ((red_d[0] + red_d[1]) + red_d[2]) + red_d[3];
@@ -531,8 +596,7 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
             else *reinterpret_cast<uint2*>(codes + row_off + (int64_t)ch * 8) = make_uint2(packed[0], packed[1]);
         }
     }
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
+    isum = wave_sum(isum, few_rows);
     if (lane == 0) red_i[wave] = isum;
     __syncthreads();
     if (tid == 0) {
@@ -648,6 +712,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
                                                        int8_t* __restrict__ codes, float* __restrict__ s_dequant,
                                                        int32_t* __restrict__ code_sum, RowParams rp, int code_offset,
                                                        BeforeTail before_tail = BeforeTail{}) {
+    constexpr int few_rows = ROWLOOP ? 0 : 1;   // the row loop is the throughput form
     constexpr int K = 1 << LOG2K;
     constexpr int NT = K / 64;
     constexpr int W = NT / 64;
@@ -687,7 +752,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
         for (int j = 0; j < 16; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) ss += (double)v[j][e] * (double)v[j][e];
-        const float rn = rms_factor<W>(ss, red_n, lane, wave, K, rp.ln_eps);
+        const float rn = rms_factor<W>(ss, red_n, lane, wave, K, rp.ln_eps, few_rows);
         const float4* gsrc = reinterpret_cast<const float4*>(rp.ln_gain + tid * 64);
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
@@ -786,8 +851,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
         for (int j = 0; j < 16; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) m = fmaxf(m, fabsf(v[j][e]));
-#pragma unroll
-        for (int s = 1; s < 64; s <<= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+        m = wave_max(m, few_rows);
         if constexpr (W > 1) {
             if (lane == 0) red_f[wave] = m;
             __syncthreads();
@@ -804,8 +868,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
         for (int j = 0; j < 16; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) s += (double)fabsf(v[j][e]);
-#pragma unroll
-        for (int sft = 1; sft < 64; sft <<= 1) s += __shfl_xor(s, sft, 64);
+        s = wave_sum(s, few_rows);
         if constexpr (W > 1) {
             if (lane == 0) red_d[wave] = s;
             __syncthreads();
@@ -890,8 +953,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
         }
     }
     if (code_sum) {   // uniform: the fp6 x fp4 GEMM needs no code sum
-#pragma unroll
-        for (int s = 1; s < 64; s <<= 1) isum += __shfl_xor(isum, s, 64);
+        isum = wave_sum(isum, few_rows);
         if constexpr (W > 1) {
             if (lane == 0) red_i[wave] = isum;
             __syncthreads();
@@ -910,14 +972,15 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
 // compiler also moves the ~100 per-thread LDS and global address computations out of the row loop and keeps
 // them in registers (about 200 VGPRs in all): measured 7-20 % faster than recomputing them per row, and the
 // LDS row buffer limits the workgroups per CU before the registers do.
-template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
+// FEW: at most 64 rows - one row per workgroup and the short-latency reductions.
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM, bool FEW>
 __global__ __launch_bounds__((1 << LOG2K) / 64, 2) void fwht_quant_bigrow_kernel(
     const void* __restrict__ x, int64_t T, int8_t* __restrict__ codes, float* __restrict__ s_dequant,
     int32_t* __restrict__ code_sum, RowParams rp, int code_offset) {
     int64_t row = blockIdx.x;
     BigRowRaw<BF16> cur;
     bigrow_load<LOG2K, BF16>(x, row, threadIdx.x, cur);
-    if constexpr (BITS == 0) {   // transform only: one row per workgroup (the row loop costs it registers it lacks)
+    if constexpr (BITS == 0 || FEW) {   // (transform only: the row loop would cost it registers it lacks)
         fwht_quant_bigrow_body<LOG2K, BITS, BF16, BF6OUT, NORM>(row, threadIdx.x, cur, codes, s_dequant, code_sum, rp,
                                                                 code_offset);
         return;
@@ -935,7 +998,7 @@ __global__ __launch_bounds__((1 << LOG2K) / 64, 2) void fwht_quant_bigrow_kernel
     }
 }
 
-template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM, bool FEW>
 int launch_bigrow_form(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, RowParams rp,
                        int code_offset, hipStream_t stream);
 
@@ -943,26 +1006,34 @@ template <int LOG2K, int BITS, bool BF16, bool BF6OUT = false>
 int launch_bigrow(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, RowParams rp,
                   int code_offset, hipStream_t stream) {
     if constexpr (BITS != 0) {
-        if (rp.ln_gain)
-            return launch_bigrow_form<LOG2K, BITS, BF16, BF6OUT, true>(x, T, codes, s_dequant, code_sum, rp, code_offset,
-                                                                       stream);
+        const bool norm = rp.ln_gain != nullptr;
+        if (rp.few_rows)
+            return norm ? launch_bigrow_form<LOG2K, BITS, BF16, BF6OUT, true, true>(x, T, codes, s_dequant, code_sum, rp,
+                                                                                    code_offset, stream)
+                        : launch_bigrow_form<LOG2K, BITS, BF16, BF6OUT, false, true>(x, T, codes, s_dequant, code_sum, rp,
+                                                                                     code_offset, stream);
+        if (norm)
+            return launch_bigrow_form<LOG2K, BITS, BF16, BF6OUT, true, false>(x, T, codes, s_dequant, code_sum, rp,
+                                                                              code_offset, stream);
     }
-    return launch_bigrow_form<LOG2K, BITS, BF16, BF6OUT, false>(x, T, codes, s_dequant, code_sum, rp, code_offset,
-                                                                stream);
+    return launch_bigrow_form<LOG2K, BITS, BF16, BF6OUT, false, false>(x, T, codes, s_dequant, code_sum, rp, code_offset,
+                                                                       stream);
 }
 
-template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM>
+template <int LOG2K, int BITS, bool BF16, bool BF6OUT, bool NORM, bool FEW>
 int launch_bigrow_form(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_t* code_sum, RowParams rp,
                        int code_offset, hipStream_t stream) {
     constexpr int K = 1 << LOG2K;
     constexpr size_t lds = sizeof(float) * K;
-    auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16, BF6OUT, NORM>;
+    auto kern = fwht_quant_bigrow_kernel<LOG2K, BITS, BF16, BF6OUT, NORM, FEW>;
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
-    static std::atomic<int> resident[64];          // per device: workgroups the chip holds at once
-    int grid = 0;
-    if (const int rc = resident_workgroups(kern, K / 64, lds, resident, &grid); rc != HBL_OK) return rc;
-    if ((int64_t)grid > T || BITS == 0) grid = (int)T;
+    int grid = (int)T;   // one row per workgroup ...
+    if constexpr (BITS != 0 && !FEW) {   // ... or as many workgroups as the chip holds at once, walking the rows
+        static std::atomic<int> resident[64];
+        if (const int rc = resident_workgroups(kern, K / 64, lds, resident, &grid); rc != HBL_OK) return rc;
+        if ((int64_t)grid > T) grid = (int)T;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(K / 64), lds, stream, x, T, codes, s_dequant, code_sum, rp,
                        code_offset);
     return after_launch();
@@ -1010,13 +1081,13 @@ __global__ __launch_bounds__(256) void quant_grouped_kernel(const QuantGroupArgs
     const int64_t row = (int)blockIdx.x - p.row_begin;
     const int tid = threadIdx.x;
     if (!p.hadamard) {
-        quant_generic_body<BITS, BF16>(row, tid, p.x, p.K, p.codes, p.s_dequant, p.code_sum, RowParams{a.eps, p.ln_gain, p.ln_eps}, p.code_offset);
+        quant_generic_body<BITS, BF16>(row, tid, p.x, p.K, p.codes, p.s_dequant, p.code_sum, RowParams{a.eps, p.ln_gain, p.ln_eps, 1}, p.code_offset);
         return;
     }
 #define HBL_SMALL_ROW(L2K)                                                                                    \
     case 1 << L2K:                                                                                            \
         if (tid < 64)                                                                                         \
-            fwht_quant_body<L2K, 1, BITS, BF16, true>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum, RowParams{a.eps, p.ln_gain, p.ln_eps}, \
+            fwht_quant_body<L2K, 1, BITS, BF16, true>(row, tid, p.x, p.codes, p.s_dequant, p.code_sum, RowParams{a.eps, p.ln_gain, p.ln_eps, 1}, \
                                                       p.code_offset);                                         \
         return;
 #define HBL_BIG_ROW(L2K)                                                                                      \
@@ -1025,7 +1096,7 @@ __global__ __launch_bounds__(256) void quant_grouped_kernel(const QuantGroupArgs
             BigRowRaw<BF16> raw;                                                                              \
             bigrow_load<L2K, BF16>(p.x, row, tid, raw);                                                       \
             fwht_quant_bigrow_body<L2K, BITS, BF16, false, true>(row, tid, raw, p.codes, p.s_dequant, p.code_sum, \
-                                                                 RowParams{a.eps, p.ln_gain, p.ln_eps}, p.code_offset); \
+                                                                 RowParams{a.eps, p.ln_gain, p.ln_eps, 1}, p.code_offset); \
         }                                                                                                     \
         return;
     switch (p.K) {
@@ -1071,12 +1142,12 @@ int launch_fwht_only(const void* x, int x_dtype, int64_t T, int64_t K, void* out
     int8_t* o = static_cast<int8_t*>(out);
 #define HBL_SMALL(L2K)                                                                                           \
     case 1 << L2K:                                                                                               \
-        return bf ? launch_one<L2K, 1, 0, true, true>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f}, out_dtype, stream)        \
-                  : launch_one<L2K, 1, 0, false, true>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f}, out_dtype, stream);
+        return bf ? launch_one<L2K, 1, 0, true, true>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f, 0}, out_dtype, stream)        \
+                  : launch_one<L2K, 1, 0, false, true>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f, 0}, out_dtype, stream);
 #define HBL_BIG(L2K)                                                                                             \
     case 1 << L2K:                                                                                               \
-        return bf ? launch_bigrow<L2K, 0, true, false>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f}, out_dtype, stream)       \
-                  : launch_bigrow<L2K, 0, false, false>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f}, out_dtype, stream);
+        return bf ? launch_bigrow<L2K, 0, true, false>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f, 0}, out_dtype, stream)       \
+                  : launch_bigrow<L2K, 0, false, false>(x, T, o, nullptr, nullptr, RowParams{0.0f, nullptr, 0.0f, 0}, out_dtype, stream);
     switch (K) {
         HBL_SMALL(7)
         HBL_SMALL(8)
@@ -1096,7 +1167,7 @@ int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream,
                       const float* ln_gain, float ln_eps) {
     if (T == 0) return HBL_OK;
-    const RowParams rp = {eps, ln_gain, ln_eps};
+    const RowParams rp = {eps, ln_gain, ln_eps, T <= 64 ? 1 : 0};
     if (code_offset == kCodesBf6 && (bits != 4 || K < 512)) return HBL_E_SHAPE;   // records need 8-element chunks
     if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
     if (hadamard && (code_offset == kCodesBf6 || !getenv("HBL_FWHT_OLD"))) {
