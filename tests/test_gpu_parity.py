@@ -248,7 +248,11 @@ def test_bf6_code_records_and_f6f4_gemm(hbl, K, hadamard):
     c_ref, s_ref = O.fwht_quant(x, 4, hadamard=hadamard, eps=EPS)
     xd = dev_x(x)
     rec, sd, cs = hbl.fwht_quant(xd, 4, hadamard, EPS, code_offset=hbl.CODES_BF6)
-    assert np.array_equal(decode_bf6_records(rec.cpu().numpy().view(np.uint8), K), c_ref.astype(np.int32))
+    rec_np = rec.cpu().numpy().view(np.uint8)
+    assert np.array_equal(decode_bf6_records(rec_np, K), c_ref.astype(np.int32))
+    # and bit for bit: the 24 data bytes of every record hold the canonical patterns (code 0 is +0, never -0)
+    want = encode_bf6_records(c_ref.astype(np.int32))
+    assert np.array_equal(rec_np.reshape(T, K // 32, 32)[:, :, :24], want.reshape(T, K // 32, 32)[:, :, :24])
     assert np.array_equal(sd.cpu().numpy(), s_ref)
     assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
     wc_ref, al_ref, wc_d, al_d, packed = setup_weights(hbl, site)
@@ -290,6 +294,30 @@ def encode_bf6_records(codes):
         for b in range(8):
             rec[:, :, 8 * w + b] = ((words[w] >> np.uint64(8 * b)) & np.uint64(0xFF)).astype(np.uint8)
     return rec.reshape(T, K)
+
+
+@pytest.mark.parametrize("K,T", [(16384, 1100), (8192, 2300), (4096, 4500)])
+def test_quantiser_rows_walked_by_resident_workgroups(hbl, K, T):
+    """More rows than the chip holds workgroups of the K >= 4096 quantiser at once: every workgroup then walks
+    several rows (the last round ragged), loading the next row while it finishes the current one.  Codes, scales
+    and code sums of all rows against the oracle, in the record form and both byte forms."""
+    note(f"row-walking quantiser K={K} T={T}")
+    site = synth.Site("a", T, K, 32, hadamard=True, outlier_frac=0.01, outlier_scale=30.0, seed=K + T)
+    x = synth.make_x(site)
+    xd = dev_x(x)
+    c4, s4 = O.fwht_quant(x, 4, hadamard=True, eps=EPS)
+    rec, sd, cs = hbl.fwht_quant(xd, 4, True, EPS, code_offset=hbl.CODES_BF6)
+    want = encode_bf6_records(c4.astype(np.int32)).reshape(T, K // 32, 32)[:, :, :24]
+    assert np.array_equal(rec.cpu().numpy().view(np.uint8).reshape(T, K // 32, 32)[:, :, :24], want)
+    assert np.array_equal(sd.cpu().numpy(), s4)
+    assert np.array_equal(cs.cpu().numpy(), c4.astype(np.int32).sum(1))
+    c, sd, cs = hbl.fwht_quant(xd, 4, True, EPS, code_offset=8)
+    assert np.array_equal(c.cpu().numpy().astype(np.int32) - 8, c4.astype(np.int32))
+    assert np.array_equal(sd.cpu().numpy(), s4) and np.array_equal(cs.cpu().numpy(), c4.astype(np.int32).sum(1))
+    c8, s8 = O.fwht_quant(x, 8, hadamard=True, eps=EPS)
+    c, sd, cs = hbl.fwht_quant(xd, 8, True, EPS)
+    assert np.array_equal(c.cpu().numpy(), c8)
+    assert np.array_equal(sd.cpu().numpy(), s8) and np.array_equal(cs.cpu().numpy(), c8.astype(np.int32).sum(1))
 
 
 def test_f6f4_gemm_extreme_codes(hbl):
