@@ -134,18 +134,21 @@ def cpu_baseline(site, x_host, W_host, synth, np, budget_s=15.0):
     """The oracle as it stands, on a bounded sample of token rows of the same workload."""
     from oracle import hbl_oracle as O
     wc, alpha = O.ternarize_weights_absmean(W_host, 1e-5)
-    rows = 4 * O.num_threads()   # probe: a few rows per thread, so that the estimate sees every core busy
+    rows = min(site.T, 4 * O.num_threads())   # probe: a few rows per thread, so that the estimate sees every core busy
     t0 = time.perf_counter()
     O.bitlinear_forward(np.ascontiguousarray(x_host[:rows]), wc, alpha, 4, site.hadamard, 1e-5)
     dt = time.perf_counter() - t0
     rows2 = int(max(rows, min(site.T, rows * budget_s / max(dt, 1e-3))))
-    rows2 = max(O.num_threads(), rows2 // O.num_threads() * O.num_threads())
+    rows2 = min(site.T, max(O.num_threads(), rows2 // O.num_threads() * O.num_threads()))
     t0 = time.perf_counter()
     O.bitlinear_forward(np.ascontiguousarray(x_host[:rows2]), wc, alpha, 4, site.hadamard, 1e-5)
     dt = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    O.fwht_quant(np.ascontiguousarray(x_host[:rows2]), 4, hadamard=site.hadamard, eps=1e-5)
+    dt_quant = time.perf_counter() - t0   # the front end alone, on the same rows (not part of `value`)
     return {
         "value": 2.0 * rows2 * site.K * site.N / dt / 1e12, "unit": "TOPS", "cores": O.num_threads(),
-        "kind": "oracle", "seconds": dt,
+        "kind": "oracle", "seconds": dt, "seconds_fwht_quant": dt_quant, "seconds_gemm_dequant": max(dt - dt_quant, 0.0),
         "sample": f"first {rows2} of {site.T} token rows of the same X, all {site.N} outputs "
                   f"(FWHT + INT4 quantiser + int32 GEMM + bf16 dequant)",
     }
