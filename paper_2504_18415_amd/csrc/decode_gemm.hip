@@ -47,15 +47,20 @@ __device__ __forceinline__ DecodeProblem select_problem(const DecodeArgs& args, 
     return p;
 }
 
-template <bool SHARE, int TT, int RQ, int D>
-__global__ __launch_bounds__(256, 2) void decode_gemm_kernel(const DecodeArgs args) {
+// NW = waves per workgroup.  Four everywhere except the streaming form on a single long-K problem with few row
+// tiles (W_down alone): there 8 waves share a row tile's K range, which shortens each wave's serial chain of
+// tiles (128 workgroups cannot be made more without narrower row tiles).
+template <bool SHARE, int TT, int RQ, int D, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(const DecodeArgs args) {
     constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;    // token rows of one code stage
     constexpr int XB = ROWS * kBK;                    // bytes of one code stage
-    constexpr int XW = SHARE ? XB : 4 * XB;           // code bytes per stage in the workgroup
-    constexpr int STAGE = XW + 4 * 1024;              // + one packed weight tile per wave
+    constexpr int XW = SHARE ? XB : NW * XB;          // code bytes per stage in the workgroup
+    constexpr int STAGE = XW + NW * 1024;             // + one packed weight tile per wave
     constexpr int XL = SHARE ? TT : RQ;               // code copies per wave per stage
     constexpr int NACC = TT == 1 ? 2 : TT;
     static_assert(D >= 3 && (ROWS & (ROWS - 1)) == 0, "pipeline depth / row count");
+    static_assert(!SHARE || NW == 4, "the shared form is written for four waves");
+    static_assert(NW * 4096 <= D * STAGE, "the in-workgroup reduction reuses the stage buffers");
 
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
@@ -64,7 +69,7 @@ __global__ __launch_bounds__(256, 2) void decode_gemm_kernel(const DecodeArgs ar
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kl = p.ksplit == 4 ? 2 : (p.ksplit == 2 ? 1 : 0);   // ksplit is 1, 2 or 4
+    const int kl = __builtin_ctz((unsigned)p.ksplit);   // ksplit is a power of two, at most NW
     const int nkb_total = p.K / kBK;
     const int nkb = nkb_total >> kl;
     int nt, ks;
@@ -72,7 +77,7 @@ __global__ __launch_bounds__(256, 2) void decode_gemm_kernel(const DecodeArgs ar
         nt = 4 * (w >> kl) + wave;
         ks = w & (p.ksplit - 1);
     } else {
-        nt = w * (4 >> kl) + (wave >> kl);
+        nt = w * (NW >> kl) + (wave >> kl);
         ks = wave & (p.ksplit - 1);
     }
     const int nt_max = p.N / 32 - 1;
@@ -256,14 +261,14 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const DecodeArgs arg
                      p.w_row_sum + n, p.K);
 }
 
-template <bool SHARE, int TT, int RQ, int D>
+template <bool SHARE, int TT, int RQ, int D, int NW = 4>
 int launch_form(const DecodeArgs& a, int wgs, int red_wgs, hipStream_t stream) {
     constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;
-    constexpr size_t lds = (size_t)D * ((SHARE ? 1 : 4) * ROWS * kBK + 4 * 1024);
-    auto kern = decode_gemm_kernel<SHARE, TT, RQ, D>;
+    constexpr size_t lds = (size_t)D * ((SHARE ? 1 : NW) * ROWS * kBK + NW * 1024);
+    auto kern = decode_gemm_kernel<SHARE, TT, RQ, D, NW>;
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(256), lds, stream, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * NW), lds, stream, a);
     int rc = after_launch();
     if (rc != HBL_OK || red_wgs == 0) return rc;
     hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)red_wgs), dim3(256), 0, stream, a);
@@ -317,6 +322,24 @@ void plan(DecodeArgs& a, bool share, int* wgs_out, int* red_out) {
     *red_out = red;
 }
 
+// A single streaming-form problem whose four-wave plan would leave long serial chains of tiles on few
+// workgroups (W_down alone: 128 row tiles, 128 K blocks): waves per workgroup for the wide form, or 0.
+int wide_waves(const DecodeArgs& a, int max_t) {
+    if (a.n != 1 || max_t > 16) return 0;
+    const DecodeProblem& p = a.p[0];
+    const int nkb = p.K / 128, tiles = p.N / 32;
+    if (nkb < 64 || tiles > 192) return 0;
+    const int nw = 8;   // 16 waves measured equal at batch 1 and 5 % slower at batch 8 and 16
+    return nkb % nw == 0 ? nw : 0;
+}
+void plan_wide(DecodeArgs& a, int nw, int* wgs_out) {
+    DecodeProblem& p = a.p[0];
+    p.ksplit = nw;   // one row tile per workgroup, its K range over all waves: 8 tiles or more per wave (nkb >= 64)
+    p.wg_begin = 0;
+    p.red_begin = 0;
+    *wgs_out = (p.N / 32 * p.ksplit + nw - 1) / nw;
+}
+
 }  // namespace
 
 bool decode_stream_preferred(int64_t T, int64_t K, int64_t N) {
@@ -326,6 +349,7 @@ bool decode_stream_preferred(int64_t T, int64_t K, int64_t N) {
     a.p[0].T = (int)T;
     a.p[0].K = (int)K;
     a.p[0].N = (int)N;
+    if (wide_waves(a, (int)T) != 0) return true;
     int wgs, red;
     plan(a, false, &wgs, &red);
     // a wave's tiles are a serial chain: few workgroups with long chains leave most of the chip idle
@@ -336,6 +360,11 @@ int decode_plan_for_tests(DecodeArgs& a, int* wgs, int* red_wgs) {
     int max_t = 0;
     for (int i = 0; i < a.n; ++i) max_t = a.p[i].T > max_t ? a.p[i].T : max_t;
     if (a.n <= 0 || max_t > 64) return HBL_E_SHAPE;
+    if (const int nw = wide_waves(a, max_t); nw != 0) {
+        plan_wide(a, nw, wgs);
+        *red_wgs = 0;
+        return HBL_OK;
+    }
     plan(a, max_t > 16, wgs, red_wgs);
     return HBL_OK;
 }
@@ -346,6 +375,11 @@ int launch_decode_gemm(DecodeArgs& a, hipStream_t stream) {
     for (int i = 0; i < a.n; ++i) max_t = a.p[i].T > max_t ? a.p[i].T : max_t;
     if (max_t > 64) return HBL_E_SHAPE;
     int wgs, red;
+    if (const int nw = wide_waves(a, max_t); nw != 0) {
+        plan_wide(a, nw, &wgs);
+        return max_t <= 8 ? launch_form<false, 1, 1, 4, 8>(a, wgs, 0, stream)
+                          : launch_form<false, 1, 2, 4, 8>(a, wgs, 0, stream);
+    }
     plan(a, max_t > 16, &wgs, &red);
     // Stages in flight per wave.  Shallow is best (measured 3..8): the memory-level parallelism comes from
     // the 2048 waves of a full grid, and deeper rings only cost LDS and queueing.  HBL_DECODE_DEPTH overrides.

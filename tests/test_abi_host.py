@@ -148,13 +148,20 @@ def test_small_batch_launch_plan(L):
     for B in (1, 8, 16):
         ks, wgs, red, single = hbl.grouped_plan(layer(B))
         assert ks == [1, 1, 1, 4] and wgs == 96 + 32 + 256 + 128 and red == 0
-        assert single == [True, True, True, False]        # W_down alone keeps the split-K pair of launches
+        assert single == [True, True, True, True]
     # batch > 16: shared form; only the K = 16384 problem is split, over workgroups, and needs the reduction
     ks, wgs, red, single = hbl.grouped_plan(layer(64))
     assert ks == [1, 1, 1, 4] and wgs == 512 and red == 64 * 4096 // 4 // 256 and single == [False] * 4
     # a single small problem is split down to 8 tiles per wave to reach more CUs
     ks, wgs, red, _ = hbl.grouped_plan([(4, 4096, 4096, True)])
     assert ks == [4] and wgs == 128 and red == 0
+    # W_down alone: 128 row tiles and 128 K blocks - the 8 waves of a wider workgroup share a row tile's K range
+    ks, wgs, red, single = hbl.grouped_plan([(8, 16384, 4096, True)])
+    assert ks == [8] and wgs == 128 and red == 0 and single == [True]
+    ks, wgs, red, single = hbl.grouped_plan([(16, 16384, 4096, True)])
+    assert ks == [8] and wgs == 128 and red == 0 and single == [True]
+    ks, wgs, red, single = hbl.grouped_plan([(32, 16384, 4096, True)])   # shared form: split over workgroups
+    assert ks == [4] and wgs == 128 and red > 0 and single == [False]
     ks, wgs, red, _ = hbl.grouped_plan([(4, 128, 96, False)])        # one K block: nothing to split
     assert ks == [1] and wgs == 1 and red == 0
     ks, wgs, red, _ = hbl.grouped_plan([(40, 8192, 160, True)])      # shared form, few rows: split over workgroups
