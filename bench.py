@@ -313,7 +313,7 @@ def bench_decode(args, hbl, synth, torch, np):
                         "67.1 MB in 15 us (profiles/decode_layer_kernels_config5.txt)"}
     return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes, "roofline": roofline,
             "launch": "one HIP graph of all layers; sequential = four forward calls per layer in model order "
-                      "(2-3 kernel nodes each), grouped = one hbl_bitlinear_forward_grouped call per layer "
+                      "(2 kernel nodes each, 3 above batch 16), grouped = one hbl_bitlinear_forward_grouped call per layer "
                       "(one quantiser launch, one weight-streaming GEMM launch, one reduction launch for batch > 16)",
             "batch": res}
 
