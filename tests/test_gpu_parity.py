@@ -642,6 +642,25 @@ def test_fwht_only_errors_and_empty(hbl):
     assert hbl.fwht(torch.zeros((0, 256), dtype=torch.float32, device="cuda")).shape == (0, 256)
 
 
+@pytest.mark.parametrize("K,T,dtype", [(16384, 700, synth.BF16), (4096, 4400, synth.BF16), (8192, 1500, synth.F32)])
+def test_ln_quantiser_rows_walked_by_resident_workgroups(hbl, K, T, dtype):
+    """The row-walking launch form with the RMS normalisation in front (its own instantiations of the kernel):
+    several rows per workgroup, record form and byte form, all rows against the oracle."""
+    note(f"row-walking ln quantiser K={K} T={T} {dtype}")
+    g = ln_gain_for(K, K + T)
+    site = synth.Site("a", T, K, 32, hadamard=True, x_dtype=dtype, outlier_frac=0.01, outlier_scale=30.0, seed=T)
+    x = synth.make_x(site)
+    c4, s4 = O.fwht_quant(O.rmsnorm(x, g, 1e-6), 4, hadamard=True, eps=EPS)
+    xd, gd = dev_x(x), torch.from_numpy(g).cuda()
+    rec, sd, cs = hbl.ln_fwht_quant(xd, gd, 1e-6, 4, True, EPS, code_offset=hbl.CODES_BF6)
+    want = encode_bf6_records(c4.astype(np.int32)).reshape(T, K // 32, 32)[:, :, :24]
+    assert np.array_equal(rec.cpu().numpy().view(np.uint8).reshape(T, K // 32, 32)[:, :, :24], want)
+    assert np.array_equal(sd.cpu().numpy(), s4) and np.array_equal(cs.cpu().numpy(), c4.astype(np.int32).sum(1))
+    c, sd, cs = hbl.ln_fwht_quant(xd, gd, 1e-6, 4, True, EPS, code_offset=8)
+    assert np.array_equal(c.cpu().numpy().astype(np.int32) - 8, c4.astype(np.int32))
+    assert np.array_equal(sd.cpu().numpy(), s4) and np.array_equal(cs.cpu().numpy(), c4.astype(np.int32).sum(1))
+
+
 def ln_gain_for(K, seed):
     """RMS-norm gains around 1 with a few large channels (the gains are where trained models park outliers)."""
     rng = np.random.default_rng(seed)
