@@ -29,6 +29,12 @@
  *   - Eq. 8 (backward through the transform) is the same transform applied
  *     to the gradient rows, in the same fp32 butterfly order.
  *   - X is a row vector per token, W is [N out x K in]: Y[T x N] = Xq * Wq^T.
+ *   - low-bit Q/K/V head states (Section 3.2, low-bit attention): the paper says
+ *     only that the post-RoPE head states are quantised "to unsigned integers
+ *     using the absmax function".  Taken here as Eq. 5 at b bits per head row,
+ *     stored with an offset: u = RoundClip(qmax/(gamma+eps) * h, -2^(b-1),
+ *     2^(b-1)-1) + 2^(b-1), qmax = 2^(b-1)-1, dequantised (u - 2^(b-1)) *
+ *     gamma/qmax.  At b = 8 this is Eq. 5 itself plus 128.
  *
  * Pins (tests/test_oracle_*.py): H*H^T = I and the popcount closed form for
  * hblo_hadamard_dense; dense H*x (n <= 64), exact integer inputs at full n,
@@ -40,7 +46,10 @@
  * integers, the gradient of a linear functional through the dense matrix
  * (n <= 64) and an independent bf16 rounding; for hblo_rmsnorm hand cases
  * with power-of-two factors, unit mean square, scale invariance, the
- * placement of ln_eps and an fp64 reference.
+ * placement of ln_eps and an fp64 reference; for hblo_kv_quant_absmax
+ * equality with the pinned Eq. 5 quantiser at 8 bits, hand rows at 4 and 3
+ * bits, the half-step reconstruction bound, code range and extremes, and a
+ * bit-by-bit unpacking of the packed stream written out in the test.
  */
 #include <math.h>
 #include <stdint.h>
@@ -359,4 +368,74 @@ int hblo_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, con
     if (!sdeq_out) free(sdeq);
     if (!acc_out) free(acc);
     return rc;
+}
+
+/* ------------------------------------------------------------------------
+ * Low-bit Q/K/V head states (Section 3.2, "low-bit attention"; reading in the
+ * header).  One row = one head of one token after RoPE, d values.
+ *   gamma = max|h|,  qmax = 2^(b-1) - 1,  s_q = qmax / (gamma + eps)  (fp32 division)
+ *   u[i]  = RoundClip(s_q * h[i], -2^(b-1), qmax) + 2^(b-1)           in [0, 2^b - 1]
+ *   scale = gamma / qmax                                             (fp32 division)
+ *   x      [rows, d] fp32 or bf16 bit patterns
+ *   codes  [rows, d] unsigned codes, one per byte (unpacked)
+ *   packed [rows, d*bits/8] or NULL: code i of a row at bits [bits*i, bits*i + bits) of the row's
+ *          little-endian bit string (8 bits: bytes; 4 bits: low nibble first; 3 bits: 8 codes in 3 bytes)
+ *   scales [rows] fp32
+ * bits is 8, 4 or 3; d must make d*bits a multiple of 8.
+ * ---------------------------------------------------------------------- */
+int hblo_kv_quant_absmax(const void* x, int x_dtype, int64_t rows, int64_t d, int bits, float eps,
+                         uint8_t* codes, uint8_t* packed, float* scales) {
+    if (!x || !codes || !scales || rows < 0 || d <= 0) return HBLO_E_ARG;
+    if (x_dtype != HBLO_F32 && x_dtype != HBLO_BF16) return HBLO_E_ARG;
+    if (bits != 8 && bits != 4 && bits != 3) return HBLO_E_ARG;
+    if ((d * bits) % 8 != 0) return HBLO_E_ARG;
+    const int half = 1 << (bits - 1);
+    const float qmax = (float)(half - 1);
+    const int64_t row_bytes = d * bits / 8;
+#pragma omp parallel
+    {
+        float* h = (float*)malloc((size_t)d * sizeof(float));
+#pragma omp for schedule(static)
+        for (int64_t r = 0; r < rows; ++r) {
+            load_row_f32(x, x_dtype, r, d, h);
+            float gamma = 0.0f;
+            for (int64_t i = 0; i < d; ++i) {
+                const float a = fabsf(h[i]);
+                if (a > gamma) gamma = a;
+            }
+            const float s_q = qmax / (gamma + eps);
+            scales[r] = gamma / qmax;
+            for (int64_t i = 0; i < d; ++i)
+                codes[r * d + i] = (uint8_t)((int)round_clip(s_q * h[i], -(float)half, qmax) + half);
+            if (packed) {
+                uint8_t* out = packed + r * row_bytes;
+                memset(out, 0, (size_t)row_bytes);
+                for (int64_t i = 0; i < d; ++i)
+                    for (int b = 0; b < bits; ++b) {
+                        const int64_t pos = i * bits + b;
+                        if ((codes[r * d + i] >> b) & 1) out[pos >> 3] |= (uint8_t)(1u << (pos & 7));
+                    }
+            }
+        }
+        free(h);
+    }
+    return HBLO_OK;
+}
+
+/* Inverse map of the above: h^[i] = ((float)u[i] - 2^(b-1)) * scale, as fp32 (out_dtype F32) or rounded to
+ * nearest even to bf16.  codes are the unpacked unsigned codes. */
+int hblo_kv_dequant(const uint8_t* codes, const float* scales, int64_t rows, int64_t d, int bits, void* out,
+                    int out_dtype) {
+    if (!codes || !scales || !out || rows < 0 || d <= 0) return HBLO_E_ARG;
+    if (bits != 8 && bits != 4 && bits != 3) return HBLO_E_ARG;
+    if (out_dtype != HBLO_F32 && out_dtype != HBLO_BF16) return HBLO_E_ARG;
+    const float half = (float)(1 << (bits - 1));
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t i = 0; i < d; ++i) {
+            const float v = ((float)codes[r * d + i] - half) * scales[r];
+            if (out_dtype == HBLO_F32) ((float*)out)[r * d + i] = v;
+            else ((uint16_t*)out)[r * d + i] = f32_to_bf16_rne(v);
+        }
+    return HBLO_OK;
 }

@@ -53,6 +53,8 @@ def lib():
         _lib.hblo_fwht_quant.argtypes = [vp, ci, i64, i64, ci, f32, ci, vp, vp, vp]
         _lib.hblo_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp]
         _lib.hblo_dequant_bf16.argtypes = [vp, i64, i64, vp, vp, i64, vp]
+        _lib.hblo_kv_quant_absmax.argtypes = [vp, ci, i64, i64, ci, f32, vp, vp, vp]
+        _lib.hblo_kv_dequant.argtypes = [vp, vp, i64, i64, ci, vp, ci]
         _lib.hblo_bitlinear_forward.argtypes = [vp, ci, i64, i64, vp, i64, vp, i64, ci, f32, ci, vp, vp, vp, vp]
     return _lib
 
@@ -189,3 +191,26 @@ def hbitlinear_forward(x, wcodes, w_scales, bits, eps: float = EPS, **kw):
 
 def plain_bitlinear_forward(x, wcodes, w_scales, bits, eps: float = EPS, **kw):
     return bitlinear_forward(x, wcodes, w_scales, bits, False, eps, **kw)
+
+
+def kv_quant_absmax(x: np.ndarray, bits: int, eps: float = EPS):
+    """Low-bit head states (Section 3.2): x [rows, d] fp32 or bf16 bits -> (unsigned codes [rows, d] uint8,
+    packed [rows, d*bits/8] uint8, scales [rows] fp32)."""
+    x = np.ascontiguousarray(x)
+    rows, d = x.shape
+    codes = np.empty((rows, d), np.uint8)
+    packed = np.empty((rows, d * bits // 8), np.uint8)
+    scales = np.empty(rows, np.float32)
+    _check(lib().hblo_kv_quant_absmax(_p(x), _x_dtype(x), rows, d, bits, eps, _p(codes), _p(packed), _p(scales)),
+           "kv_quant_absmax")
+    return codes, packed, scales
+
+
+def kv_dequant(codes: np.ndarray, scales: np.ndarray, bits: int, out_bf16: bool = False) -> np.ndarray:
+    """(u - 2^(bits-1)) * scale per row, fp32 or bf16 bit patterns."""
+    codes = np.ascontiguousarray(codes, np.uint8)
+    scales = np.ascontiguousarray(scales, np.float32)
+    rows, d = codes.shape
+    out = np.empty((rows, d), np.uint16 if out_bf16 else np.float32)
+    _check(lib().hblo_kv_dequant(_p(codes), _p(scales), rows, d, bits, _p(out), 1 if out_bf16 else 0), "kv_dequant")
+    return out

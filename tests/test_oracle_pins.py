@@ -432,3 +432,59 @@ def test_rotating_weights_and_activations_cancels():
     got = O.fwht_rows(x).astype(np.float64) @ O.fwht_rows(W).astype(np.float64).T
     want = x.astype(np.float64) @ W.astype(np.float64).T
     assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+
+
+# --- Low-bit Q/K/V head states (Section 3.2) ----------------------------------------------------------
+
+def test_kv_absmax_hand_row(golden):
+    c = golden["kv_absmax_hand_row"]
+    x = np.array([c["x"]], np.float32)
+    for bits in (4, 3):
+        codes, packed, scales = O.kv_quant_absmax(x, bits, c["eps"][0])
+        assert codes[0].tolist() == [int(v) for v in c[f"codes{bits}"]]
+        assert packed[0].tolist() == [int(v) for v in c[f"packed{bits}"]]
+        assert scales[0] == np.float32(c[f"scale{bits}"][0])
+
+
+def test_kv_absmax_is_eq5_plus_128_at_8_bits():
+    """At 8 bits the head-state quantiser must be the (separately pinned) INT8 absmax quantiser of Eq. 5 with an
+    offset of 128, row for row, for both input types."""
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((37, 128)) * np.exp(rng.standard_normal((37, 1)))).astype(np.float32)
+    x[3] = 0.0                                               # a zero row: codes 128, scale 0
+    for xx in (x, synth.f32_to_bf16_bits(x)):
+        q, s = O.fwht_quant(xx, 8, hadamard=False, eps=1e-5)
+        codes, packed, scales = O.kv_quant_absmax(xx, 8, 1e-5)
+        assert np.array_equal(codes.astype(np.int32) - 128, q.astype(np.int32))
+        assert np.array_equal(packed, codes) and np.array_equal(scales, s)
+    assert np.all(codes[3] == 128) and scales[3] == 0.0
+
+
+@pytest.mark.parametrize("bits", [8, 4, 3])
+def test_kv_absmax_invariants(bits):
+    rng = np.random.default_rng(bits)
+    rows, d = 64, 128
+    x = (rng.standard_normal((rows, d)) * 3.0).astype(np.float32)
+    x[:, 5] *= 20.0                                          # an outlier channel, as in K states
+    half, qmax = 1 << (bits - 1), (1 << (bits - 1)) - 1
+    codes, packed, scales = O.kv_quant_absmax(x, bits, 1e-5)
+    assert codes.min() >= 0 and codes.max() <= 2 * half - 1
+    # the row maximum maps to +-qmax exactly, and -2^(b-1) is never produced (|qmax h/(gamma+eps)| <= qmax)
+    amax = np.abs(x).argmax(1)
+    top = codes[np.arange(rows), amax].astype(np.int32) - half
+    assert np.array_equal(top, np.sign(x[np.arange(rows), amax]).astype(np.int32) * qmax)
+    assert codes.min() >= 1
+    # reconstruction: within half a step of the scale (plus the eps shrink and fp32 rounding)
+    xhat = O.kv_dequant(codes, scales, bits)
+    assert np.all(np.abs(xhat - x) <= scales[:, None] * (0.5 + 1e-3))
+    assert np.allclose(scales, np.abs(x).max(1) / qmax, rtol=1e-6)
+    # scaling a row by a power of two scales the scale and leaves the codes alone (eps = 0)
+    c1, _, s1 = O.kv_quant_absmax(x, bits, 0.0)
+    c2, _, s2 = O.kv_quant_absmax(x * 4.0, bits, 0.0)
+    assert np.array_equal(c1, c2) and np.array_equal(s2, s1 * 4.0)
+    # the packed stream, unpacked bit by bit here
+    bitsarr = np.unpackbits(packed, axis=1, bitorder="little").reshape(rows, d, bits)
+    back = (bitsarr * (1 << np.arange(bits))).sum(2)
+    assert np.array_equal(back, codes)
+    # bf16 output of the inverse map: the fp32 result rounded to nearest even
+    assert np.array_equal(O.kv_dequant(codes, scales, bits, out_bf16=True), synth.f32_to_bf16_bits(xhat))
