@@ -328,6 +328,40 @@ def measured_traffic(site_name, int8_path):
     return None
 
 
+def bench_kv_quant(hbl, torch):
+    """Per-head absmax quantiser of the attention states (Section 3.2) on the K (or V) states of the 7B prefill
+    batch: 8192 tokens x 32 heads of 128, bf16 in, packed codes + one fp32 scale per head out.  HBM-bound:
+    algorithmic bytes = 2 per value in, bits/8 per value + 4 per row out."""
+    rows, d, nbuf = 8192 * 32, 128, 6   # six distinct 67 MB inputs: more than the 256 MB memory-side cache holds
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    xs = [torch.randn((rows, d), device="cuda", generator=g).to(torch.bfloat16) for _ in range(nbuf)]
+    backs = [torch.empty_like(x) for x in xs]
+    out = {"workload": f"{rows} head rows of {d} (8192 tokens x 32 heads), bf16, {nbuf} buffers in rotation"}
+    for bits in (8, 4, 3):
+        ps = [hbl.kv_quant_absmax(x, bits) for x in xs]
+        res = {}
+        for name, fn, nbytes in (
+                ("quant", lambda i: hbl.kv_quant_absmax(xs[i], bits, packed=ps[i][0], scales=ps[i][1]),
+                 rows * d * 2 + rows * d * bits // 8 + rows * 4),
+                ("dequant", lambda i: hbl.kv_dequant(ps[i][0], ps[i][1], d, bits, out=backs[i]),
+                 rows * d * bits // 8 + rows * 4 + rows * d * 2)):
+            for i in range(nbuf):
+                fn(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 4 * nbuf
+            e0.record()
+            for r in range(reps):
+                fn(r % nbuf)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            res[name] = {"us": us, "GBps": nbytes / us / 1e3, "frac_hbm_peak": nbytes / us / 1e3 / 8000.0}
+        out[str(bits)] = res
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -376,6 +410,7 @@ def main():
         result["prefill_layer_7b"] = bench_prefill_layer(args, hbl, synth, torch, np)
         torch.cuda.empty_cache()
         result["decode"] = bench_decode(args, hbl, synth, torch, np)
+        result["kv_quant"] = bench_kv_quant(hbl, torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(site, x_host, W_host, synth, np)
     print(json.dumps(result))

@@ -252,6 +252,31 @@ int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_d
                           const int32_t* code_sum, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
                           const float* w_scales, int64_t n_scale_groups, void* y, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Low-bit attention states (Section 3.2: 8-, 4- and 3-bit Q/K/V heads and KV cache).
+ * The head states after RoPE are quantised per head row "to unsigned integers using the absmax
+ * function"; the paper prints no formula, and this library takes Eq. 5 at b bits with an offset:
+ *   gamma = max|h|, qmax = 2^(b-1) - 1,
+ *   u[i] = RoundClip(qmax/(gamma+eps) * h[i], -2^(b-1), qmax) + 2^(b-1)  in [0, 2^b - 1],
+ *   scale = gamma / qmax,  h^[i] = (u[i] - 2^(b-1)) * scale
+ * (round half to even; at b = 8 this is Eq. 5 plus 128).  The [BOS] token's K/V rows, which the
+ * paper keeps at 8 bits, are the caller's to route: quantise them in a call of their own with bits = 8.
+ *   x       [rows, d] device, x_dtype; one row = one head of one token; d in {32, 64, 128, 256, 512}
+ *   bits    8, 4 or 3
+ *   packed  device, hbl_kv_packed_bytes(rows, d, bits) = rows*d*bits/8 bytes, 16-byte aligned: one
+ *           little-endian bit string, row r from byte r*d*bits/8, code i of a row at bits
+ *           [bits*i, bits*i + bits) of its row (bytes; low nibble first; 8 codes per 3 bytes)
+ *   scales  [rows] fp32 device
+ * Errors as above (HBL_E_SHAPE for another d, HBL_E_BITS, HBL_E_DTYPE, HBL_E_NULL, HBL_E_ALIGN);
+ * rows = 0 is a no-op.  Nothing is allocated; the calls enqueue on `stream` and return.
+ */
+size_t hbl_kv_packed_bytes(int64_t rows, int64_t d, int bits);
+int hbl_kv_quant_absmax(const void* x, int x_dtype, int64_t rows, int64_t d, int bits, float eps,
+                        void* packed, float* scales, void* stream);
+/* The inverse map: out [rows, d] out_dtype (HBL_F32, or HBL_BF16 rounded to nearest even), 16-byte aligned. */
+int hbl_kv_dequant(const void* packed, const float* scales, int64_t rows, int64_t d, int bits,
+                   void* out, int out_dtype, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

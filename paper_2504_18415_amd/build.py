@@ -13,7 +13,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhbitlinear.so")
-SOURCES = ["api.hip", "fwht_quant.hip", "ternary_setup.hip", "ternary_gemm.hip", "ternary_gemm_f6f4.hip", "decode_gemm.hip"]
+SOURCES = ["api.hip", "fwht_quant.hip", "ternary_setup.hip", "ternary_gemm.hip", "ternary_gemm_f6f4.hip", "decode_gemm.hip",
+           "kv_quant.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

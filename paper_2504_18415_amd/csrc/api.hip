@@ -341,6 +341,33 @@ int hbl_fwht(const void* x, int x_dtype, int64_t T, int64_t K, void* out, int ou
     return launch_fwht_only(x, x_dtype, T, K, out, out_dtype, static_cast<hipStream_t>(stream));
 }
 
+size_t hbl_kv_packed_bytes(int64_t rows, int64_t d, int bits) {
+    if (!kv_shape_ok(rows, d, bits)) return 0;
+    return (size_t)rows * (size_t)d * (size_t)bits / 8;
+}
+
+int hbl_kv_quant_absmax(const void* x, int x_dtype, int64_t rows, int64_t d, int bits, float eps, void* packed,
+                        float* scales, void* stream) {
+    if (bits != 8 && bits != 4 && bits != 3) return HBL_E_BITS;
+    if (x_dtype != HBL_F32 && x_dtype != HBL_BF16) return HBL_E_DTYPE;
+    if (!kv_shape_ok(rows, d, bits)) return HBL_E_SHAPE;
+    if (rows == 0) return HBL_OK;
+    if (!x || !packed || !scales) return HBL_E_NULL;
+    if (!aligned16(x) || !aligned16(packed)) return HBL_E_ALIGN;
+    return launch_kv_quant(x, x_dtype, rows, d, bits, eps, packed, scales, static_cast<hipStream_t>(stream));
+}
+
+int hbl_kv_dequant(const void* packed, const float* scales, int64_t rows, int64_t d, int bits, void* out,
+                   int out_dtype, void* stream) {
+    if (bits != 8 && bits != 4 && bits != 3) return HBL_E_BITS;
+    if (out_dtype != HBL_F32 && out_dtype != HBL_BF16) return HBL_E_DTYPE;
+    if (!kv_shape_ok(rows, d, bits)) return HBL_E_SHAPE;
+    if (rows == 0) return HBL_OK;
+    if (!packed || !scales || !out) return HBL_E_NULL;
+    if (!aligned16(packed) || !aligned16(out)) return HBL_E_ALIGN;
+    return launch_kv_dequant(packed, scales, rows, d, bits, out, out_dtype, static_cast<hipStream_t>(stream));
+}
+
 int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packed, int64_t N, int32_t* acc,
                  void* stream) {
     int rc = check_gemm_shape(T, K, N, false);

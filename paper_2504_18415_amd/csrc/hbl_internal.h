@@ -116,6 +116,12 @@ int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits
                       const float* ln_gain = nullptr, float ln_eps = 0.0f);
 
 // Transform only: out[t] = Hadamard(x[t]) as fp32 or bf16 (K a power of two, 128..16384).
+// Low-bit head states (kv_quant.hip)
+bool kv_shape_ok(int64_t rows, int64_t d, int bits);
+int launch_kv_quant(const void* x, int x_dtype, int64_t rows, int64_t d, int bits, float eps, void* packed,
+                    float* scales, hipStream_t stream);
+int launch_kv_dequant(const void* packed, const float* scales, int64_t rows, int64_t d, int bits, void* out,
+                      int out_dtype, hipStream_t stream);
 int launch_fwht_only(const void* x, int x_dtype, int64_t T, int64_t K, void* out, int out_dtype, hipStream_t stream);
 
 // GEMM + epilogue. If acc_out != nullptr the raw int32 accumulators are written

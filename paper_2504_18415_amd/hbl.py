@@ -31,6 +31,7 @@ EXPORTS = [
     "hbl_hbitlinear_forward", "hbl_plain_bitlinear_forward", "hbl_fwht_quant", "hbl_gemm_i32",
     "hbl_gemm_dequant_bf16", "hbl_grouped_workspace_bytes", "hbl_bitlinear_forward_grouped", "hbl_fwht",
     "hbl_ln_bitlinear_forward", "hbl_ln_fwht_quant", "hbl_debug_grouped_plan",
+    "hbl_kv_packed_bytes", "hbl_kv_quant_absmax", "hbl_kv_dequant",
 ]
 
 _lib = None
@@ -83,6 +84,10 @@ def lib():
         L.hbl_gemm_i32.argtypes = [vp, i64, i64, vp, i64, vp, vp]
         L.hbl_gemm_dequant_bf16.argtypes = [vp, ci, vp, vp, i64, i64, vp, i64, vp, i64, vp, vp]
         L.hbl_fwht.argtypes = [vp, ci, i64, i64, vp, ci, vp]
+        L.hbl_kv_packed_bytes.argtypes = [i64, i64, ci]
+        L.hbl_kv_packed_bytes.restype = ctypes.c_size_t
+        L.hbl_kv_quant_absmax.argtypes = [vp, ci, i64, i64, ci, ctypes.c_float, vp, vp, vp]
+        L.hbl_kv_dequant.argtypes = [vp, vp, i64, i64, ci, vp, ci, vp]
         ip = ctypes.POINTER(ci)
         L.hbl_debug_grouped_plan.argtypes = [ctypes.POINTER(Problem), ci, ip, ip, ip, ip]
         L.hbl_ln_bitlinear_forward.argtypes = [vp, ci, i64, i64, vp, f32, ci, vp, i64, vp, i64, ci, f32, vp, vp, sz, vp]
@@ -317,3 +322,30 @@ def grouped_plan(shapes):
     wgs, red = ctypes.c_int(0), ctypes.c_int(0)
     _check(lib().hbl_debug_grouped_plan(arr, n, ks, ctypes.byref(wgs), ctypes.byref(red), st), "grouped_plan")
     return list(ks), wgs.value, red.value, [bool(v) for v in st]
+
+
+def kv_quant_absmax(x: torch.Tensor, bits: int, eps: float = EPS, packed: Optional[torch.Tensor] = None,
+                    scales: Optional[torch.Tensor] = None):
+    """Low-bit head states (Section 3.2): x [rows, d] -> (packed uint8 [rows, d*bits/8], scales fp32 [rows])."""
+    _dev_check(x)
+    rows, d = x.shape
+    nbytes = lib().hbl_kv_packed_bytes(rows, d, bits)
+    if packed is None:
+        packed = torch.empty((rows, d * bits // 8) if nbytes or rows == 0 else (0,), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty(rows, dtype=torch.float32, device=x.device)
+    _check(lib().hbl_kv_quant_absmax(_ptr(x), _x_dtype(x), rows, d, bits, eps, _ptr(packed), _ptr(scales), _stream()),
+           "kv_quant_absmax")
+    return packed, scales
+
+
+def kv_dequant(packed: torch.Tensor, scales: torch.Tensor, d: int, bits: int, out_dtype=torch.bfloat16,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Inverse map of :func:`kv_quant_absmax`: -> [rows, d] bf16 or fp32."""
+    _dev_check(packed, scales)
+    rows = scales.shape[0]
+    if out is None:
+        out = torch.empty((rows, d), dtype=out_dtype, device=packed.device)
+    _check(lib().hbl_kv_dequant(_ptr(packed), _ptr(scales), rows, d, bits, _ptr(out),
+                                BF16 if out.dtype == torch.bfloat16 else F32, _stream()), "kv_dequant")
+    return out

@@ -170,3 +170,28 @@ def test_small_batch_launch_plan(L):
         hbl.grouped_plan([(65, 4096, 4096, True)])
     with pytest.raises(hbl.HblError):
         hbl.grouped_plan([(4, 4096 + 128, 4096, True)])
+
+
+def test_kv_quant_argument_errors_before_any_launch(L):
+    from paper_2504_18415_amd import hbl
+    E = {n: getattr(hbl, n) for n in ("E_NULL", "E_SHAPE", "E_BITS", "E_DTYPE", "E_ALIGN")}
+    assert L.hbl_kv_packed_bytes(10, 128, 8) == 1280 and L.hbl_kv_packed_bytes(10, 128, 4) == 640
+    assert L.hbl_kv_packed_bytes(10, 128, 3) == 480 and L.hbl_kv_packed_bytes(10, 96, 4) == 0
+    assert L.hbl_kv_packed_bytes(10, 128, 5) == 0
+    a = 4096   # a non-null, 16-byte aligned stand-in address: every call below must fail before touching it
+    q = lambda x, dt, rows, d, bits, p, s: L.hbl_kv_quant_absmax(x, dt, rows, d, bits, 1e-5, p, s, None)
+    assert q(a, hbl.BF16, 4, 128, 5, a, a) == E["E_BITS"]
+    assert q(a, 7, 4, 128, 4, a, a) == E["E_DTYPE"]
+    assert q(a, hbl.BF16, 4, 96, 4, a, a) == E["E_SHAPE"]
+    assert q(a, hbl.BF16, -1, 128, 4, a, a) == E["E_SHAPE"]
+    assert q(None, hbl.BF16, 4, 128, 4, a, a) == E["E_NULL"]
+    assert q(a, hbl.BF16, 4, 128, 4, a, None) == E["E_NULL"]
+    assert q(a + 4, hbl.BF16, 4, 128, 4, a, a) == E["E_ALIGN"]
+    assert q(None, hbl.BF16, 0, 128, 4, None, None) == 0                      # no rows: nothing to do
+    dq = lambda p, s, rows, d, bits, o, dt: L.hbl_kv_dequant(p, s, rows, d, bits, o, dt, None)
+    assert dq(a, a, 4, 128, 2, a, hbl.BF16) == E["E_BITS"]
+    assert dq(a, a, 4, 128, 3, a, 9) == E["E_DTYPE"]
+    assert dq(a, a, 4, 1024, 3, a, hbl.F32) == E["E_SHAPE"]
+    assert dq(a, None, 4, 128, 3, a, hbl.F32) == E["E_NULL"]
+    assert dq(a, a, 4, 128, 3, a + 8, hbl.F32) == E["E_ALIGN"]
+    assert dq(None, None, 0, 128, 3, None, hbl.F32) == 0

@@ -822,3 +822,45 @@ def test_offsets_beyond_two_to_the_31(hbl):
         del y
     del x
     torch.cuda.empty_cache()
+
+
+# --- low-bit Q/K/V head states (Section 3.2) -----------------------------------------------------------
+
+@pytest.mark.parametrize("bits", [8, 4, 3])
+@pytest.mark.parametrize("d,rows,dtype", [(128, 4100, synth.BF16), (64, 333, synth.BF16), (256, 77, synth.F32),
+                                          (32, 1030, synth.F32), (512, 65, synth.BF16)])
+def test_kv_quant_absmax_parity(hbl, bits, d, rows, dtype):
+    """Per-head absmax quantiser of the attention states: the packed stream and the scales bit for bit against
+    the oracle, then the inverse map in both output types; row counts that leave a ragged last workgroup."""
+    note(f"kv quant bits={bits} d={d} rows={rows} {dtype}")
+    rng = np.random.default_rng(1000 * bits + d + rows)
+    x = rng.standard_normal((rows, d)).astype(np.float32) * np.exp(rng.standard_normal((rows, 1))).astype(np.float32)
+    x[:, d // 3] *= 15.0                      # an outlier channel, as key states have
+    x[rows // 2] = 0.0                        # an all-zero head
+    xh = synth.f32_to_bf16_bits(x) if dtype == synth.BF16 else x
+    codes, packed_ref, s_ref = O.kv_quant_absmax(xh, bits, EPS)
+    packed, scales = hbl.kv_quant_absmax(dev_x(xh), bits, EPS)
+    assert packed.shape == (rows, d * bits // 8)
+    assert np.array_equal(packed.cpu().numpy(), packed_ref)
+    assert np.array_equal(scales.cpu().numpy(), s_ref)
+    out32 = hbl.kv_dequant(packed, scales, d, bits, out_dtype=torch.float32)
+    assert np.array_equal(out32.cpu().numpy(), O.kv_dequant(codes, s_ref, bits))
+    out16 = hbl.kv_dequant(packed, scales, d, bits, out_dtype=torch.bfloat16)
+    assert np.array_equal(host_bf16_bits(out16), O.kv_dequant(codes, s_ref, bits, out_bf16=True))
+
+
+def test_kv_quant_errors_and_empty(hbl):
+    note("kv quant errors")
+    x = torch.zeros((4, 96), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(hbl.HblError):
+        hbl.kv_quant_absmax(x, 4)                                   # head size not supported
+    x = torch.zeros((4, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(hbl.HblError):
+        hbl.kv_quant_absmax(x, 5)
+    p, s = hbl.kv_quant_absmax(x[:0], 4)
+    assert p.shape[0] == 0 and s.shape[0] == 0
+    p, s = hbl.kv_quant_absmax(x, 3)                                # zero rows of data: every code is the offset
+    torch.cuda.synchronize()
+    assert np.array_equal(np.unpackbits(p.cpu().numpy(), axis=1, bitorder="little").reshape(4, 128, 3),
+                          np.broadcast_to(np.array([0, 0, 1], np.uint8), (4, 128, 3)))
+    assert np.all(s.cpu().numpy() == 0.0)
