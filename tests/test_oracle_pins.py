@@ -446,6 +446,15 @@ def test_kv_absmax_hand_row(golden):
         assert scales[0] == np.float32(c[f"scale{bits}"][0])
 
 
+def test_kv_absmax_ties_go_to_even(golden):
+    c = golden["kv_absmax_ties"]
+    for bits in (4, 3):
+        x = np.array([c[f"x{bits}"]], np.float32)
+        codes, _, scales = O.kv_quant_absmax(x, bits, c["eps"][0])
+        assert codes[0].tolist() == [int(v) for v in c[f"codes{bits}"]]
+        assert scales[0] == 1.0
+
+
 def test_kv_absmax_is_eq5_plus_128_at_8_bits():
     """At 8 bits the head-state quantiser must be the (separately pinned) INT8 absmax quantiser of Eq. 5 with an
     offset of 128, row for row, for both input types."""
