@@ -1,5 +1,5 @@
 // Stand-alone micro-benchmarks of what one MI355X sustains, used to put the library's kernels in
-// context (the design doc quotes the figures): matrix-core rate with register-resident operands for the
+// context: matrix-core rate with register-resident operands for the
 // two MFMA forms the GEMM kernels use, by operand bit pattern, and HBM read / copy bandwidth.
 // Build and run:  python -m paper_2504_18415_amd.microbench
 #include <hip/hip_runtime.h>

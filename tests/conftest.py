@@ -9,7 +9,7 @@ if ROOT not in sys.path:
 
 
 def pytest_configure(config):
-    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu under gpurun)")
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on a GPU box)")
 
 
 def load_golden(name):

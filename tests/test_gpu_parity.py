@@ -23,6 +23,7 @@ pytestmark = pytest.mark.gpu
 EPS = 1e-5
 
 
+# a scratch folder beside the tests, if the run provides one: the case names are kept there as well
 _CASE_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
 
 
