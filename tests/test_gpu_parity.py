@@ -23,16 +23,9 @@ pytestmark = pytest.mark.gpu
 EPS = 1e-5
 
 
-# a scratch folder beside the tests, if the run provides one: the case names are kept there as well
-_CASE_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-
-
 def note(msg):
     """Name the case before each GPU step (survives a lost box: flushed line by line)."""
     print(f"[gpu-case] {msg}", flush=True)
-    if os.path.isdir(_CASE_LOG):
-        with open(os.path.join(_CASE_LOG, "gpu_cases.log"), "a") as fh:
-            fh.write(msg + "\n")
 
 
 @pytest.fixture(scope="module")
