@@ -7,8 +7,6 @@ Bars (from the benchmark spec):
     rel = |y - y_ref| / max(|y_ref|, 1e-3 * rms(y_ref row)).
 """
 import math
-import os
-import sys
 
 import numpy as np
 import pytest
