@@ -325,18 +325,23 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
     a.N = (int)N;
     a.rows_per_group = n_scale_groups > 0 ? (int)(N / n_scale_groups) : (int)N;
     a.split_k = 1;
-    const int64_t big_tiles = (int64_t)((N + 255) / 256) * ((T + 255) / 256);
+    // Workgroup tile: 64 K outputs either way (the 256 accumulator registers of four waves).  512 features x 128
+    // tokens moves 32 KB per 128-feature stage through L2 and LDS (16 KB of codes + 16 KB of packed weights) against
+    // 40 KB for 256 x 256 (32 + 8): measured 4 % faster on the GEMM at N = 4096 and 12288, equal at N = 32768.  The
+    // square tile stays for shapes the wide one pads more; below ~180 tiles (256 CUs) the small tile takes over
+    // (192 big tiles measured 8 % faster than 768 tiles of 128 x 128).
+    const int64_t tiles_sq = (int64_t)((N + 255) / 256) * ((T + 255) / 256);
+    const int64_t tiles_wide = (int64_t)((N + 511) / 512) * ((T + 127) / 128);
     static const int override_tile = [] {
         const char* e = getenv("HBL_GEMM_F6F4_TILE");
         return e ? atoi(e) : -1;
     }();
-    // 256 x 256 tiles once they give most CUs a workgroup (192 tiles on 256 CUs measured 8 % faster than 768
-    // tiles of 128 x 128), the small tile below that
-    int cfg = big_tiles >= 180 ? 0 : 1;
+    int cfg = tiles_sq >= 180 ? (tiles_wide <= tiles_sq ? 2 : 0) : 1;
     if (override_tile >= 0) cfg = override_tile;
     switch (cfg) {
-        case 0: return launch_cfg<2, 2, 4, 4, 3>(a, stream);   // 256 x 256, 4 waves of 128 x 128
+        case 0: return launch_cfg<2, 2, 4, 4, 3>(a, stream);   // 256 x 256, 2 x 2 waves of 128 x 128
         case 1: return launch_cfg<2, 2, 2, 2, 4>(a, stream);   // 128 x 128
+        case 2: return launch_cfg<4, 1, 4, 4, 3>(a, stream);   // 512 features x 128 tokens, 4 x 1 waves of 128 x 128
         default: return HBL_E_SHAPE;
     }
 }
