@@ -33,6 +33,14 @@ __device__ __forceinline__ void lds_dma16(uint32_t lds_addr, const void* base, u
                  : "memory", "m0");
 }
 
+// Output rows leave with the non-temporal hint: y is written once and never read by the kernel, and keeping it
+// out of the way of the operand panels in L2 measured 3.5 % faster at N = 32768 (537 MB of output), 3 % at
+// N = K = 4096, and no different at N = 12288 and on W_down.
+__device__ __forceinline__ void store_y16(uint16_t* dst, uint4 val) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    __builtin_nontemporal_store((u32x4){val.x, val.y, val.z, val.w}, reinterpret_cast<u32x4*>(dst));
+}
+
 struct GemmArgs {
     const int8_t* codes;      // [T, K]
     const uint32_t* packed;   // tiles [N/32][K/128][64 lanes][4 dwords]

@@ -288,7 +288,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
             const uint4 val = *reinterpret_cast<const uint4*>(obuf + row * ROWB + c * 16);
             const int t = t0 + (wt * TT + jg + row / 32) * 32 + (row & 31);
             const int n = n0 + wn * TN * 32 + c * 8;
-            if (t < a.T && n < a.N) *reinterpret_cast<uint4*>(a.y + (size_t)t * a.N + n) = val;
+            if (t < a.T && n < a.N) store_y16(a.y + (size_t)t * a.N + n, val);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
