@@ -323,8 +323,10 @@ def measured_traffic(site_name, int8_path):
     profiles/hbm_traffic_counters.txt (FETCH_SIZE scaled by the copy-kernel factor 2.000, WRITE_SIZE by
     1.000).  Only the workload those passes covered has a figure; counters cannot be read from inside
     this process."""
-    if site_name == "wdown_7b" and not int8_path:
-        return int(196824 * 2.000 * 1024 + 65536 * 1.000 * 1024)
+    if site_name == "wdown_7b":
+        if not int8_path:
+            return int(196774 * 2.000 * 1024 + 65556 * 1.000 * 1024)
+        return int(196880 * 2.000 * 1024 + 65550 * 1.000 * 1024)
     return None
 
 
