@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void kv_dequant_kernel(const uint8_t* __restri
 }  // namespace
 
 bool kv_shape_ok(int64_t rows, int64_t d, int bits) {
-    if (rows < 0 || (bits != 8 && bits != 4 && bits != 3)) return false;
+    if (rows < 0 || rows > 0x7FFFFFFF || (bits != 8 && bits != 4 && bits != 3)) return false;   // grid fits 32 bits
     return d == 32 || d == 64 || d == 128 || d == 256 || d == 512;   // d/8 lanes per row, a power of two in 4..64
 }
 

@@ -184,6 +184,7 @@ def test_kv_quant_argument_errors_before_any_launch(L):
     assert q(a, 7, 4, 128, 4, a, a) == E["E_DTYPE"]
     assert q(a, hbl.BF16, 4, 96, 4, a, a) == E["E_SHAPE"]
     assert q(a, hbl.BF16, -1, 128, 4, a, a) == E["E_SHAPE"]
+    assert q(a, hbl.BF16, 1 << 31, 128, 4, a, a) == E["E_SHAPE"]
     assert q(None, hbl.BF16, 4, 128, 4, a, a) == E["E_NULL"]
     assert q(a, hbl.BF16, 4, 128, 4, a, None) == E["E_NULL"]
     assert q(a + 4, hbl.BF16, 4, 128, 4, a, a) == E["E_ALIGN"]
