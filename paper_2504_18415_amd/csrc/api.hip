@@ -84,7 +84,7 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
         rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, kCodesBf6, s,
                                ln_gain, ln_eps);
         if (rc != HBL_OK) return rc;
-        return launch_ternary_gemm_f6f4(ws.codes, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, s);
+        return launch_ternary_gemm_f6f4(ws.codes, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, s, ws.partial);
     }
     // otherwise INT4 codes travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs
     const int code_offset = bits == 4 ? 8 : 0;

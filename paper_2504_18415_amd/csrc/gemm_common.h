@@ -60,6 +60,10 @@ struct GemmArgs {
     int32_t* partial;
 };
 
+// Second launch of a split-K GEMM (ternary_gemm.hip): adds the split_k int32 partial tiles and dequantises.
+// code_sum may be null (signed codes, no correction).
+int launch_splitk_reduce(const GemmArgs& a, hipStream_t stream);
+
 // Outer factors of Eq. 1 and Eq. 5/6 on four consecutive output features of one token:
 // y = bf16(((float)(acc - corr) * s_d) * alpha), corr = sum_k q + code_offset * (sum_k c + K).
 // (ws = the four features' sum_k c, already loaded; ignored when code_offset == 0)

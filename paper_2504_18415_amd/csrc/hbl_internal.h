@@ -77,6 +77,19 @@ inline int decode_split_k(int64_t T, int64_t K, int64_t N) {
 
 // Layout of the forward workspace: int8 codes [T,K] | float s_dequant [T] | int32 code_sum [T], and for
 // T <= 64: | int32 partial [split_k][T][N].
+// K split of the fp6 x fp4 prefill GEMM at mid-size batches: between 65 tokens and about a thousand a long-K
+// projection has too few output tiles (128 x 128) to give most CUs a workgroup, so the K range is cut until about
+// 256 workgroups exist, each keeping at least 8 K-blocks of 128; the int32 partial tiles then take one more launch.
+// Only for K >= 8192: at K = 4096 the unsplit call is short already and the extra launch costs more than it saves
+// (measured: W_down at 96-512 tokens 48-52 us -> 26-45 us; K = 4096 projections 18-20 us -> 21-29 us).
+inline int prefill_split_k(int64_t T, int64_t K, int64_t N) {
+    if (T <= 64 || K < 8192) return 1;
+    const int64_t tiles = ((N + 127) / 128) * ((T + 127) / 128), nkb = K / 128;
+    int sk = 1;
+    while (sk < 8 && tiles * sk * 2 <= 256 && nkb % (sk * 2) == 0 && nkb / (sk * 2) >= 8) sk *= 2;
+    return sk;
+}
+
 struct Workspace {
     int8_t* codes;
     float* s_dequant;
@@ -94,9 +107,10 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
     w.code_sum = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
     off += round_up(static_cast<size_t>(T) * sizeof(int32_t), 256);
     w.partial = nullptr;
-    if (T <= 64) {
+    const int split = T <= 64 ? decode_split_k(T, K, N) : prefill_split_k(T, K, N);
+    if (T <= 64 || split > 1) {
         w.partial = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
-        off += round_up(static_cast<size_t>(decode_split_k(T, K, N)) * T * N * sizeof(int32_t), 256);
+        off += round_up(static_cast<size_t>(split) * T * N * sizeof(int32_t), 256);
     }
     w.bytes = off;
     return w;
@@ -135,7 +149,7 @@ int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t
 // packed form; exact, INT4 activations only.
 int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, const void* packed, int64_t N,
                              const float* s_dequant, const float* w_scales, int64_t n_scale_groups, void* y_bf16,
-                             hipStream_t stream);
+                             hipStream_t stream, int32_t* splitk_partial = nullptr);
 
 // ---------------------------------------------------------------------------------------------
 // Grouped small-batch path: up to kMaxGroup independent projections (T <= 64 each) served by one

@@ -367,10 +367,22 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs a) {
         for (int k = 0; k < a.split_k; ++k)
             sum += *reinterpret_cast<const v4i*>(a.partial + ((size_t)k * a.T + t) * a.N + n);
         *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) =
-            dequant_quad(sum, a.code_sum[t], a.s_dequant[t], a.w_scales[n / a.rows_per_group], a.code_offset,
+            dequant_quad(sum, a.code_sum ? a.code_sum[t] : 0, a.s_dequant[t], a.w_scales[n / a.rows_per_group], a.code_offset,
                          a.w_row_sum + n, a.K);
     }
 }
+
+}  // namespace
+namespace gemm {
+int launch_splitk_reduce(const GemmArgs& a, hipStream_t stream) {
+    const int64_t quads = (int64_t)a.T * (a.N / 4);
+    int64_t blocks = (quads + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    return after_launch();
+}
+}  // namespace gemm
+namespace {
 
 template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT = false, int OCC = 1>
 int launch_cfg(GemmArgs a, hipStream_t stream) {
@@ -387,11 +399,7 @@ int launch_cfg(GemmArgs a, hipStream_t stream) {
                        stream, a);
     int rc = after_launch();
     if (rc != HBL_OK || !SPLIT || a.split_k == 1) return rc;
-    const int64_t quads = (int64_t)a.T * (a.N / 4);
-    int64_t blocks = (quads + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
-    return after_launch();
+    return launch_splitk_reduce(a, stream);
 }
 
 // Developer override for tile-shape experiments: HBL_GEMM_TILE=<index into the table below>.

@@ -27,7 +27,9 @@ using namespace gemm;
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE>
+// SPLIT: workgroup (tile, ks) covers K-blocks [ks * nkb/split_k, (ks+1) * nkb/split_k) and leaves its accumulators,
+// converted to int32 (they are exact integers), in partial[ks][T][N] for the reduction launch.
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool SPLIT = false>
 __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kernel(const GemmArgs a) {
     constexpr int NW = WAVES_N * WAVES_T;
     constexpr int BN = WAVES_N * TN * 32;
@@ -51,13 +53,21 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
 
     // each XCD gets a contiguous run of tiles, feature tile fastest (workgroups are dealt round-robin)
     int wg = blockIdx.x;
+    int ks = 0;
     const int nwg = a.tiles_n * a.tiles_t;
-    if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
+    if constexpr (SPLIT) {
+        ks = wg % a.split_k;
+        wg = wg / a.split_k;
+    } else {
+        if ((nwg & 7) == 0) wg = (wg & 7) * (nwg >> 3) + (wg >> 3);
+    }
     const int tile_n = wg % a.tiles_n;
     const int tile_t = wg / a.tiles_n;
     const int n0 = tile_n * BN;
     const int t0 = tile_t * BT;
-    const int nkb = a.K / kBK;
+    const int nkb_total = a.K / kBK;
+    const int nkb = SPLIT ? nkb_total / a.split_k : nkb_total;   // K-blocks of this workgroup
+    const int kb0 = ks * nkb;
 
     const char* wbase[WL];
 #pragma unroll
@@ -65,12 +75,12 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
         int nt = n0 / 32 + wave + NW * m;
         const int nt_max = a.N / 32 - 1;
         nt = nt < nt_max ? nt : nt_max;
-        wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb) * 1024;
+        wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb_total + kb0) * 1024;
     }
     const uint32_t wlane = lane * 16;
     // copy q covers tokens 8q..8q+7: lane l -> token 8q + l/8, LDS slot l%8, global 16-byte chunk
     // (l%8) ^ ((token/2) % 8); tokens past T are clamped to the last row
-    const char* xbase = reinterpret_cast<const char*>(a.codes) + (size_t)t0 * a.K;
+    const char* xbase = reinterpret_cast<const char*>(a.codes) + (size_t)t0 * a.K + (size_t)kb0 * kBK;
     uint32_t xlane[XL];
 #pragma unroll
     for (int m = 0; m < XL; ++m) {
@@ -239,6 +249,26 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
     // epilogue reuses them
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
+    if constexpr (SPLIT) {
+        if (a.split_k > 1) {   // int32 partial tiles, stored from where the accumulators are (a small volume)
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TT; ++j) {
+                    const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
+                        const v4i o = {(int)acc[i][j][4 * g], (int)acc[i][j][4 * g + 1], (int)acc[i][j][4 * g + 2],
+                                       (int)acc[i][j][4 * g + 3]};
+                        if (t < a.T && n < a.N)
+                            *reinterpret_cast<v4i*>(a.partial + ((size_t)ks * a.T + t) * a.N + n) = o;
+                    }
+                }
+            return;
+        }
+    }
+
     // Epilogue.  A lane holds token (lane & 31) of a 32 x 32 tile, register quad g holding features
     // 8g + 4*(lane >> 5) + 0..3: stored from there, every instruction would touch 32 token rows with
     // 16 bytes each, and the output burst at the end of each round of workgroups (all of them finish
@@ -294,25 +324,29 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
     }
 }
 
-template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE>
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool SPLIT = false>
 int launch_cfg(GemmArgs a, hipStream_t stream) {
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int BT = WAVES_T * TT * 32;
     constexpr size_t lds = (size_t)NSTAGE * (BT * kBK + (BN / 32) * 1024);
     a.tiles_n = (a.N + BN - 1) / BN;
     a.tiles_t = (a.T + BT - 1) / BT;
-    auto kern = ternary_gemm_f6f4_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE>;
+    if (!SPLIT) a.split_k = 1;
+    auto kern = ternary_gemm_f6f4_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, SPLIT>;
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t)), dim3(64 * WAVES_N * WAVES_T), lds, stream, a);
-    return after_launch();
+    hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t * a.split_k)), dim3(64 * WAVES_N * WAVES_T), lds,
+                       stream, a);
+    const int rc = after_launch();
+    if (rc != HBL_OK || a.split_k == 1) return rc;
+    return launch_splitk_reduce(a, stream);
 }
 
 }  // namespace
 
 int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, const void* packed, int64_t N,
                              const float* s_dequant, const float* w_scales, int64_t n_scale_groups, void* y_bf16,
-                             hipStream_t stream) {
+                             hipStream_t stream, int32_t* splitk_partial) {
     if (T == 0) return HBL_OK;
     GemmArgs a = {};
     a.codes = code_records;
@@ -324,7 +358,10 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
     a.K = (int)K;
     a.N = (int)N;
     a.rows_per_group = n_scale_groups > 0 ? (int)(N / n_scale_groups) : (int)N;
-    a.split_k = 1;
+    a.split_k = splitk_partial ? prefill_split_k(T, K, N) : 1;
+    a.partial = splitk_partial;
+    a.code_sum = nullptr;   // signed operands: no correction terms
+    a.code_offset = 0;
     // Workgroup tile: 64 K outputs either way (the 256 accumulator registers of four waves).  512 features x 128
     // tokens moves 32 KB per 128-feature stage through L2 and LDS (16 KB of codes + 16 KB of packed weights) against
     // 40 KB for 256 x 256 (32 + 8): measured 4 % faster on the GEMM at N = 4096 and 12288, equal at N = 32768.  The
@@ -338,6 +375,8 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
     }();
     int cfg = tiles_sq >= 180 ? (tiles_wide <= tiles_sq ? 2 : 0) : 1;
     if (override_tile >= 0) cfg = override_tile;
+    if (a.split_k > 1 && override_tile < 0) return launch_cfg<2, 2, 2, 2, 4, true>(a, stream);   // mid-size batch
+    a.split_k = 1;
     switch (cfg) {
         case 0: return launch_cfg<2, 2, 4, 4, 3>(a, stream);   // 256 x 256, 2 x 2 waves of 128 x 128
         case 1: return launch_cfg<2, 2, 2, 2, 4>(a, stream);   // 128 x 128

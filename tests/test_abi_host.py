@@ -46,6 +46,9 @@ def test_size_queries(L):
     ws = L.hbl_workspace_bytes(8192, 16384, 4096, 4)
     assert ws >= 8192 * 16384 + 8 * 8192 and ws % 256 == 0
     assert L.hbl_workspace_bytes(17, 256, 256, 8) >= 17 * 256 + 8 * 17
+    # a mid-size batch on a long K brings room for the split-K partial tiles (4 slices of [T, N] int32 here)
+    assert L.hbl_workspace_bytes(256, 16384, 4096, 4) >= 256 * 16384 + 4 * 256 * 4096 * 4
+    assert L.hbl_workspace_bytes(256, 4096, 4096, 4) < 256 * 4096 + 256 * 4096 * 4
     assert L.hbl_ternarize_workspace_bytes(4096, 16384) >= 8
     assert L.hbl_ternarize_workspace_bytes(4096, 16384) <= 4096 * 16384 // 16
 

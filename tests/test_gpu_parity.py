@@ -446,6 +446,15 @@ def test_configs_3_4_reduced_shapes(hbl, T, K, N):
     run_site(hbl, synth.shrink(synth.config_sites(4)[1], T=T, K=K, N=N), 4)
 
 
+@pytest.mark.parametrize("T,K,N", [(300, 16384, 1056), (130, 8192, 2048), (513, 16384, 416)])
+def test_mid_size_batch_split_k(hbl, T, K, N):
+    """Between 65 tokens and about a thousand a long-K projection has few output tiles: the fp6 x fp4 GEMM then
+    splits K over workgroups and a reduction launch adds the int32 partial tiles.  Ragged T and N, splits of 8, 4
+    and 2; every output against the oracle."""
+    note(f"mid-size batch split-K T={T} K={K} N={N}")
+    run_site(hbl, synth.shrink(synth.config_sites(4)[1], T=T, K=K, N=N), 4)
+
+
 def test_config3_full_size_sampled(hbl):
     note("config 3 full size, sampled rows")
     site = synth.config_sites(3)[0]
