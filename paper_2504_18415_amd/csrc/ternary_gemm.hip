@@ -416,6 +416,7 @@ int choose(const GemmArgs& a, hipStream_t stream) {
     const int64_t big_tiles = (int64_t)((a.N + 255) / 256) * ((a.T + 255) / 256);
     int cfg;
     if (a.T <= 64 && a.partial != nullptr && !RAW) cfg = a.T <= 32 ? 6 : 7;
+    else if (a.T > 64 && a.partial != nullptr && a.split_k > 1 && !RAW) cfg = 8;   // mid-size batch, long K
     else if (a.T <= 32) cfg = 0;
     else if (a.T <= 64) cfg = 1;
     else if (big_tiles >= 200) {
@@ -433,6 +434,7 @@ int choose(const GemmArgs& a, hipStream_t stream) {
         case 4: return launch_cfg<4, 1, 4, 4, 3, RAW>(a, stream);   // 512 features x 128 tokens, 4 waves of 128 x 128
         case 6: if constexpr (!RAW) return launch_cfg<4, 1, 1, 1, 4, false, true>(a, stream);   // 128 x 32, split-K
         case 7: if constexpr (!RAW) return launch_cfg<4, 1, 1, 2, 4, false, true>(a, stream);   // 128 x 64, split-K
+        case 8: if constexpr (!RAW) return launch_cfg<2, 2, 2, 2, 4, false, true>(a, stream);   // 128 x 128, split-K
         default: return HBL_E_SHAPE;
     }
 }
@@ -459,7 +461,7 @@ int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t
     a.N = (int)N;
     a.rows_per_group = n_scale_groups > 0 ? (int)(N / n_scale_groups) : (int)N;
     a.tiles_n = a.tiles_t = 0;
-    a.split_k = splitk_partial ? decode_split_k(T, K, N) : 1;
+    a.split_k = splitk_partial ? (T <= 64 ? decode_split_k(T, K, N) : prefill_split_k(T, K, N)) : 1;
     a.partial = splitk_partial;
     return acc_out ? choose<true>(a, stream) : choose<false>(a, stream);
 }

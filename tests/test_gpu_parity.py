@@ -453,6 +453,7 @@ def test_mid_size_batch_split_k(hbl, T, K, N):
     and 2; every output against the oracle."""
     note(f"mid-size batch split-K T={T} K={K} N={N}")
     run_site(hbl, synth.shrink(synth.config_sites(4)[1], T=T, K=K, N=N), 4)
+    run_site(hbl, synth.shrink(synth.config_sites(4)[1], T=T, K=K, N=N), 8)     # the int8 kernel's split form
 
 
 def test_config3_full_size_sampled(hbl):
