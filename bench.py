@@ -59,75 +59,111 @@ def to_dev(torch, np, x):
     return torch.from_numpy(x).cuda()
 
 
+def timed_calls(torch, fn, steps, warmup):
+    """ms per call of fn(): `warmup` untimed calls, then `steps` calls bracketed by synchronisation."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def traced_calls(torch, hbl, fn, steps):
+    """Per-kernel durations of `steps` more calls of fn(): every launch carries its own start / stop event pair
+    (hbl_trace_begin / hbl_trace_end: the dispatch's device timestamps, no marker packets between the kernels),
+    so the launches overlap their dispatch with the previous kernel as in the untraced loop.
+    -> {kernel name: mean ms per launch}, launches per call."""
+    torch.cuda.synchronize()
+    with hbl.trace(16 * steps) as tr:
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+    names = sorted({n for n, _ in tr.launches})
+    return {n: tr.mean_ms(n) for n in names}, tr.seen / steps
+
+
 def bench_prefill(args, hbl, synth, torch, np):
     site = {s.name: s for s in synth.config_sites(4)}[args.site]
     T, K, N, bits, eps = site.T, site.K, site.N, 4, hbl.EPS
     x_host = synth.make_x(site)
     x = to_dev(torch, np, x_host)
     packed, alphas, W_host = setup_site(hbl, synth, torch, site, eps)
+    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    ws = hbl.alloc_workspace(T, K, N, bits)
+
+    def step():
+        hbl.hbitlinear_forward(x, packed, N, alphas, bits, eps, y=y, workspace=ws)
+
+    # THE timed region: K calls of the public function after W warm-up calls, bracketed by synchronisation
+    ms_per_step = timed_calls(torch, step, args.steps, args.warmup)
+    # the same K calls once more with every launch timed by its own event pair: the per-kernel durations
+    kernel_ms, launches_per_step = traced_calls(torch, hbl, step, args.steps)
+
+    # INT8 activations (the paper's first training stage) on the same site: int8 matrix cores, byte codes
+    ms_int8 = timed_calls(torch, lambda: hbl.hbitlinear_forward(x, packed, N, alphas, 8, eps, y=y, workspace=ws),
+                          args.steps, 3)
+    # INT4 activations kept on the int8 matrix cores (codes + 8 in bytes) through the stage-level calls: what the
+    # fp6 x fp4 path is measured against
     codes = torch.empty((T, K), dtype=torch.int8, device="cuda")
     sd = torch.empty(T, dtype=torch.float32, device="cuda")
     cs = torch.empty(T, dtype=torch.int32, device="cuda")
-    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
-    ws = hbl.alloc_workspace(T, K, N, bits)
-    # the code form hbl_hbitlinear_forward itself uses for this shape (INT4, T > 64, n = 16384 / 4096)
-    code_form = hbl.CODES_UINT4_PLUS8 if os.environ.get("HBL_NO_F6F4") else hbl.CODES_BF6
 
-    def step_split(ev=None):
-        if ev:
-            ev[0].record()
-        hbl.fwht_quant_into(x, bits, site.hadamard, codes, sd, cs, eps, code_offset=code_form)
-        if ev:
-            ev[1].record()
-        hbl.gemm_dequant_bf16(codes, sd, cs, packed, N, alphas, y=y, code_offset=code_form)
-        if ev:
-            ev[2].record()
+    def step_int8_cores():
+        hbl.fwht_quant_into(x, bits, site.hadamard, codes, sd, cs, eps, code_offset=hbl.CODES_UINT4_PLUS8)
+        hbl.gemm_dequant_bf16(codes, sd, cs, packed, N, alphas, y=y, code_offset=hbl.CODES_UINT4_PLUS8)
 
-    for _ in range(args.warmup):
-        step_split()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step_split(evs[i])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_split = (t1 - t0) * 1e3 / args.steps
-    t_quant = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps     # ms
-    t_gemm = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps      # ms
-
-    # THE timed region: K steps of the public call (the same two launches, no events in between),
-    # after W warm-up steps, bracketed by synchronisation
-    for _ in range(args.warmup):
-        hbl.hbitlinear_forward(x, packed, N, alphas, bits, eps, y=y, workspace=ws)
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    for _ in range(args.steps):
-        hbl.hbitlinear_forward(x, packed, N, alphas, bits, eps, y=y, workspace=ws)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t2) * 1e3 / args.steps
-
-    # INT8 activations (the paper's first training stage) on the same site, for reference: int8 matrix cores
-    for _ in range(3):
-        hbl.hbitlinear_forward(x, packed, N, alphas, 8, eps, y=y, workspace=ws)
-    torch.cuda.synchronize()
-    t3 = time.perf_counter()
-    for _ in range(args.steps):
-        hbl.hbitlinear_forward(x, packed, N, alphas, 8, eps, y=y, workspace=ws)
-    torch.cuda.synchronize()
-    ms_int8 = (time.perf_counter() - t3) * 1e3 / args.steps
+    ms_i8cores = timed_calls(torch, step_int8_cores, args.steps, 3)
+    i8_kernel_ms, _ = traced_calls(torch, hbl, step_int8_cores, args.steps)
+    del codes
 
     ops = 2.0 * T * K * N
+    t_gemm = kernel_ms.get("ternary_gemm_f6f4_kernel", float("nan"))
+    t_quant = kernel_ms.get("fwht_quant_bigrow_kernel", float("nan"))
     out = {
-        "ms_per_step_int8_acts": ms_int8, "tops_end_to_end_int8_acts": ops / (ms_int8 * 1e-3) / 1e12,
-        "T": T, "K": K, "N": N, "ms_per_step": ms_per_step, "ms_split_calls": ms_split,
-        "ms_fwht_quant": t_quant, "ms_gemm": t_gemm,
+        "T": T, "K": K, "N": N, "ms_per_step": ms_per_step, "kernel_ms": kernel_ms,
+        "launches_per_step": launches_per_step, "ms_fwht_quant": t_quant, "ms_gemm": t_gemm,
         "tops_end_to_end": ops / (ms_per_step * 1e-3) / 1e12,
         "tops_gemm": ops / (t_gemm * 1e-3) / 1e12,
-        "fwht_quant_gbs": (2.0 * T * K + T * K + 8.0 * T) / (t_quant * 1e-3) / 1e9,
+        # bytes the quantiser launch moves: bf16 in, code records out (0.75 byte per feature + padding, as stored), scales
+        "fwht_quant_bytes": 2.0 * T * K + hbl.code_bytes(T, K, hbl.CODES_BF6) + 4.0 * T,
+        "int8_activations": {"ms_per_step": ms_int8, "TOPS": ops / (ms_int8 * 1e-3) / 1e12,
+                             "frac_int8_mfma_peak": ops / (ms_int8 * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS},
+        "int4_on_int8_cores": {"ms_per_step": ms_i8cores, "TOPS": ops / (ms_i8cores * 1e-3) / 1e12,
+                               "frac_int8_mfma_peak": ops / (ms_i8cores * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
+                               "kernel_ms": i8_kernel_ms,
+                               "note": "stage-level calls with HBL_CODES_UINT4_PLUS8: same results, int8 MFMA"},
     }
+    out["fwht_quant_gbs"] = out["fwht_quant_bytes"] / (t_quant * 1e-3) / 1e9
     return out, site, x_host, W_host
+
+
+def bench_other_prefill_configs(args, hbl, synth, torch, np):
+    """Whole forward call (both launches) on the other prefill configurations: 2 (INT4 and INT8), 3 and the
+    W_o site of 4 - with the input recipe of each configuration."""
+    eps, out = hbl.EPS, {}
+    cases = [("config2_wo_1p3b_int4", synth.config_sites(2)[0], 4), ("config2_wo_1p3b_int8", synth.config_sites(2)[0], 8),
+             ("config3_wdown_3b_int4", synth.config_sites(3)[0], 4), ("config4_wo_7b_int4", synth.config_sites(4)[0], 4)]
+    for name, site, bits in cases:
+        x = to_dev(torch, np, synth.make_x(site))
+        packed, alphas, _ = setup_site(hbl, synth, torch, site, eps)
+        y = torch.empty((site.T, site.N), dtype=torch.bfloat16, device="cuda")
+        ws = hbl.alloc_workspace(site.T, site.K, site.N, bits)
+
+        def step():
+            hbl.hbitlinear_forward(x, packed, site.N, alphas, bits, eps, y=y, workspace=ws)
+
+        ms = timed_calls(torch, step, args.steps, args.warmup)
+        kernel_ms, _ = traced_calls(torch, hbl, step, args.steps)
+        ops = 2.0 * site.T * site.K * site.N
+        out[name] = {"T": site.T, "K": site.K, "N": site.N, "bits": bits, "ms_per_step": ms,
+                     "TOPS": ops / (ms * 1e-3) / 1e12, "frac_int8_mfma_peak": ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
+                     "kernel_ms": kernel_ms}
+        del x, packed, y, ws
+        torch.cuda.empty_cache()
+    return out
 
 
 def cpu_baseline(site, x_host, W_host, synth, np, budget_s=15.0):
@@ -308,7 +344,7 @@ def bench_decode(args, hbl, synth, torch, np):
                 "bound": "hbm", "achieved": res[best]["grouped"]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": res[best]["grouped"]["GBps"] / HBM_PEAK_GBS,
                 # FETCH_SIZE + WRITE_SIZE of the layer's GEMM launch at batch <= 8 (profiles/hbm_traffic_counters.txt)
-                "traffic": int(33431 * 2.000 * 1024 + 378 * 1024),
+                "traffic": measured_traffic("decode_gemm_kernel", "layer_7b_batch8"),
                 "note": "call level: both launches of the grouped call; the GEMM launch alone streams the layer's "
                         "67.1 MB in 15 us (profiles/decode_layer_kernels_config5.txt)"}
     return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes, "roofline": roofline,
@@ -318,20 +354,31 @@ def bench_decode(args, hbl, synth, torch, np):
             "batch": res}
 
 
-def measured_traffic(site_name, int8_path):
-    """HBM bytes one GEMM launch moves, from the rocprofv3 --pmc passes recorded in
-    profiles/hbm_traffic_counters.txt (FETCH_SIZE scaled by the copy-kernel factor 2.000, WRITE_SIZE by
-    1.000).  Only the workload those passes covered has a figure; counters cannot be read from inside
-    this process."""
-    if site_name == "wdown_7b":
-        if not int8_path:
-            return int(196774 * 2.000 * 1024 + 65556 * 1.000 * 1024)
-        return int(196880 * 2.000 * 1024 + 65550 * 1.000 * 1024)
-    return None
+def measured_traffic(kernel, workload):
+    """HBM bytes one launch moves, from the rocprofv3 --pmc passes recorded in profiles/hbm_traffic_counters.txt
+    (its `@traffic kernel workload FETCH_KIB WRITE_KIB` lines; FETCH_SIZE and WRITE_SIZE scaled by the `@scale`
+    factors a copy kernel of known size gave).  Counters cannot be read from inside this process; a workload
+    the passes did not cover has no figure (None)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
+    scale, rows = {}, {}
+    try:
+        with open(path) as fh:
+            for line in fh:
+                f = line.split()
+                if len(f) == 3 and f[0] == "@scale":
+                    scale[f[1]] = float(f[2])
+                elif len(f) == 5 and f[0] == "@traffic":
+                    rows[(f[1], f[2])] = (float(f[3]), float(f[4]))
+    except OSError:
+        return None
+    if (kernel, workload) not in rows or "FETCH_SIZE" not in scale or "WRITE_SIZE" not in scale:
+        return None
+    fetch, write = rows[(kernel, workload)]
+    return int(fetch * scale["FETCH_SIZE"] * 1024 + write * scale["WRITE_SIZE"] * 1024)
 
 
 def bench_kv_quant(hbl, torch):
-    """Per-head absmax quantiser of the attention states (Section 3.2) on the K (or V) states of the 7B prefill
+    """Per-head absmax quantiser of the attention states (Section 3.1) on the K (or V) states of the 7B prefill
     batch: 8192 tokens x 32 heads of 128, bf16 in, packed codes + one fp32 scale per head out.  HBM-bound:
     algorithmic bytes = 2 per value in, bits/8 per value + 4 per row out."""
     rows, d, nbuf = 8192 * 32, 128, 6   # six distinct 67 MB inputs: more than the 256 MB memory-side cache holds
@@ -378,13 +425,11 @@ def main():
     torch.cuda.set_device(0)
 
     pre, site, x_host, W_host = bench_prefill(args, hbl, synth, torch, np)
-    int8_path = bool(os.environ.get("HBL_NO_F6F4"))
-    gemm_peak = INT8_MFMA_PEAK_TOPS if int8_path else F6F4_MFMA_PEAK_TOPS
     result = {
         "metric": "H-BitLinear TOPS (INT4 acts)", "value": pre["tops_end_to_end"], "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": pre["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "i8" if int8_path else "bf6 x fp4 (exact small integers), fp32 accumulate",
+        "dtype": "bf6 x fp4 (exact small integers), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"config 4 (7B prefill) {site.name}: X bf16 [{site.T}x{site.K}] -> {site.N}, "
                                f"Hadamard n={site.K}, INT4 activations, 2-bit packed ternary W",
@@ -392,22 +437,26 @@ def main():
         "frac_int8_mfma_peak_end_to_end": pre["tops_end_to_end"] / INT8_MFMA_PEAK_TOPS,
         # the GEMM's own dtype sets its roofline; the benchmark's target is quoted against the int8 peak,
         # so that fraction is given too
-        "roofline": {"kernel": "ternary_gemm_kernel (int8 MFMA)" if int8_path
-                               else "ternary_gemm_f6f4_kernel (fp6 x fp4 MFMA, GEMM + dequant epilogue)",
-                     "bound": "mfma", "achieved": pre["tops_gemm"], "peak": gemm_peak, "unit": "TOP/s",
-                     "frac": pre["tops_gemm"] / gemm_peak, "traffic": measured_traffic(site.name, int8_path),
+        "roofline": {"kernel": "ternary_gemm_f6f4_kernel (fp6 x fp4 MFMA, GEMM + dequant epilogue)",
+                     "bound": "mfma", "achieved": pre["tops_gemm"], "peak": F6F4_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": pre["tops_gemm"] / F6F4_MFMA_PEAK_TOPS,
+                     "traffic": measured_traffic("ternary_gemm_f6f4_kernel", site.name),
                      "traffic_unit": "bytes per launch (FETCH_SIZE + WRITE_SIZE, profiles/hbm_traffic_counters.txt)",
-                     "algorithmic_bytes": site.T * site.K + site.N * site.K // 4 + 2 * site.T * site.N,
+                     "algorithmic_bytes": hbl.code_bytes(site.T, site.K, hbl.CODES_BF6) + site.N * site.K // 4
+                                          + 2 * site.T * site.N,
                      "avg_kernel_ms": pre["ms_gemm"],
+                     "timing": "mean over the launches of K calls of the public function, each launch with an event "
+                               "pair of its own (hbl_trace_begin / hbl_trace_end)",
                      "frac_of_int8_mfma_peak": pre["tops_gemm"] / INT8_MFMA_PEAK_TOPS},
         "fwht_quant": {"avg_kernel_ms": pre["ms_fwht_quant"], "bound": "hbm", "achieved": pre["fwht_quant_gbs"],
-                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pre["fwht_quant_gbs"] / HBM_PEAK_GBS},
-        # the stage-level calls with three event records per step (where the per-kernel durations come from)
-        "ms_split_calls_with_events": pre["ms_split_calls"],
-        "int8_activations": {"ms_per_step": pre["ms_per_step_int8_acts"], "TOPS": pre["tops_end_to_end_int8_acts"],
-                             "frac_int8_mfma_peak": pre["tops_end_to_end_int8_acts"] / INT8_MFMA_PEAK_TOPS},
+                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pre["fwht_quant_gbs"] / HBM_PEAK_GBS,
+                       "algorithmic_bytes": pre["fwht_quant_bytes"]},
+        "kernel_ms": pre["kernel_ms"], "launches_per_step": pre["launches_per_step"],
+        "int8_activations": pre["int8_activations"], "int4_on_int8_cores": pre["int4_on_int8_cores"],
     }
     if not args.no_decode:
+        torch.cuda.empty_cache()
+        result["other_prefill_configs"] = bench_other_prefill_configs(args, hbl, synth, torch, np)
         torch.cuda.empty_cache()
         result["prefill_layer_7b"] = bench_prefill_layer(args, hbl, synth, torch, np)
         torch.cuda.empty_cache()

@@ -185,21 +185,13 @@ size_t hbl_grouped_workspace_bytes(const hbl_problem* problems, int n_problems);
 int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, float eps,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
-/*
- * Diagnostic, host only (no launch, no device access): the plan the small-batch GEMM launch of a
- * grouped call would use for these problems (every T in 1..64, n_problems <= 8; only T, K, N and
- * hadamard are read).
- *   ksplit[i]              K slices per 32-row weight tile of problem i (inside a workgroup when every
- *                          T <= 16, over workgroups plus a reduction launch otherwise)
- *   gemm_workgroups        grid size of the GEMM launch;  reduce_workgroups  of the reduction (0 = none)
- *   single_call_streams[i] 1 if a single forward call on problem i uses the weight-streaming kernel
- */
-int hbl_debug_grouped_plan(const hbl_problem* problems, int n_problems, int* ksplit, int* gemm_workgroups,
-                           int* reduce_workgroups, int* single_call_streams);
-
 /* ---------------------------------------------------------------------------
  * Stage-level entry points (parity checks and profiling; same kernels)
  * ------------------------------------------------------------------------- */
+
+/* Bytes of the code buffer hbl_fwht_quant writes for [T, K] activations in the given form (0 for a form
+ * the shape does not allow). */
+size_t hbl_code_bytes(int64_t T, int64_t K, int code_form);
 
 /*
  * Activation front end only (Eq. 3-6): transform (if hadamard != 0) and quantise.
@@ -241,21 +233,34 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
                  int32_t* acc, void* stream);
 
 /*
+ * The same contraction on the fp6 x fp4 matrix-core kernel, the one every INT4 forward call with T > 64 and
+ * K >= 512 runs: acc[t][o] = sum_k q[t][k] * c[o][k] as int32 [T, N], read out of that kernel's fp32
+ * accumulators (exact integers) with no dequantisation, in the launch configuration (workgroup tile,
+ * K split over workgroups at mid-size batches) hbl_hbitlinear_forward takes for the same T, K, N.
+ *   code_records  [T, K] bytes of HBL_CODES_BF6 records as written by hbl_fwht_quant (K >= 512)
+ *   workspace     device, >= hbl_workspace_bytes(T, K, N, 4), 256-byte aligned (holds the int32 partial
+ *                 tiles when the K range is split; the code region of it is not touched)
+ */
+int hbl_gemm_i32_bf6(const void* code_records, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+                     int32_t* acc, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * GEMM + dequantising epilogue only (Eq. 7 given the quantised activations): the second of the
  * two launches the forward calls make, on caller-held intermediates.
  *   codes [T, K] int8, s_dequant [T] fp32, code_sum [T] int32: as written by hbl_fwht_quant with
  *   the same code_offset;  y [T, N] bf16 out
- * hbl_hbitlinear_forward(x, ...) == hbl_fwht_quant(x, ..., hadamard=1, code_offset = bits==4 ? 8 : 0)
- * into the workspace followed by this call; hbl_plain_bitlinear_forward likewise with hadamard=0.
+ * A forward call is hbl_fwht_quant(x, ..., hadamard, code_offset) into the workspace followed by this
+ * call, with code_offset = HBL_CODES_BF6 for INT4 activations when T > 64 and K >= 512 (fp6 x fp4
+ * matrix cores), HBL_CODES_UINT4_PLUS8 for INT4 otherwise, HBL_CODES_INT8 for INT8 activations.
  */
 int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_dequant,
                           const int32_t* code_sum, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
                           const float* w_scales, int64_t n_scale_groups, void* y, void* stream);
 
 /* ---------------------------------------------------------------------------
- * Low-bit attention states (Section 3.2: 8-, 4- and 3-bit Q/K/V heads and KV cache).
- * The head states after RoPE are quantised per head row "to unsigned integers using the absmax
- * function"; the paper prints no formula, and this library takes Eq. 5 at b bits with an offset:
+ * Low-bit attention states (Section 3.1, Main Results: 8-, 4- and 3-bit Q/K/V heads and KV cache).
+ * The head states after RoPE are quantised per head row; the paper names the method (absmax, to unsigned
+ * codes, no calibration) and prints no formula, and this library takes Eq. 5 at b bits with an offset:
  *   gamma = max|h|, qmax = 2^(b-1) - 1,
  *   u[i] = RoundClip(qmax/(gamma+eps) * h[i], -2^(b-1), qmax) + 2^(b-1)  in [0, 2^b - 1],
  *   scale = gamma / qmax,  h^[i] = (u[i] - 2^(b-1)) * scale
@@ -276,6 +281,24 @@ int hbl_kv_quant_absmax(const void* x, int x_dtype, int64_t rows, int64_t d, int
 /* The inverse map: out [rows, d] out_dtype (HBL_F32, or HBL_BF16 rounded to nearest even), 16-byte aligned. */
 int hbl_kv_dequant(const void* packed, const float* scales, int64_t rows, int64_t d, int bits,
                    void* out, int out_dtype, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Kernel timing (benchmarks and profiling; not part of the forward path)
+ * ---------------------------------------------------------------------------
+ * Between hbl_trace_begin and hbl_trace_end every kernel this library launches from the calling thread
+ * goes out with a start / stop event pair of its own, filled by the runtime with that dispatch's device
+ * timestamps: the durations are the kernels' own (what a kernel trace of a profiler reports), with no
+ * marker packets between the launches.  The events are host objects created at hbl_trace_begin (no device
+ * memory); hbl_trace_end waits for the traced launches to finish.  Do not trace calls that are being
+ * captured into a HIP graph.
+ *   max_launches   launches to time (later ones are launched untimed but still counted)
+ *   ms             [capacity] out: duration of launch i in milliseconds, in launch order
+ *   kernel_names   [capacity] out: static strings naming the kernel family of launch i (or NULL)
+ *   n_launches     out: launches seen since hbl_trace_begin
+ * Errors: HBL_E_SHAPE for a bad count, for begin inside an open trace or end without one; HBL_E_HIP.
+ */
+int hbl_trace_begin(int max_launches);
+int hbl_trace_end(float* ms, const char** kernel_names, int capacity, int* n_launches);
 
 #ifdef __cplusplus
 }

@@ -29,9 +29,9 @@
  *   - Eq. 8 (backward through the transform) is the same transform applied
  *     to the gradient rows, in the same fp32 butterfly order.
  *   - X is a row vector per token, W is [N out x K in]: Y[T x N] = Xq * Wq^T.
- *   - low-bit Q/K/V head states (Section 3.2, low-bit attention): the paper says
- *     only that the post-RoPE head states are quantised "to unsigned integers
- *     using the absmax function".  Taken here as Eq. 5 at b bits per head row,
+ *   - low-bit Q/K/V head states (Section 3.1, Main Results, low-bit attention):
+ *     the paper names the method for the post-RoPE head states (absmax, to
+ *     unsigned codes) and prints no formula.  Taken here as Eq. 5 at b bits per head row,
  *     stored with an offset: u = RoundClip(qmax/(gamma+eps) * h, -2^(b-1),
  *     2^(b-1)-1) + 2^(b-1), qmax = 2^(b-1)-1, dequantised (u - 2^(b-1)) *
  *     gamma/qmax.  At b = 8 this is Eq. 5 itself plus 128.
@@ -371,7 +371,7 @@ int hblo_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, con
 }
 
 /* ------------------------------------------------------------------------
- * Low-bit Q/K/V head states (Section 3.2, "low-bit attention"; reading in the
+ * Low-bit Q/K/V head states (Section 3.1, Main Results, low-bit attention; reading in the
  * header).  One row = one head of one token after RoPE, d values.
  *   gamma = max|h|,  qmax = 2^(b-1) - 1,  s_q = qmax / (gamma + eps)  (fp32 division)
  *   u[i]  = RoundClip(s_q * h[i], -2^(b-1), qmax) + 2^(b-1)           in [0, 2^b - 1]

@@ -194,7 +194,7 @@ def plain_bitlinear_forward(x, wcodes, w_scales, bits, eps: float = EPS, **kw):
 
 
 def kv_quant_absmax(x: np.ndarray, bits: int, eps: float = EPS):
-    """Low-bit head states (Section 3.2): x [rows, d] fp32 or bf16 bits -> (unsigned codes [rows, d] uint8,
+    """Low-bit head states (Section 3.1, Main Results): x [rows, d] fp32 or bf16 bits -> (unsigned codes [rows, d] uint8,
     packed [rows, d*bits/8] uint8, scales [rows] fp32)."""
     x = np.ascontiguousarray(x)
     rows, d = x.shape

@@ -1,10 +1,14 @@
 """Builds libhbitlinear.so (HIP, gfx950 only) in-tree with hipcc.
 
-Usage: ``python -m paper_2504_18415_amd.build`` or ``build.build_library()``.
-The sources are cross-compiled, so no GPU is needed to build.
+Usage: ``python -m paper_2504_18415_amd.build [--incremental]`` or ``build.build_library()``.
+The sources are cross-compiled, so no GPU is needed to build.  Every translation unit is compiled by a
+process of its own (in parallel) into ``csrc/_build/`` and the objects are linked into the library;
+``incremental=True`` recompiles only the units older than their source or than any header.
 """
 from __future__ import annotations
 
+import concurrent.futures
+import glob
 import os
 import subprocess
 import sys
@@ -12,12 +16,13 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
+OBJ_DIR = os.path.join(CSRC, "_build")
 LIB = os.path.join(PKG, "libhbitlinear.so")
 SOURCES = ["api.hip", "fwht_quant.hip", "ternary_setup.hip", "ternary_gemm.hip", "ternary_gemm_f6f4.hip", "decode_gemm.hip",
            "kv_quant.hip"]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                       # butterflies and scales round once per operation
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument", "-Wno-inline-asm",
@@ -25,11 +30,7 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    tmp = LIB + f".tmp{os.getpid()}"
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, *srcs, "-o", tmp]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -37,12 +38,33 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
         sys.stderr.write(err + "\n")
-        raise RuntimeError("hipcc failed building libhbitlinear.so")
+        raise RuntimeError("hipcc failed: " + " ".join(cmd[-3:]))
     if verbose and err.strip():
         print(err)
+
+
+def build_library(verbose: bool = False, extra_flags=(), incremental: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    newest_header = max(os.path.getmtime(h) for h in headers)
+    jobs, objs = [], []
+    for s in SOURCES:
+        src = os.path.join(CSRC, s)
+        obj = os.path.join(OBJ_DIR, s.replace(".hip", ".o"))
+        objs.append(obj)
+        fresh = (incremental and not extra_flags and os.path.exists(obj)
+                 and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header))
+        if not fresh:
+            jobs.append([hipcc, *HIPCC_FLAGS, *extra_flags, "-c", src, "-o", obj])
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, max(len(jobs), 1))) as pool:
+        for f in [pool.submit(_run, cmd, verbose) for cmd in jobs]:
+            f.result()
+    tmp = LIB + f".tmp{os.getpid()}"
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp], verbose)
     os.replace(tmp, LIB)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=True, incremental="--incremental" in sys.argv))

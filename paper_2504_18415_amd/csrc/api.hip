@@ -1,20 +1,25 @@
 // C-ABI entry points of libhbitlinear: argument validation and kernel sequencing only.
-#include <stdlib.h>
+#include <vector>
 
 #include "hbl_internal.h"
+#include "hbl_test_exports.h"
 
 namespace hbl {
 
 static thread_local int g_last_hip_error = 0;
 
-int decode_wg_target() {
-    static const int v = [] {
-        const char* e = getenv("HBL_DECODE_WGS");
-        const int t = e ? atoi(e) : 192;
-        return t > 0 ? t : 192;
-    }();
-    return v;
-}
+namespace {
+// The calling thread's kernel-timing trace (hbl_trace_begin / hbl_trace_end).
+struct TraceState {
+    LaunchTrace view{};
+    std::vector<hipEvent_t> start, stop;
+    std::vector<const char*> names;
+    bool open = false;
+};
+thread_local TraceState g_trace;
+}  // namespace
+
+LaunchTrace* current_trace() { return g_trace.open ? &g_trace.view : nullptr; }
 
 int note_hip_error(hipError_t e) {
     g_last_hip_error = (int)e;
@@ -78,9 +83,8 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Workspace ws = carve_workspace(workspace, T, K, N);
     // INT4 at prefill sizes: bf6 code records and the fp6 x fp4 matrix cores (exact, twice the int8
-    // MFMA rate).  HBL_NO_F6F4=1 keeps everything on the int8 path.
-    static const bool no_f6f4 = getenv("HBL_NO_F6F4") != nullptr;
-    if (!no_f6f4 && bf6_path_supported(T, K, bits, hadamard)) {
+    // MFMA rate).
+    if (bf6_path_supported(T, K, bits, hadamard)) {
         rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, kCodesBf6, s,
                                ln_gain, ln_eps);
         if (rc != HBL_OK) return rc;
@@ -91,8 +95,7 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, code_offset, s,
                            ln_gain, ln_eps);
     if (rc != HBL_OK) return rc;
-    static const bool no_stream = getenv("HBL_NO_DECODE_STREAM") != nullptr;
-    if (!no_stream && decode_stream_preferred(T, K, N)) {   // a handful of tokens: one weight-streaming launch
+    if (decode_stream_preferred(T, K, N)) {   // a handful of tokens: one weight-streaming launch
         DecodeArgs da = {};
         da.n = 1;
         fill_decode_problem(da.p[0], ws, nullptr, T, K, Wq_packed, N, w_scales, groups, code_offset, y);
@@ -171,7 +174,7 @@ int hbl_unpack_ternary_2bit(const void* packed, int64_t N, int64_t K, int8_t* co
 
 size_t hbl_workspace_bytes(int64_t T, int64_t K, int64_t N, int bits) {
     (void)bits;
-    if (T <= 0 || K <= 0) return 256;
+    if (T <= 0 || K <= 0 || N <= 0) return 256;
     return carve_workspace(nullptr, T, K, N).bytes;
 }
 
@@ -290,7 +293,7 @@ int hbl_ln_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, const fl
                              static_cast<hipStream_t>(stream), ln_gain, ln_eps);
 }
 
-int hbl_debug_grouped_plan(const hbl_problem* problems, int n_problems, int* ksplit, int* gemm_workgroups,
+int hbl_test_grouped_plan(const hbl_problem* problems, int n_problems, int* ksplit, int* gemm_workgroups,
                            int* reduce_workgroups, int* single_call_streams) {
     if (!problems || !ksplit || !gemm_workgroups || !reduce_workgroups || !single_call_streams) return HBL_E_NULL;
     if (n_problems < 1 || n_problems > kMaxGroup) return HBL_E_SHAPE;
@@ -312,6 +315,13 @@ int hbl_debug_grouped_plan(const hbl_problem* problems, int n_problems, int* ksp
     if (rc != HBL_OK) return rc;
     for (int i = 0; i < n_problems; ++i) ksplit[i] = da.p[i].ksplit;
     return HBL_OK;
+}
+
+size_t hbl_code_bytes(int64_t T, int64_t K, int code_form) {
+    if (T < 0 || K < 128 || K > 16384 || (K % 128) != 0) return 0;
+    if (code_form == HBL_CODES_INT8 || code_form == HBL_CODES_UINT4_PLUS8) return (size_t)T * (size_t)K;
+    if (code_form == HBL_CODES_BF6) return K >= 512 ? code_record_bytes(T, K) : 0;
+    return 0;
 }
 
 int hbl_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, int hadamard,
@@ -377,6 +387,86 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
     if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(acc)) return HBL_E_ALIGN;
     return launch_ternary_gemm(codes, 0, T, K, Wq_packed, N, nullptr, nullptr, nullptr, 1, nullptr, acc,
                                nullptr, static_cast<hipStream_t>(stream));
+}
+
+int hbl_gemm_i32_bf6(const void* code_records, int64_t T, int64_t K, const void* Wq_packed, int64_t N, int32_t* acc,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_gemm_shape(T, K, N, false);
+    if (rc != HBL_OK) return rc;
+    if (K < 512) return HBL_E_SHAPE;
+    if (T == 0) return HBL_OK;
+    if (!code_records || !Wq_packed || !acc || !workspace) return HBL_E_NULL;
+    if (!aligned16(code_records) || !aligned16(Wq_packed) || !aligned16(acc) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return HBL_E_ALIGN;
+    if (workspace_bytes < hbl_workspace_bytes(T, K, N, 4)) return HBL_E_WORKSPACE;
+    const Workspace ws = carve_workspace(workspace, T, K, N);
+    return launch_ternary_gemm_f6f4(static_cast<const int8_t*>(code_records), T, K, Wq_packed, N, nullptr, nullptr, 1,
+                                    nullptr, static_cast<hipStream_t>(stream), T > 64 ? ws.partial : nullptr, acc);
+}
+
+int hbl_test_gemm_i32_tile(const void* codes, int code_form, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+                           int32_t* acc, int tile, void* partial, size_t partial_bytes, void* stream) {
+    if (code_form != HBL_CODES_INT8 && code_form != HBL_CODES_BF6) return HBL_E_BITS;
+    if (tile < kTileSquare || tile > kTileSplitK) return HBL_E_SHAPE;
+    int rc = check_gemm_shape(T, K, N, false);
+    if (rc != HBL_OK) return rc;
+    if (T <= 64 || (code_form == HBL_CODES_BF6 && K < 512)) return HBL_E_SHAPE;
+    if (!codes || !Wq_packed || !acc) return HBL_E_NULL;
+    if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(acc) || !aligned16(partial)) return HBL_E_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (tile == kTileSplitK) {
+        // the K cut the launcher will take: the forward's own for this shape, else 4 (or 2) slices
+        if (code_form != HBL_CODES_BF6) return HBL_E_SHAPE;
+        int split = prefill_split_k(T, K, N);
+        if (split == 1) split = (K / 128) % 4 == 0 ? 4 : ((K / 128) % 2 == 0 ? 2 : 1);
+        if (!partial || partial_bytes < (size_t)split * T * N * sizeof(int32_t)) return HBL_E_WORKSPACE;
+    }
+    if (code_form == HBL_CODES_BF6)
+        return launch_ternary_gemm_f6f4(static_cast<const int8_t*>(codes), T, K, Wq_packed, N, nullptr, nullptr, 1,
+                                        nullptr, s, tile == kTileSplitK ? static_cast<int32_t*>(partial) : nullptr, acc,
+                                        tile);
+    return launch_ternary_gemm(static_cast<const int8_t*>(codes), 0, T, K, Wq_packed, N, nullptr, nullptr, nullptr, 1,
+                               nullptr, acc, nullptr, s, tile);
+}
+
+int hbl_trace_begin(int max_launches) {
+    if (max_launches < 1 || max_launches > (1 << 20)) return HBL_E_SHAPE;
+    TraceState& t = g_trace;
+    if (t.open) return HBL_E_SHAPE;
+    while ((int)t.start.size() < max_launches) {
+        hipEvent_t a = nullptr, b = nullptr;
+        hipError_t e = hipEventCreate(&a);
+        if (e == hipSuccess) e = hipEventCreate(&b);
+        if (e != hipSuccess) {
+            if (a) (void)hipEventDestroy(a);
+            return note_hip_error(e);
+        }
+        t.start.push_back(a);
+        t.stop.push_back(b);
+    }
+    t.names.assign(t.start.size(), nullptr);
+    t.view = LaunchTrace{t.start.data(), t.stop.data(), t.names.data(), max_launches, 0};
+    t.open = true;
+    return HBL_OK;
+}
+
+int hbl_trace_end(float* ms, const char** kernel_names, int capacity, int* n_launches) {
+    TraceState& t = g_trace;
+    if (!t.open) return HBL_E_SHAPE;
+    t.open = false;
+    const int seen = t.view.count;
+    const int timed = seen < t.view.capacity ? seen : t.view.capacity;
+    if (n_launches) *n_launches = seen;
+    for (int i = 0; i < timed && i < capacity; ++i) {
+        hipError_t e = hipEventSynchronize(t.stop[i]);
+        float v = 0.0f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&v, t.start[i], t.stop[i]);
+        if (e != hipSuccess) return note_hip_error(e);
+        if (ms) ms[i] = v;
+        if (kernel_names) kernel_names[i] = t.names[i];
+    }
+    return HBL_OK;
 }
 
 int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_dequant, const int32_t* code_sum,

@@ -15,8 +15,6 @@
 //  - shared (T <= 64): the four waves take four row tiles over one K range and share the code stage
 //    (32 or 64 rows x 128 B): one barrier per stage.  A K range split over workgroups leaves int32
 //    partial tiles that a second launch adds and dequantises.
-#include <stdlib.h>
-
 #include <atomic>
 
 #include "gemm_common.h"
@@ -268,10 +266,10 @@ int launch_form(const DecodeArgs& a, int wgs, int red_wgs, hipStream_t stream) {
     auto kern = decode_gemm_kernel<SHARE, TT, RQ, D, NW>;
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(64 * NW), lds, stream, a);
+    launch_kernel("decode_gemm_kernel", kern, dim3((unsigned)wgs), dim3(64 * NW), lds, stream, a);
     int rc = after_launch();
     if (rc != HBL_OK || red_wgs == 0) return rc;
-    hipLaunchKernelGGL(decode_reduce_kernel, dim3((unsigned)red_wgs), dim3(256), 0, stream, a);
+    launch_kernel("decode_reduce_kernel", decode_reduce_kernel, dim3((unsigned)red_wgs), dim3(256), 0, stream, a);
     return after_launch();
 }
 
@@ -381,21 +379,12 @@ int launch_decode_gemm(DecodeArgs& a, hipStream_t stream) {
                           : launch_form<false, 1, 2, 4, 8>(a, wgs, 0, stream);
     }
     plan(a, max_t > 16, &wgs, &red);
-    // Stages in flight per wave.  Shallow is best (measured 3..8): the memory-level parallelism comes from
-    // the 2048 waves of a full grid, and deeper rings only cost LDS and queueing.  HBL_DECODE_DEPTH overrides.
-    static const int depth = [] { const char* e = getenv("HBL_DECODE_DEPTH"); return e ? atoi(e) : 0; }();
-#define HBL_FORM(SH, TT_, RQ_, DEF)                                                        \
-    switch (depth ? depth : DEF) {                                                         \
-        case 3: return launch_form<SH, TT_, RQ_, 3>(a, wgs, SH ? red : 0, stream);         \
-        case 4: return launch_form<SH, TT_, RQ_, 4>(a, wgs, SH ? red : 0, stream);         \
-        case 6: return launch_form<SH, TT_, RQ_, 6>(a, wgs, SH ? red : 0, stream);         \
-        default: return launch_form<SH, TT_, RQ_, 8>(a, wgs, SH ? red : 0, stream);        \
-    }
-    if (max_t <= 8) HBL_FORM(false, 1, 1, 4)
-    if (max_t <= 16) HBL_FORM(false, 1, 2, 4)
-    if (max_t <= 32) HBL_FORM(true, 1, 1, 4)
-    HBL_FORM(true, 2, 1, 4)
-#undef HBL_FORM
+    // Stages in flight per wave: 4.  Shallow is best (3 to 8 measured): the memory-level parallelism comes from
+    // the 2048 waves of a full grid, and deeper rings only cost LDS and queueing.
+    if (max_t <= 8) return launch_form<false, 1, 1, 4>(a, wgs, 0, stream);
+    if (max_t <= 16) return launch_form<false, 1, 2, 4>(a, wgs, 0, stream);
+    if (max_t <= 32) return launch_form<true, 1, 1, 4>(a, wgs, red, stream);
+    return launch_form<true, 2, 1, 4>(a, wgs, red, stream);
 }
 
 }  // namespace hbl

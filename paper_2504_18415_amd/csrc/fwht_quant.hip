@@ -17,8 +17,6 @@
 // so that every global access is one contiguous CH-element piece per lane and
 // the stage order e -> lane -> r -> wave is ascending.  The wave stages swap
 // the wave bits with the low r bits through LDS once, then run in registers.
-#include <stdlib.h>
-
 #include <atomic>
 
 #include "hbl_internal.h"
@@ -495,7 +493,7 @@ int launch_one(const void* x, int64_t T, int8_t* codes, float* s_dequant, int32_
     auto kern = fwht_quant_kernel<LOG2K, W, BITS, BF16, HADAMARD>;
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, rp, code_offset);
+    launch_kernel("fwht_quant_kernel", kern, dim3((unsigned)T), dim3(64 * W), lds, stream, x, codes, s_dequant, code_sum, rp, code_offset);
     return after_launch();
 }
 
@@ -619,7 +617,7 @@ void launch_generic_slots(const void* x, int64_t T, int64_t K, RowParams rp, int
     const dim3 grid((unsigned)T), block(256);
     const int64_t per_thread = (K / 8 + 255) / 256;   // 8-element chunks per thread
 #define HBL_GENERIC(MAXC)                                                                                     \
-    hipLaunchKernelGGL((quant_generic_kernel<BITS, BF16, MAXC>), grid, block, 0, stream, x, (int)K, codes, s_dequant, \
+    launch_kernel("quant_generic_kernel", (quant_generic_kernel<BITS, BF16, MAXC>), grid, block, 0, stream, x, (int)K, codes, s_dequant, \
                        code_sum, rp, code_offset)
     if (per_thread <= 1) HBL_GENERIC(1);
     else if (per_thread <= 2) HBL_GENERIC(2);
@@ -1034,7 +1032,7 @@ int launch_bigrow_form(const void* x, int64_t T, int8_t* codes, float* s_dequant
         if (const int rc = resident_workgroups(kern, K / 64, lds, resident, &grid); rc != HBL_OK) return rc;
         if ((int64_t)grid > T) grid = (int)T;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(K / 64), lds, stream, x, T, codes, s_dequant, code_sum, rp,
+    launch_kernel("fwht_quant_bigrow_kernel", kern, dim3((unsigned)grid), dim3(K / 64), lds, stream, x, T, codes, s_dequant, code_sum, rp,
                        code_offset);
     return after_launch();
 }
@@ -1052,11 +1050,15 @@ int dispatch_bigrow(const void* x, int x_dtype, int64_t T, int bits, RowParams r
               : launch_bigrow<LOG2K, 4, false>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream);
 }
 
-template <int LOG2K, int W>
+// WITH_H = false: rows of 4096 and more, whose transform belongs to the all-register kernel above - only the
+// plain quantiser is compiled from this body for them.
+template <int LOG2K, int W, bool WITH_H = true>
 int dispatch(const void* x, int x_dtype, int64_t T, int bits, RowParams rp, bool hadamard, int8_t* codes,
              float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream) {
     const bool bf = x_dtype == HBL_BF16;
-    if (hadamard) {
+    if constexpr (!WITH_H) {
+        if (hadamard) return HBL_E_SHAPE;
+    } else if (hadamard) {
         if (bits == 8) return bf ? launch_one<LOG2K, W, 8, true, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream)
                                  : launch_one<LOG2K, W, 8, false, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream);
         return bf ? launch_one<LOG2K, W, 4, true, true>(x, T, codes, s_dequant, code_sum, rp, code_offset, stream)
@@ -1129,7 +1131,7 @@ int launch_quant_grouped(const QuantGroupArgs& args, int bits, int x_dtype, hipS
     auto launch = [&](auto kern) -> int {
         static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
         if (const int rc = allow_dynamic_lds(kern, 64 * 1024, lds_allowed); rc != HBL_OK) return rc;
-        hipLaunchKernelGGL(kern, dim3((unsigned)rows), dim3(256), lds, stream, args);
+        launch_kernel("quant_grouped_kernel", kern, dim3((unsigned)rows), dim3(256), lds, stream, args);
         return after_launch();
     };
     if (bits == 8) return bf ? launch(quant_grouped_kernel<8, true>) : launch(quant_grouped_kernel<8, false>);
@@ -1170,7 +1172,7 @@ int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits
     const RowParams rp = {eps, ln_gain, ln_eps, T <= 64 ? 1 : 0};
     if (code_offset == kCodesBf6 && (bits != 4 || K < 512)) return HBL_E_SHAPE;   // records need 8-element chunks
     if (!hadamard && !is_pow2(K)) return launch_generic(x, x_dtype, T, K, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
-    if (hadamard && (code_offset == kCodesBf6 || !getenv("HBL_FWHT_OLD"))) {
+    if (hadamard) {
         if (K == 4096) return dispatch_bigrow<12>(x, x_dtype, T, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
         if (K == 8192) return dispatch_bigrow<13>(x, x_dtype, T, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
         if (K == 16384) return dispatch_bigrow<14>(x, x_dtype, T, bits, rp, codes, s_dequant, code_sum, code_offset, stream);
@@ -1181,9 +1183,9 @@ int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits
         case 512:   return dispatch<9, 1>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
         case 1024:  return dispatch<10, 1>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
         case 2048:  return dispatch<11, 1>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 4096:  return dispatch<12, 2>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 8192:  return dispatch<13, 4>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
-        case 16384: return dispatch<14, 4>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 4096:  return dispatch<12, 2, false>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 8192:  return dispatch<13, 4, false>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
+        case 16384: return dispatch<14, 4, false>(x, x_dtype, T, bits, rp, hadamard, codes, s_dequant, code_sum, code_offset, stream);
         default:    return HBL_E_SHAPE;
     }
 }

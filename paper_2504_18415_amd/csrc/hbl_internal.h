@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <atomic>
@@ -13,6 +14,35 @@ namespace hbl {
 
 // Records a failed HIP call for hbl_last_hip_error() and yields HBL_E_HIP.
 int note_hip_error(hipError_t e);
+
+// Per-launch kernel timing (hbl_trace_begin / hbl_trace_end): while a trace is open on the calling thread every
+// kernel launch of the library goes out with a start / stop event pair of its own, which the runtime fills with
+// the dispatch's own device timestamps (no marker packets between the kernels, so the launches overlap their
+// dispatch with the previous kernel exactly as untraced launches do).
+struct LaunchTrace {
+    hipEvent_t* start;
+    hipEvent_t* stop;
+    const char** names;
+    int capacity;
+    int count;      // launches seen since hbl_trace_begin (may exceed capacity: the excess is not timed)
+};
+LaunchTrace* current_trace();   // the calling thread's open trace, or nullptr
+
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(const char* name, void (*kern)(KArgs...), dim3 grid, dim3 block, size_t lds,
+                          hipStream_t stream, Args&&... args) {
+    LaunchTrace* tr = current_trace();
+    if (tr != nullptr) {
+        const int i = tr->count++;
+        if (i < tr->capacity) {
+            tr->names[i] = name;
+            hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)lds, stream, tr->start[i], tr->stop[i], 0,
+                                  static_cast<KArgs>(args)...);
+            return;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, static_cast<KArgs>(args)...);
+}
 
 inline int after_launch() {
     hipError_t e = hipGetLastError();
@@ -66,12 +96,12 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Split-K factor of the small-T (decode) GEMM: split K only until there are enough workgroups (128
 // output rows each) to occupy the chip, and never below 4 K-blocks of 128 per workgroup.  Every
 // split costs a second launch (the reduction) and T*N*4 bytes of partials per slice.
-int decode_wg_target();   // HBL_DECODE_WGS developer override, default 192
+constexpr int kDecodeWgTarget = 192;
 inline int decode_split_k(int64_t T, int64_t K, int64_t N) {
     if (T > 64 || T <= 0) return 1;
     const int64_t nkb = K / 128, groups = (N + 127) / 128;
     int sk = 1;
-    while ((int64_t)sk * groups < decode_wg_target() && nkb % (sk * 2) == 0 && nkb / (sk * 2) >= 4) sk *= 2;
+    while ((int64_t)sk * groups < kDecodeWgTarget && nkb % (sk * 2) == 0 && nkb / (sk * 2) >= 4) sk *= 2;
     return sk;
 }
 
@@ -120,6 +150,8 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
 // Codes are stored as code + code_offset (0, or 8 for INT4 so that the stored bytes are 0..15), or -
 // code_offset == kCodesBf6 - as bf6 records (see fwht_quant.hip; INT4 with K >= 512).
 constexpr int kCodesBf6 = 6;
+// bytes of [T, K] codes as bf6 records
+inline size_t code_record_bytes(int64_t T, int64_t K) { return (size_t)T * (size_t)K; }
 inline bool bf6_path_supported(int64_t T, int64_t K, int bits, bool hadamard) {
     (void)hadamard;
     return bits == 4 && T > 64 && K >= 512;
@@ -138,18 +170,25 @@ int launch_kv_dequant(const void* packed, const float* scales, int64_t rows, int
                       int out_dtype, hipStream_t stream);
 int launch_fwht_only(const void* x, int x_dtype, int64_t T, int64_t K, void* out, int out_dtype, hipStream_t stream);
 
+// Workgroup tiles of the two prefill GEMM kernels.  kTileAuto is the choice every forward call makes from the
+// shape; the others let the parity tests run a given tile on a shape of their own.
+constexpr int kTileAuto = -1, kTileSquare = 0 /*256 x 256*/, kTileSmall = 1 /*128 x 128*/,
+              kTileWide = 2 /*512 features x 128 tokens*/, kTileSplitK = 3 /*128 x 128, K cut over workgroups*/;
+
 // GEMM + epilogue. If acc_out != nullptr the raw int32 accumulators are written
 // (no scales, no code_sum needed); otherwise y (bf16) is written.
 int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,
                         const float* s_dequant, const int32_t* code_sum, const float* w_scales,
                         int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, int32_t* splitk_partial,
-                        hipStream_t stream);
+                        hipStream_t stream, int tile = kTileAuto);
 
 // GEMM + epilogue on the fp6 x fp4 matrix-core path: codes as bf6 records, weights from the second
 // packed form; exact, INT4 activations only.
+// acc_out != nullptr: the raw accumulators as int32 [T, N] instead of y.
 int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, const void* packed, int64_t N,
                              const float* s_dequant, const float* w_scales, int64_t n_scale_groups, void* y_bf16,
-                             hipStream_t stream, int32_t* splitk_partial = nullptr);
+                             hipStream_t stream, int32_t* splitk_partial = nullptr, int32_t* acc_out = nullptr,
+                             int tile = kTileAuto);
 
 // ---------------------------------------------------------------------------------------------
 // Grouped small-batch path: up to kMaxGroup independent projections (T <= 64 each) served by one

@@ -1,8 +1,8 @@
-// Low-bit Q/K/V head states (Section 3.2, the 8/4/3-bit attention results): per head row of d values
+// Low-bit Q/K/V head states (Section 3.1, Main Results: the 8/4/3-bit attention results): per head row of d values
 //   gamma = max|h|,  qmax = 2^(b-1) - 1,
 //   u[i]  = RoundClip(qmax/(gamma+eps) * h[i], -2^(b-1), qmax) + 2^(b-1)   (unsigned, in [0, 2^b - 1])
 //   scale = gamma / qmax,   h^[i] = (u[i] - 2^(b-1)) * scale.
-// The paper states only "unsigned integers using the absmax function"; this is Eq. 5 at b bits with an
+// The paper names the method (absmax, to unsigned codes) and prints no formula; this is Eq. 5 at b bits with an
 // offset (Eq. 5 itself plus 128 at b = 8).  Round-half-to-even, IEEE fp32 divisions, eps added as in Eq. 5.
 //
 // Memory-bound streaming kernels.  A thread owns 8 consecutive values (one 16-byte load of bf16, two of
@@ -167,8 +167,8 @@ int launch_kv_quant(const void* x, int x_dtype, int64_t rows, int64_t d, int bit
     uint8_t* out = static_cast<uint8_t*>(packed);
     const bool bf = x_dtype == HBL_BF16;
 #define HBL_KVQ(B)                                                                                               \
-    if (bf) hipLaunchKernelGGL((kv_quant_kernel<B, true>), grid, block, 0, stream, x, threads, lpr, eps, out, scales); \
-    else hipLaunchKernelGGL((kv_quant_kernel<B, false>), grid, block, 0, stream, x, threads, lpr, eps, out, scales);
+    if (bf) launch_kernel("kv_quant_kernel", (kv_quant_kernel<B, true>), grid, block, 0, stream, x, threads, lpr, eps, out, scales); \
+    else launch_kernel("kv_quant_kernel", (kv_quant_kernel<B, false>), grid, block, 0, stream, x, threads, lpr, eps, out, scales);
     if (bits == 8) { HBL_KVQ(8) } else if (bits == 4) { HBL_KVQ(4) } else { HBL_KVQ(3) }
 #undef HBL_KVQ
     return after_launch();
@@ -183,8 +183,8 @@ int launch_kv_dequant(const void* packed, const float* scales, int64_t rows, int
     const uint8_t* in = static_cast<const uint8_t*>(packed);
     const bool bf = out_dtype == HBL_BF16;
 #define HBL_KVD(B)                                                                                              \
-    if (bf) hipLaunchKernelGGL((kv_dequant_kernel<B, true>), grid, block, 0, stream, in, scales, threads, lpr, out);  \
-    else hipLaunchKernelGGL((kv_dequant_kernel<B, false>), grid, block, 0, stream, in, scales, threads, lpr, out);
+    if (bf) launch_kernel("kv_dequant_kernel", (kv_dequant_kernel<B, true>), grid, block, 0, stream, in, scales, threads, lpr, out);  \
+    else launch_kernel("kv_dequant_kernel", (kv_dequant_kernel<B, false>), grid, block, 0, stream, in, scales, threads, lpr, out);
     if (bits == 8) { HBL_KVD(8) } else if (bits == 4) { HBL_KVD(4) } else { HBL_KVD(3) }
 #undef HBL_KVD
     return after_launch();

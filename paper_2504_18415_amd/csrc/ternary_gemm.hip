@@ -12,8 +12,6 @@
 // sum_k q[t][k] (the per-token code sum written by the quantiser kernel) is subtracted in the
 // epilogue, all in int32.  Both operands are staged through LDS with direct global->LDS 16-byte
 // loads, NSTAGE deep: codes into an XOR-swizzled [token][128 B] layout, weights tile by tile.
-#include <stdlib.h>
-
 #include <atomic>
 #include <type_traits>
 
@@ -366,6 +364,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs a) {
         v4i sum = {0, 0, 0, 0};
         for (int k = 0; k < a.split_k; ++k)
             sum += *reinterpret_cast<const v4i*>(a.partial + ((size_t)k * a.T + t) * a.N + n);
+        if (a.acc_out) {   // raw export: the integer sum itself
+            *reinterpret_cast<v4i*>(a.acc_out + (size_t)t * a.N + n) = sum;
+            continue;
+        }
         *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) =
             dequant_quad(sum, a.code_sum ? a.code_sum[t] : 0, a.s_dequant[t], a.w_scales[n / a.rows_per_group], a.code_offset,
                          a.w_row_sum + n, a.K);
@@ -378,7 +380,7 @@ int launch_splitk_reduce(const GemmArgs& a, hipStream_t stream) {
     const int64_t quads = (int64_t)a.T * (a.N / 4);
     int64_t blocks = (quads + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
+    launch_kernel("splitk_reduce_kernel", splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, a);
     return after_launch();
 }
 }  // namespace gemm
@@ -395,24 +397,15 @@ int launch_cfg(GemmArgs a, hipStream_t stream) {
     auto kern = ternary_gemm_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, RAW, SPLIT, OCC>;
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t * a.split_k)), dim3(64 * WAVES_N * WAVES_T), lds,
+    launch_kernel("ternary_gemm_kernel", kern, dim3((unsigned)(a.tiles_n * a.tiles_t * a.split_k)), dim3(64 * WAVES_N * WAVES_T), lds,
                        stream, a);
     int rc = after_launch();
     if (rc != HBL_OK || !SPLIT || a.split_k == 1) return rc;
     return launch_splitk_reduce(a, stream);
 }
 
-// Developer override for tile-shape experiments: HBL_GEMM_TILE=<index into the table below>.
-int tile_override() {
-    static const int v = [] {
-        const char* e = getenv("HBL_GEMM_TILE");
-        return e ? atoi(e) : -1;
-    }();
-    return v;
-}
-
 template <bool RAW>
-int choose(const GemmArgs& a, hipStream_t stream) {
+int choose(const GemmArgs& a, hipStream_t stream, int tile) {
     const int64_t big_tiles = (int64_t)((a.N + 255) / 256) * ((a.T + 255) / 256);
     int cfg;
     if (a.T <= 64 && a.partial != nullptr && !RAW) cfg = a.T <= 32 ? 6 : 7;
@@ -425,7 +418,12 @@ int choose(const GemmArgs& a, hipStream_t stream) {
         const int64_t wide_tiles = (int64_t)((a.N + 511) / 512) * ((a.T + 127) / 128);
         cfg = wide_tiles <= big_tiles ? 4 : 3;
     } else cfg = 2;
-    if (tile_override() >= 0 && tile_override() <= 4 && cfg < 6) cfg = tile_override();
+    if (tile != kTileAuto && cfg < 6) {   // parity tests name the tile of the unsplit kernel themselves
+        if (tile == kTileSquare) cfg = 3;
+        else if (tile == kTileSmall) cfg = 2;
+        else if (tile == kTileWide) cfg = 4;
+        else return HBL_E_SHAPE;
+    }
     switch (cfg) {
         case 0: return launch_cfg<4, 1, 2, 1, 4, RAW>(a, stream);   // 256 features x 32 tokens, 4 waves
         case 1: return launch_cfg<4, 1, 2, 2, 4, RAW>(a, stream);   // 256 x 64, 4 waves
@@ -444,7 +442,7 @@ int choose(const GemmArgs& a, hipStream_t stream) {
 int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,
                         const float* s_dequant, const int32_t* code_sum, const float* w_scales,
                         int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, int32_t* splitk_partial,
-                        hipStream_t stream) {
+                        hipStream_t stream, int tile) {
     if (T == 0) return HBL_OK;
     GemmArgs a;
     a.codes = codes;
@@ -463,7 +461,7 @@ int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t
     a.tiles_n = a.tiles_t = 0;
     a.split_k = splitk_partial ? (T <= 64 ? decode_split_k(T, K, N) : prefill_split_k(T, K, N)) : 1;
     a.partial = splitk_partial;
-    return acc_out ? choose<true>(a, stream) : choose<false>(a, stream);
+    return acc_out ? choose<true>(a, stream, tile) : choose<false>(a, stream, tile);
 }
 
 }  // namespace hbl

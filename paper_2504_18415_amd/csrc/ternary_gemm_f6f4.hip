@@ -13,8 +13,6 @@
 //     stage is 128 bytes as before and an operand is one 16-byte + one 8-byte LDS read;
 //   - weights come from the second packed form (sign / magnitude bit pairs): two AND and one shift
 //     turn a packed dword into two operand registers of eight fp4 values each.
-#include <stdlib.h>
-
 #include <atomic>
 #include <type_traits>
 
@@ -29,7 +27,10 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 // SPLIT: workgroup (tile, ks) covers K-blocks [ks * nkb/split_k, (ks+1) * nkb/split_k) and leaves its accumulators,
 // converted to int32 (they are exact integers), in partial[ks][T][N] for the reduction launch.
-template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool SPLIT = false>
+// RAW: the accumulators themselves leave the kernel, as int32 [T, N] (acc_out), with no dequantisation: the
+// export the parity tests compare with the integer contraction of Eq. 7 bit for bit.  With SPLIT the partial
+// tiles are int32 either way and the reduction launch writes their sum undequantised.
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool SPLIT = false, bool RAW = false>
 __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kernel(const GemmArgs a) {
     constexpr int NW = WAVES_N * WAVES_T;
     constexpr int BN = WAVES_N * TN * 32;
@@ -249,20 +250,21 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
     // epilogue reuses them
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    if constexpr (SPLIT) {
-        if (a.split_k > 1) {   // int32 partial tiles, stored from where the accumulators are (a small volume)
+    if constexpr (SPLIT || RAW) {
+        if (RAW || a.split_k > 1) {   // int32 tiles, stored from where the accumulators are
+            int32_t* const out = (SPLIT && a.split_k > 1) ? a.partial + (size_t)ks * a.T * a.N : a.acc_out;
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TT; ++j) {
+                    __builtin_amdgcn_sched_barrier(0);   // one accumulator tile at a time (register pressure)
                     const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int n = n0 + (wn * TN + i) * 32 + 8 * g + 4 * (lane >> 5);
                         const v4i o = {(int)acc[i][j][4 * g], (int)acc[i][j][4 * g + 1], (int)acc[i][j][4 * g + 2],
                                        (int)acc[i][j][4 * g + 3]};
-                        if (t < a.T && n < a.N)
-                            *reinterpret_cast<v4i*>(a.partial + ((size_t)ks * a.T + t) * a.N + n) = o;
+                        if (t < a.T && n < a.N) *reinterpret_cast<v4i*>(out + (size_t)t * a.N + n) = o;
                     }
                 }
             return;
@@ -324,7 +326,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
     }
 }
 
-template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool SPLIT = false>
+template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool SPLIT = false, bool RAW = false>
 int launch_cfg(GemmArgs a, hipStream_t stream) {
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int BT = WAVES_T * TT * 32;
@@ -332,10 +334,10 @@ int launch_cfg(GemmArgs a, hipStream_t stream) {
     a.tiles_n = (a.N + BN - 1) / BN;
     a.tiles_t = (a.T + BT - 1) / BT;
     if (!SPLIT) a.split_k = 1;
-    auto kern = ternary_gemm_f6f4_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, SPLIT>;
+    auto kern = ternary_gemm_f6f4_kernel<WAVES_N, WAVES_T, TN, TT, NSTAGE, SPLIT, RAW>;
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(a.tiles_n * a.tiles_t * a.split_k)), dim3(64 * WAVES_N * WAVES_T), lds,
+    launch_kernel("ternary_gemm_f6f4_kernel", kern, dim3((unsigned)(a.tiles_n * a.tiles_t * a.split_k)), dim3(64 * WAVES_N * WAVES_T), lds,
                        stream, a);
     const int rc = after_launch();
     if (rc != HBL_OK || a.split_k == 1) return rc;
@@ -346,7 +348,7 @@ int launch_cfg(GemmArgs a, hipStream_t stream) {
 
 int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, const void* packed, int64_t N,
                              const float* s_dequant, const float* w_scales, int64_t n_scale_groups, void* y_bf16,
-                             hipStream_t stream, int32_t* splitk_partial) {
+                             hipStream_t stream, int32_t* splitk_partial, int32_t* acc_out, int tile) {
     if (T == 0) return HBL_OK;
     GemmArgs a = {};
     a.codes = code_records;
@@ -354,6 +356,7 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
     a.s_dequant = s_dequant;
     a.w_scales = w_scales;
     a.y = static_cast<uint16_t*>(y_bf16);
+    a.acc_out = acc_out;
     a.T = (int)T;
     a.K = (int)K;
     a.N = (int)N;
@@ -369,18 +372,28 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
     // (192 big tiles measured 8 % faster than 768 tiles of 128 x 128).
     const int64_t tiles_sq = (int64_t)((N + 255) / 256) * ((T + 255) / 256);
     const int64_t tiles_wide = (int64_t)((N + 511) / 512) * ((T + 127) / 128);
-    static const int override_tile = [] {
-        const char* e = getenv("HBL_GEMM_F6F4_TILE");
-        return e ? atoi(e) : -1;
-    }();
-    int cfg = tiles_sq >= 180 ? (tiles_wide <= tiles_sq ? 2 : 0) : 1;
-    if (override_tile >= 0) cfg = override_tile;
-    if (a.split_k > 1 && override_tile < 0) return launch_cfg<2, 2, 2, 2, 4, true>(a, stream);   // mid-size batch
-    a.split_k = 1;
+    int cfg = tiles_sq >= 180 ? (tiles_wide <= tiles_sq ? kTileWide : kTileSquare) : kTileSmall;
+    if (a.split_k > 1) cfg = kTileSplitK;   // mid-size batch, long K
+    if (tile != kTileAuto) {                // parity tests name the tile themselves
+        cfg = tile;
+        if (cfg == kTileSplitK) {
+            if (!splitk_partial) return HBL_E_WORKSPACE;
+            // any power-of-two cut that leaves whole K-blocks; the forward's own choice when it has one
+            if (a.split_k == 1) a.split_k = (K / 128) % 4 == 0 ? 4 : ((K / 128) % 2 == 0 ? 2 : 1);
+        }
+    }
+    if (cfg == kTileSplitK && a.split_k <= 1) cfg = kTileSmall;   // nothing to cut: the same tile, unsplit
+    if (cfg != kTileSplitK) a.split_k = 1;
+    const bool raw = acc_out != nullptr;
     switch (cfg) {
-        case 0: return launch_cfg<2, 2, 4, 4, 3>(a, stream);   // 256 x 256, 2 x 2 waves of 128 x 128
-        case 1: return launch_cfg<2, 2, 2, 2, 4>(a, stream);   // 128 x 128
-        case 2: return launch_cfg<4, 1, 4, 4, 3>(a, stream);   // 512 features x 128 tokens, 4 x 1 waves of 128 x 128
+        case kTileSquare:   // 256 x 256, 2 x 2 waves of 128 x 128
+            return raw ? launch_cfg<2, 2, 4, 4, 3, false, true>(a, stream) : launch_cfg<2, 2, 4, 4, 3>(a, stream);
+        case kTileSmall:    // 128 x 128
+            return raw ? launch_cfg<2, 2, 2, 2, 4, false, true>(a, stream) : launch_cfg<2, 2, 2, 2, 4>(a, stream);
+        case kTileWide:     // 512 features x 128 tokens, 4 x 1 waves of 128 x 128
+            return raw ? launch_cfg<4, 1, 4, 4, 3, false, true>(a, stream) : launch_cfg<4, 1, 4, 4, 3>(a, stream);
+        case kTileSplitK:   // 128 x 128, K cut over workgroups, int32 partial tiles + reduction launch
+            return launch_cfg<2, 2, 2, 2, 4, true>(a, stream);
         default: return HBL_E_SHAPE;
     }
 }

@@ -180,36 +180,36 @@ int launch_ternarize(const float* W, int64_t count, float eps, int8_t* codes, fl
                      hipStream_t stream) {
     double* partial = static_cast<double*>(workspace);
     const int64_t nb = sum_blocks(count);
-    hipLaunchKernelGGL(abs_sum_partial_kernel, dim3((unsigned)nb), dim3(kSumBlock), 0, stream, W, count, partial);
+    launch_kernel("abs_sum_partial_kernel", abs_sum_partial_kernel, dim3((unsigned)nb), dim3(kSumBlock), 0, stream, W, count, partial);
     int rc = after_launch();
     if (rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(abs_mean_final_kernel, dim3(1), dim3(256), 0, stream, partial, nb, count, alpha);
+    launch_kernel("abs_mean_final_kernel", abs_mean_final_kernel, dim3(1), dim3(256), 0, stream, partial, nb, count, alpha);
     rc = after_launch();
     if (rc != HBL_OK) return rc;
     int64_t blocks = (count + 255) / 256;
     if (blocks > 16384) blocks = 16384;
-    hipLaunchKernelGGL(ternarize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, W, count, alpha, eps, codes);
+    launch_kernel("ternarize_kernel", ternarize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, W, count, alpha, eps, codes);
     return after_launch();
 }
 
 int launch_pack(const int8_t* codes, int64_t N, int64_t K, void* packed, hipStream_t stream) {
     const int64_t total = (N / 32) * (K / 128) * 256;
-    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
+    launch_kernel("pack_kernel", pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
                        static_cast<uint32_t*>(packed));
     int rc = after_launch();
     if (rc != HBL_OK) return rc;
     int32_t* row_sum = reinterpret_cast<int32_t*>(static_cast<char*>(packed) + packed_tile_bytes(N, K));
-    hipLaunchKernelGGL(row_sum_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, codes, N, K, row_sum);
+    launch_kernel("row_sum_kernel", row_sum_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, codes, N, K, row_sum);
     rc = after_launch();
     if (rc != HBL_OK) return rc;
-    hipLaunchKernelGGL(pack_f4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
+    launch_kernel("pack_f4_kernel", pack_f4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
                        reinterpret_cast<uint32_t*>(static_cast<char*>(packed) + packed_f4_offset(N, K)));
     return after_launch();
 }
 
 int launch_unpack(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream) {
     const int64_t total = (N / 32) * (K / 128) * 256;
-    hipLaunchKernelGGL(unpack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+    launch_kernel("unpack_kernel", unpack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
                        static_cast<const uint32_t*>(packed), N, K, codes);
     return after_launch();
 }

@@ -30,9 +30,13 @@ EXPORTS = [
     "hbl_packed_bytes", "hbl_pack_ternary_2bit", "hbl_unpack_ternary_2bit", "hbl_workspace_bytes",
     "hbl_hbitlinear_forward", "hbl_plain_bitlinear_forward", "hbl_fwht_quant", "hbl_gemm_i32",
     "hbl_gemm_dequant_bf16", "hbl_grouped_workspace_bytes", "hbl_bitlinear_forward_grouped", "hbl_fwht",
-    "hbl_ln_bitlinear_forward", "hbl_ln_fwht_quant", "hbl_debug_grouped_plan",
-    "hbl_kv_packed_bytes", "hbl_kv_quant_absmax", "hbl_kv_dequant",
+    "hbl_ln_bitlinear_forward", "hbl_ln_fwht_quant", "hbl_gemm_i32_bf6",
+    "hbl_kv_packed_bytes", "hbl_kv_quant_absmax", "hbl_kv_dequant", "hbl_trace_begin", "hbl_trace_end",
+    "hbl_code_bytes",
 ]
+# exports for the test suite only (csrc/hbl_test_exports.h)
+TEST_EXPORTS = ["hbl_test_grouped_plan", "hbl_test_gemm_i32_tile"]
+TILE_SQUARE, TILE_SMALL, TILE_WIDE, TILE_SPLIT_K = 0, 1, 2, 3
 
 _lib = None
 
@@ -89,7 +93,13 @@ def lib():
         L.hbl_kv_quant_absmax.argtypes = [vp, ci, i64, i64, ci, ctypes.c_float, vp, vp, vp]
         L.hbl_kv_dequant.argtypes = [vp, vp, i64, i64, ci, vp, ci, vp]
         ip = ctypes.POINTER(ci)
-        L.hbl_debug_grouped_plan.argtypes = [ctypes.POINTER(Problem), ci, ip, ip, ip, ip]
+        L.hbl_test_grouped_plan.argtypes = [ctypes.POINTER(Problem), ci, ip, ip, ip, ip]
+        L.hbl_test_gemm_i32_tile.argtypes = [vp, ci, i64, i64, vp, i64, vp, ci, vp, sz, vp]
+        L.hbl_gemm_i32_bf6.argtypes = [vp, i64, i64, vp, i64, vp, vp, sz, vp]
+        L.hbl_code_bytes.restype = sz
+        L.hbl_code_bytes.argtypes = [i64, i64, ci]
+        L.hbl_trace_begin.argtypes = [ci]
+        L.hbl_trace_end.argtypes = [ctypes.POINTER(f32), ctypes.POINTER(ctypes.c_char_p), ci, ip]
         L.hbl_ln_bitlinear_forward.argtypes = [vp, ci, i64, i64, vp, f32, ci, vp, i64, vp, i64, ci, f32, vp, vp, sz, vp]
         L.hbl_ln_fwht_quant.argtypes = [vp, ci, i64, i64, vp, f32, ci, f32, ci, ci, vp, vp, vp, vp]
         L.hbl_grouped_workspace_bytes.restype = sz
@@ -124,6 +134,22 @@ def _dev_check(*ts):
     for t in ts:
         if t is not None and (not t.is_cuda or not t.is_contiguous()):
             raise ValueError("tensors must be contiguous device tensors")
+
+
+def _check_projection(T, K, N, Wq_packed, w_scales, y, workspace=None):
+    """Sizes and dtypes the kernels rely on and cannot see through raw pointers: a short packed buffer or
+    output would make them read or write out of bounds on the device."""
+    if N <= 0 or K <= 0:
+        raise ValueError(f"N and K must be positive (N={N}, K={K})")
+    if Wq_packed.dtype != torch.uint8 or Wq_packed.numel() < packed_bytes(N, K):
+        raise ValueError(f"Wq_packed must be uint8 with at least packed_bytes({N}, {K}) = {packed_bytes(N, K)} "
+                         f"elements (got {Wq_packed.dtype}, {Wq_packed.numel()})")
+    if w_scales.dtype != torch.float32 or w_scales.numel() < 1:
+        raise ValueError("w_scales must be a non-empty float32 tensor")
+    if y is not None and (y.dtype != torch.bfloat16 or tuple(y.shape) != (T, N)):
+        raise ValueError(f"y must be bfloat16 [{T}, {N}] (got {y.dtype} {tuple(y.shape)})")
+    if workspace is not None and workspace.dtype != torch.uint8:
+        raise ValueError("workspace must be a uint8 tensor")
 
 
 def ternarize_weights_absmean(W: torch.Tensor, eps: float = EPS) -> Tuple[torch.Tensor, torch.Tensor]:
@@ -169,6 +195,7 @@ def alloc_workspace(T: int, K: int, N: int, bits: int, device="cuda") -> torch.T
 def _forward(fn, name, x, Wq_packed, N, w_scales, bits, eps, y, workspace):
     _dev_check(x, Wq_packed, w_scales, y, workspace)
     T, K = x.shape
+    _check_projection(T, K, N, Wq_packed, w_scales, y, workspace)
     if y is None:
         y = torch.empty((T, N), dtype=torch.bfloat16, device=x.device)
     if workspace is None:
@@ -194,6 +221,10 @@ def plain_bitlinear_forward(x: torch.Tensor, Wq_packed: torch.Tensor, N: int, w_
                     eps, y, workspace)
 
 
+def code_bytes(T: int, K: int, code_form: int) -> int:
+    return int(lib().hbl_code_bytes(T, K, code_form))
+
+
 def fwht_quant(x: torch.Tensor, bits: int, hadamard: bool = True, eps: float = EPS, code_offset: int = 0):
     """Eq. 3-6 only -> (codes int8 [T,K] stored as code+code_offset, s_dequant fp32 [T], code_sum int32 [T])."""
     _dev_check(x)
@@ -210,9 +241,66 @@ def gemm_i32(codes: torch.Tensor, Wq_packed: torch.Tensor, N: int) -> torch.Tens
     """acc int32 [T,N] = codes [T,K] . c^T (exact)."""
     _dev_check(codes, Wq_packed)
     T, K = codes.shape
+    _check_projection(T, K, N, Wq_packed, torch.empty(1), None)
     acc = torch.empty((T, N), dtype=torch.int32, device=codes.device)
     _check(lib().hbl_gemm_i32(_ptr(codes), T, K, _ptr(Wq_packed), N, _ptr(acc), _stream()), "gemm_i32")
     return acc
+
+
+def gemm_i32_bf6(records: torch.Tensor, Wq_packed: torch.Tensor, N: int,
+                 workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """acc int32 [T,N] from bf6 code records [T,K] on the fp6 x fp4 kernel, in the forward call's own launch
+    configuration for the shape (exact integers read out of its fp32 accumulators)."""
+    _dev_check(records, Wq_packed, workspace)
+    T, K = records.shape
+    _check_projection(T, K, N, Wq_packed, torch.empty(1), None, workspace)
+    acc = torch.empty((T, N), dtype=torch.int32, device=records.device)
+    if workspace is None:
+        workspace = alloc_workspace(T, K, N, 4, records.device)
+    _check(lib().hbl_gemm_i32_bf6(_ptr(records), T, K, _ptr(Wq_packed), N, _ptr(acc), _ptr(workspace),
+                                  workspace.numel(), _stream()), "gemm_i32_bf6")
+    return acc
+
+
+def gemm_i32_tile_for_tests(codes: torch.Tensor, code_form: int, Wq_packed: torch.Tensor, N: int, tile: int) -> torch.Tensor:
+    """Test-suite export: the integer contraction through one named workgroup tile (TILE_*) of the int8
+    (``CODES_INT8``) or fp6 x fp4 (``CODES_BF6``) prefill kernel."""
+    _dev_check(codes, Wq_packed)
+    T, K = codes.shape
+    _check_projection(T, K, N, Wq_packed, torch.empty(1), None)
+    acc = torch.empty((T, N), dtype=torch.int32, device=codes.device)
+    partial = torch.empty(8 * T * N * 4 if tile == TILE_SPLIT_K else 16, dtype=torch.uint8, device=codes.device)
+    _check(lib().hbl_test_gemm_i32_tile(_ptr(codes), code_form, T, K, _ptr(Wq_packed), N, _ptr(acc), tile,
+                                        _ptr(partial), partial.numel(), _stream()), "test_gemm_i32_tile")
+    return acc
+
+
+class trace:
+    """``with hbl.trace(n) as tr: ...`` - per-launch kernel durations of the library calls made inside the
+    block (hbl_trace_begin / hbl_trace_end).  Afterwards ``tr.launches`` is a list of (kernel name, ms) in
+    launch order and ``tr.seen`` the number of launches (those beyond ``n`` are not timed)."""
+
+    def __init__(self, max_launches: int):
+        self.n = int(max_launches)
+        self.launches, self.seen = [], 0
+
+    def __enter__(self):
+        _check(lib().hbl_trace_begin(self.n), "trace_begin")
+        return self
+
+    def __exit__(self, *exc):
+        ms = (ctypes.c_float * self.n)()
+        names = (ctypes.c_char_p * self.n)()
+        seen = ctypes.c_int(0)
+        _check(lib().hbl_trace_end(ms, names, self.n, ctypes.byref(seen)), "trace_end")
+        self.seen = seen.value
+        k = min(self.seen, self.n)
+        self.launches = [((names[i] or b"?").decode(), float(ms[i])) for i in range(k)]
+        return False
+
+    def mean_ms(self, kernel: str) -> float:
+        v = [ms for name, ms in self.launches if name == kernel]
+        return sum(v) / len(v) if v else float("nan")
 
 
 def gemm_dequant_bf16(codes: torch.Tensor, s_dequant: torch.Tensor, code_sum: torch.Tensor, Wq_packed: torch.Tensor,
@@ -221,6 +309,10 @@ def gemm_dequant_bf16(codes: torch.Tensor, s_dequant: torch.Tensor, code_sum: to
     """Second launch of the forward on caller-held intermediates: y bf16 [T,N]."""
     _dev_check(codes, s_dequant, code_sum, Wq_packed, w_scales, y)
     T, K = codes.shape
+    _check_projection(T, K, N, Wq_packed, w_scales, y)
+    if (s_dequant.dtype != torch.float32 or s_dequant.numel() < T or code_sum.dtype != torch.int32
+            or code_sum.numel() < T):
+        raise ValueError("s_dequant must be float32 [T] and code_sum int32 [T]")
     if y is None:
         y = torch.empty((T, N), dtype=torch.bfloat16, device=codes.device)
     _check(lib().hbl_gemm_dequant_bf16(_ptr(codes), code_offset, _ptr(s_dequant), _ptr(code_sum), T, K, _ptr(Wq_packed), N,
@@ -245,6 +337,9 @@ def make_problems(items) -> "ctypes.Array":
         ln_gain, ln_eps = (it[7], it[8]) if len(it) > 7 else (None, 0.0)
         _dev_check(x, Wq_packed, w_scales, y, ln_gain)
         T, K = x.shape
+        _check_projection(T, K, N, Wq_packed, w_scales, y)
+        if ln_gain is not None and (ln_gain.dtype != torch.float32 or ln_gain.numel() != K):
+            raise ValueError("ln_gain must be float32 [K]")
         arr[i] = Problem(_ptr(x), _x_dtype(x), bits, int(bool(hadamard)), 0, T, K, N, _ptr(Wq_packed),
                          _ptr(w_scales), w_scales.numel(), _ptr(y), _ptr(ln_gain), ln_eps)
     return arr
@@ -289,6 +384,9 @@ def ln_bitlinear_forward(x: torch.Tensor, ln_gain: torch.Tensor, ln_eps: float, 
     """Eq. 7 with its LN (RMS normalisation with gain ``ln_gain`` [K] fp32) fused into the quantiser launch."""
     _dev_check(x, ln_gain, Wq_packed, w_scales, y, workspace)
     T, K = x.shape
+    _check_projection(T, K, N, Wq_packed, w_scales, y, workspace)
+    if ln_gain.dtype != torch.float32 or ln_gain.numel() != K:
+        raise ValueError("ln_gain must be float32 [K]")
     if y is None:
         y = torch.empty((T, N), dtype=torch.bfloat16, device=x.device)
     if workspace is None:
@@ -320,13 +418,13 @@ def grouped_plan(shapes):
     ks = (ctypes.c_int * n)()
     st = (ctypes.c_int * n)()
     wgs, red = ctypes.c_int(0), ctypes.c_int(0)
-    _check(lib().hbl_debug_grouped_plan(arr, n, ks, ctypes.byref(wgs), ctypes.byref(red), st), "grouped_plan")
+    _check(lib().hbl_test_grouped_plan(arr, n, ks, ctypes.byref(wgs), ctypes.byref(red), st), "grouped_plan")
     return list(ks), wgs.value, red.value, [bool(v) for v in st]
 
 
 def kv_quant_absmax(x: torch.Tensor, bits: int, eps: float = EPS, packed: Optional[torch.Tensor] = None,
                     scales: Optional[torch.Tensor] = None):
-    """Low-bit head states (Section 3.2): x [rows, d] -> (packed uint8 [rows, d*bits/8], scales fp32 [rows])."""
+    """Low-bit head states (Section 3.1, Main Results): x [rows, d] -> (packed uint8 [rows, d*bits/8], scales fp32 [rows])."""
     _dev_check(x)
     rows, d = x.shape
     nbytes = lib().hbl_kv_packed_bytes(rows, d, bits)

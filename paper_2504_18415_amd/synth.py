@@ -155,6 +155,13 @@ def config_sites(cfg: int, batch: int = 64, layer: int = 0) -> List[Site]:
     raise ValueError(f"unknown config {cfg}")
 
 
+def config4_wdown_swiglu() -> Site:
+    """Parity-only variant of the configuration-4 W_down site: the same shape, weights and outlier channels,
+    with the input drawn as a gated-activation output, SiLU(a)*b, instead of a Gaussian (the configuration's
+    wording allows both readings: "as in config 3" names the SwiGLU draw, its parenthesis the Gaussian one)."""
+    return replace(config_sites(4)[1], name="wdown_7b_swiglu", x_kind="swiglu", x_stream=2)
+
+
 def shrink(site: Site, T: int | None = None, K: int | None = None, N: int | None = None) -> Site:
     """Same recipe at a smaller shape (parity cases the oracle finishes in seconds)."""
     return replace(site, T=T or site.T, K=K or site.K, N=N or site.N)

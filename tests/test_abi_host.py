@@ -32,6 +32,11 @@ def test_every_declared_symbol_is_exported(L):
     for n in names:
         assert hasattr(L, n), n
     assert sorted(hbl.EXPORTS) == names
+    for n in hbl.TEST_EXPORTS:                      # test-suite exports: csrc/hbl_test_exports.h, not the public header
+        assert hasattr(L, n) and n not in names, n
+    test_hdr = open(os.path.join(ROOT, "paper_2504_18415_amd", "csrc", "hbl_test_exports.h")).read()
+    test_hdr = re.sub(r"/\*.*?\*/", "", test_hdr, flags=re.S)
+    assert sorted(set(re.findall(r"\b(hbl_[a-z0-9_]+)\s*\(", test_hdr))) == sorted(hbl.TEST_EXPORTS)
 
 
 def test_status_text(L):
@@ -46,6 +51,7 @@ def test_size_queries(L):
     ws = L.hbl_workspace_bytes(8192, 16384, 4096, 4)
     assert ws >= 8192 * 16384 + 8 * 8192 and ws % 256 == 0
     assert L.hbl_workspace_bytes(17, 256, 256, 8) >= 17 * 256 + 8 * 17
+    assert L.hbl_workspace_bytes(17, 256, 0, 8) == 256 and L.hbl_workspace_bytes(17, 256, -32, 8) == 256
     # a mid-size batch on a long K brings room for the split-K partial tiles (4 slices of [T, N] int32 here)
     assert L.hbl_workspace_bytes(256, 16384, 4096, 4) >= 256 * 16384 + 4 * 256 * 4096 * 4
     assert L.hbl_workspace_bytes(256, 4096, 4096, 4) < 256 * 4096 + 256 * 4096 * 4
@@ -199,3 +205,28 @@ def test_kv_quant_argument_errors_before_any_launch(L):
     assert dq(a, None, 4, 128, 3, a, hbl.F32) == E["E_NULL"]
     assert dq(a, a, 4, 128, 3, a + 8, hbl.F32) == E["E_ALIGN"]
     assert dq(None, None, 0, 128, 3, None, hbl.F32) == 0
+
+
+def test_trace_calls_without_a_gpu(L):
+    """The timing trace is host state: opening, nesting and closing it needs no device (events are created
+    lazily only when a count is asked for, so keep it to the error paths here)."""
+    n = ctypes.c_int(-1)
+    assert L.hbl_trace_end(None, None, 0, ctypes.byref(n)) == -2          # no open trace
+    assert L.hbl_trace_begin(0) == -2 and L.hbl_trace_begin(-5) == -2
+
+
+def test_raw_accumulator_exports_reject_bad_arguments(L):
+    P = ctypes.c_void_p(0x10000)
+    NUL = ctypes.c_void_p(0)
+    f = L.hbl_gemm_i32_bf6
+    assert f(P, 128, 256, P, 64, P, P, 1 << 30, NUL) == -2                 # records need K >= 512
+    assert f(P, 128, 1024, P, 48, P, P, 1 << 30, NUL) == -2                # N not a multiple of 32
+    assert f(NUL, 128, 1024, P, 64, P, P, 1 << 30, NUL) == -1
+    assert f(P, 128, 1024, P, 64, P, P, 16, NUL) == -5                     # workspace too small
+    assert f(P, 0, 1024, P, 64, P, P, 0, NUL) == 0                         # empty batch
+    g = L.hbl_test_gemm_i32_tile
+    assert g(P, 6, 32, 1024, P, 64, P, 1, NUL, 0, NUL) == -2               # prefill tiles: T > 64
+    assert g(P, 8, 128, 1024, P, 64, P, 1, NUL, 0, NUL) == -3              # code form
+    assert g(P, 6, 128, 1024, P, 64, P, 7, NUL, 0, NUL) == -2              # tile
+    assert g(P, 0, 128, 1024, P, 64, P, 3, P, 1 << 30, NUL) == -2          # K cut: fp6 x fp4 kernel only
+    assert g(P, 6, 128, 1024, P, 64, P, 3, NUL, 0, NUL) == -5              # K cut needs the partial buffer

@@ -109,7 +109,7 @@ def test_ternarize_and_pack_roundtrip(hbl, N, K):
     assert a_dev.cpu().numpy()[0] == a_ref
     assert np.array_equal(c_dev.cpu().numpy(), c_ref)
     packed = hbl.pack_ternary_2bit(c_dev)
-    assert packed.numel() == N * K // 2 + 4 * N          # two 2-bit forms + int32 row sums
+    assert packed.numel() == hbl.packed_bytes(N, K)
     row_sums = packed[N * K // 4:N * K // 4 + 4 * N].view(torch.int32).cpu().numpy()
     assert np.array_equal(row_sums, c_ref.astype(np.int32).sum(1))
     back = hbl.unpack_ternary_2bit(packed, N, K)
@@ -406,6 +406,13 @@ def run_site(hbl, site, bits, sample_rows=None):
     y = fn(xd, packed, site.N, al_d, bits, EPS)
     codes, sd, cs = hbl.fwht_quant(xd, bits, site.hadamard, EPS)
     acc = hbl.gemm_i32(codes, packed, site.N)
+    # the forward call above ran the fp6 x fp4 kernel if INT4, T > 64, K >= 512: that kernel's own accumulators,
+    # from the code records it reads, in the launch configuration the forward call takes for this shape
+    acc6 = None
+    if bits == 4 and site.T > 64 and site.K >= 512:
+        rec, _, _ = hbl.fwht_quant(xd, 4, site.hadamard, EPS, code_offset=hbl.CODES_BF6)
+        acc6 = hbl.gemm_i32_bf6(rec, packed, site.N)
+        del rec
     torch.cuda.synchronize()
     rows = np.arange(site.T) if sample_rows is None else sample_rows
     xs = np.ascontiguousarray(x[rows])
@@ -418,6 +425,9 @@ def run_site(hbl, site, bits, sample_rows=None):
     same = (c_got == c_ref).all(axis=1)
     a_got = acc[rows_t].cpu().numpy()
     assert np.array_equal(a_got[same], a_ref[same]), "int32 accumulators differ on rows with identical codes"
+    if acc6 is not None:
+        a6 = acc6[rows_t].cpu().numpy()
+        assert np.array_equal(a6[same], a_ref[same]), "fp6 x fp4 kernel: accumulators differ from the int32 contraction"
     y_bits = host_bf16_bits(y[rows_t])
     mx, mean = rel_err(y_bits, y_ref)
     assert mx <= 1e-2 and mean <= 1e-3, (mx, mean)
@@ -456,21 +466,95 @@ def test_mid_size_batch_split_k(hbl, T, K, N):
     run_site(hbl, synth.shrink(synth.config_sites(4)[1], T=T, K=K, N=N), 8)     # the int8 kernel's split form
 
 
+def panel_rows(T, seed, panel=128):
+    """First and last token row of every `panel`-token workgroup panel of the prefill GEMM launch, plus one
+    seeded row inside each: every workgroup row of the launch has rows under the oracle."""
+    rng = np.random.default_rng(seed)
+    rows = []
+    for p0 in range(0, T, panel):
+        p1 = min(p0 + panel, T) - 1
+        rows += [p0, p1, int(rng.integers(p0, p1 + 1))]
+    return np.unique(np.asarray(rows, dtype=np.int64))
+
+
 def test_config3_full_size_sampled(hbl):
-    note("config 3 full size, sampled rows")
+    note("config 3 full size, rows of every token panel")
     site = synth.config_sites(3)[0]
-    rows = np.sort(np.random.default_rng(3).choice(site.T, 24, replace=False))
-    run_site(hbl, site, 4, sample_rows=rows)
+    rate, exact = run_site(hbl, site, 4, sample_rows=panel_rows(site.T, 3))
+    assert rate == 0 and exact == 1.0
 
 
 @pytest.mark.parametrize("idx", [0, 1])
 def test_config4_full_size_sampled(hbl, idx):
-    """7B prefill sites in the launch configuration the benchmark times; oracle on sampled token rows."""
+    """7B prefill sites in the launch configuration the benchmark times; the oracle on the first, the last and
+    one more token row of every 128-token workgroup panel (all 64 of them), every output of those rows and
+    the timed kernel's own int32 accumulators bit for bit."""
     site = synth.config_sites(4)[idx]
-    note(f"config 4 {site.name} full size, sampled rows")
-    rows = np.sort(np.random.default_rng(4 + idx).choice(site.T, 16, replace=False))
-    rows[0], rows[-1] = 0, site.T - 1
-    run_site(hbl, site, 4, sample_rows=rows)
+    note(f"config 4 {site.name} full size, rows of every token panel")
+    rate, exact = run_site(hbl, site, 4, sample_rows=panel_rows(site.T, 4 + idx))
+    assert rate == 0 and exact == 1.0
+
+
+def test_config4_wdown_swiglu_input(hbl):
+    """Configuration 4's W_down with its input drawn as a gated-activation output SiLU(a)*b (heavy-tailed,
+    mostly small values) and the same 1 % outlier channels x50: parity-only variant of the site above."""
+    site = synth.config4_wdown_swiglu()
+    note("config 4 wdown_7b, SwiGLU-shaped input, rows of every token panel")
+    rate, exact = run_site(hbl, site, 4, sample_rows=panel_rows(site.T, 44))
+    assert rate == 0 and exact == 1.0
+    run_site(hbl, synth.shrink(site, T=200, N=96), 4)            # and every row of a reduced shape
+
+
+@pytest.mark.parametrize("T,K,N", [(300, 1024, 544), (129, 4096, 96), (513, 512, 1056)])
+def test_prefill_gemm_tiles_raw_accumulators(hbl, T, K, N):
+    """Every workgroup tile of both prefill GEMM kernels (256 x 256, 128 x 128, 512 x 128, and the fp6 x fp4
+    kernel's K cut over workgroups) on ragged shapes: the int32 accumulators, read straight out of the
+    kernel, against the oracle's integer contraction - every element, bit for bit."""
+    note(f"prefill GEMM tiles, raw accumulators T={T} K={K} N={N}")
+    rng = np.random.default_rng(T + K + N)
+    q = rng.integers(-8, 8, (T, K)).astype(np.int8)
+    q[3] = -8                                                     # the largest magnitudes the codes can take
+    q[5] = 7
+    c = rng.integers(-1, 2, (N, K)).astype(np.int8)
+    c[1] = 1
+    c[2] = -1
+    want = O.gemm_i32(q, c)
+    packed = hbl.pack_ternary_2bit(torch.from_numpy(c).cuda())
+    rec = torch.from_numpy(encode_bf6_records(q.astype(np.int32)).view(np.int8)).cuda()
+    qd = torch.from_numpy(q).cuda()
+    for tile in (hbl.TILE_SQUARE, hbl.TILE_SMALL, hbl.TILE_WIDE, hbl.TILE_SPLIT_K):
+        got = hbl.gemm_i32_tile_for_tests(rec, hbl.CODES_BF6, packed, N, tile).cpu().numpy()
+        assert np.array_equal(got, want), f"fp6 x fp4 kernel, tile {tile}"
+    q8 = rng.integers(-128, 128, (T, K)).astype(np.int8)
+    want8 = O.gemm_i32(q8, c)
+    q8d = torch.from_numpy(q8).cuda()
+    for tile in (hbl.TILE_SQUARE, hbl.TILE_SMALL, hbl.TILE_WIDE):
+        got = hbl.gemm_i32_tile_for_tests(q8d, hbl.CODES_INT8, packed, N, tile).cpu().numpy()
+        assert np.array_equal(got, want8), f"int8 kernel, tile {tile}"
+        got = hbl.gemm_i32_tile_for_tests(qd, hbl.CODES_INT8, packed, N, tile).cpu().numpy()
+        assert np.array_equal(got, want), f"int8 kernel on INT4 codes, tile {tile}"
+    assert np.array_equal(hbl.gemm_i32_bf6(rec, packed, N).cpu().numpy(), want)      # the forward's own choice
+
+
+def test_f6f4_raw_accumulators_extreme_and_split_k_shapes(hbl):
+    """|acc| = 8 * 16384 = 2^17 out of the fp6 x fp4 kernel as an integer, and the mid-size-batch shapes on
+    which the forward call itself cuts K (8, 4 and 2 slices): raw accumulators against the oracle."""
+    note("f6f4 raw accumulators: extremes and the forward's own K cuts")
+    rng = np.random.default_rng(17)
+    for T, K, N in [(130, 16384, 64), (300, 16384, 1056), (130, 8192, 2048), (513, 16384, 416)]:
+        q = rng.integers(-8, 8, (T, K)).astype(np.int8)
+        q[0] = -8
+        q[T - 1] = 7
+        c = rng.integers(-1, 2, (N, K)).astype(np.int8)
+        c[0] = 1
+        c[N - 1] = -1
+        want = O.gemm_i32(q, c)
+        assert np.abs(want).max() == 8 * K
+        packed = hbl.pack_ternary_2bit(torch.from_numpy(c).cuda())
+        rec = torch.from_numpy(encode_bf6_records(q.astype(np.int32)).view(np.int8)).cuda()
+        assert np.array_equal(hbl.gemm_i32_bf6(rec, packed, N).cpu().numpy(), want), (T, K, N)
+        got = hbl.gemm_i32_tile_for_tests(rec, hbl.CODES_BF6, packed, N, hbl.TILE_SPLIT_K).cpu().numpy()
+        assert np.array_equal(got, want), (T, K, N, "split-K tile")
 
 
 @pytest.mark.parametrize("T,K,N,groups,bits,hadamard", [
@@ -516,7 +600,7 @@ def test_forward_reuses_caller_buffers_and_is_deterministic(hbl):
 def test_empty_batch_and_errors_on_device(hbl):
     note("empty batch / errors")
     x = torch.empty((0, 256), dtype=torch.bfloat16, device="cuda")
-    packed = torch.zeros(256 * 256 // 4, dtype=torch.uint8, device="cuda")
+    packed = torch.zeros(hbl.packed_bytes(256, 256), dtype=torch.uint8, device="cuda")
     al = torch.ones(1, dtype=torch.float32, device="cuda")
     y = hbl.hbitlinear_forward(x, packed, 256, al, 4)
     assert y.shape == (0, 256)
@@ -826,7 +910,7 @@ def test_offsets_beyond_two_to_the_31(hbl):
     torch.cuda.empty_cache()
 
 
-# --- low-bit Q/K/V head states (Section 3.2) -----------------------------------------------------------
+# --- low-bit Q/K/V head states (Section 3.1) -----------------------------------------------------------
 
 @pytest.mark.parametrize("bits", [8, 4, 3])
 @pytest.mark.parametrize("d,rows,dtype", [(128, 4100, synth.BF16), (64, 333, synth.BF16), (256, 77, synth.F32),
@@ -866,3 +950,23 @@ def test_kv_quant_errors_and_empty(hbl):
     assert np.array_equal(np.unpackbits(p.cpu().numpy(), axis=1, bitorder="little").reshape(4, 128, 3),
                           np.broadcast_to(np.array([0, 0, 1], np.uint8), (4, 128, 3)))
     assert np.all(s.cpu().numpy() == 0.0)
+
+
+def test_binding_rejects_short_buffers_before_the_library_sees_them(hbl):
+    """The binding checks what the library cannot see through raw pointers: a packed-weight buffer or an output
+    too small for the stated N would be read or written out of bounds on the device."""
+    note("binding validation")
+    x = torch.zeros((4, 256), dtype=torch.bfloat16, device="cuda")
+    al = torch.ones(1, dtype=torch.float32, device="cuda")
+    good = torch.zeros(hbl.packed_bytes(64, 256), dtype=torch.uint8, device="cuda")
+    with pytest.raises(ValueError):
+        hbl.hbitlinear_forward(x, good[:-16], 64, al, 4)
+    with pytest.raises(ValueError):
+        hbl.hbitlinear_forward(x, good, 128, al, 4)                               # packed for 64 rows, N says 128
+    with pytest.raises(ValueError):
+        hbl.hbitlinear_forward(x, good, 64, al, 4, y=torch.empty((4, 32), dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(ValueError):
+        hbl.hbitlinear_forward(x, good, 64, al.double(), 4)
+    with pytest.raises(ValueError):
+        hbl.bitlinear_forward_grouped([(x, good, 128, al, 4, True, None)])
+    assert hbl.hbitlinear_forward(x, good, 64, al, 4).shape == (4, 64)

@@ -434,7 +434,7 @@ def test_rotating_weights_and_activations_cancels():
     assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
 
 
-# --- Low-bit Q/K/V head states (Section 3.2) ----------------------------------------------------------
+# --- Low-bit Q/K/V head states (Section 3.1) ----------------------------------------------------------
 
 def test_kv_absmax_hand_row(golden):
     c = golden["kv_absmax_hand_row"]
