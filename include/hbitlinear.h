@@ -44,6 +44,7 @@ extern "C" {
 #define HBL_E_WORKSPACE (-5) /* workspace smaller than the matching *_workspace_bytes() */
 #define HBL_E_HIP (-6)       /* a HIP call failed; see hbl_last_hip_error()             */
 #define HBL_E_ALIGN (-7)     /* a pointer is not aligned to 16 bytes                    */
+#define HBL_E_SCRATCH (-8)   /* problem exceeds the static scratch of hbl_bitlinear_forward_small */
 
 /* activation storage types */
 #define HBL_F32 0
@@ -137,6 +138,24 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
                                 const void* Wq_packed, int64_t N, const float* w_scales,
                                 int64_t n_scale_groups, int bits, float eps, void* y,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The forward call for callers that cannot allocate device memory or carry a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation and the same
+ * kernels as hbl_hbitlinear_forward (hadamard != 0) / hbl_plain_bitlinear_forward (hadamard == 0), with
+ * bit-identical output; the intermediates (activation codes, per-token scale and code sum, int32 partial
+ * tiles of a split K range) live in a 13 MiB array in the library's own device image, one copy per GPU,
+ * held until the process ends.  The call allocates nothing and frees nothing.
+ *   Limits: T <= 64 (decode batches) and hbl_workspace_bytes(T, K, N, bits) <= 13 MiB, which covers every
+ *   K <= 16384 with N <= 32768 at T = 64; beyond them HBL_E_SCRATCH and nothing is launched.
+ *   Every call on a GPU shares that GPU's array, on whatever stream: two calls that may run at the same
+ *   time on one GPU race (calls on one stream are ordered and safe).  Nothing in the array has to start
+ *   at zero: a call writes every byte it later reads.
+ * Other arguments, layouts and errors as hbl_hbitlinear_forward.
+ */
+int hbl_bitlinear_forward_small(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed,
+                                int64_t N, const float* w_scales, int64_t n_scale_groups, int bits, float eps,
+                                int hadamard, void* y, void* stream);
 
 /*
  * Eq. 7 including its LN: y = Q_w(W) . Q_INT8/4(X_r), X_r = Hadamard(LN(X)) (hadamard != 0), or

@@ -21,6 +21,34 @@ thread_local TraceState g_trace;
 
 LaunchTrace* current_trace() { return g_trace.open ? &g_trace.view : nullptr; }
 
+// Scratch of hbl_bitlinear_forward_small, the entry point that allocates nothing: it plays the part the
+// caller's workspace plays in the other forward calls (activation codes, per-token scale and code sum, int32
+// partial tiles of a split K range).  One copy per GPU, held until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress: the device address, asked once per device, is what is passed on.
+constexpr size_t kSmallScratchBytes = (size_t)13 << 20;   // largest hbl_workspace_bytes(64, K, N) over K <= 16384, N <= 32768: 12.94 MiB
+static __device__ __align__(256) unsigned char scratch[kSmallScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int scratch_of_current_device(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return note_hip_error(e);
+    if (dev < 0 || dev >= kMaxDevices) return HBL_E_SHAPE;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {   // first call on this device (it is current): every GPU holds its own copy of the array
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return note_hip_error(e);
+        if (p == nullptr) return note_hip_error(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return HBL_OK;
+}
+}  // namespace
+
 int note_hip_error(hipError_t e) {
     g_last_hip_error = (int)e;
     return HBL_E_HIP;
@@ -131,6 +159,7 @@ const char* hbl_strerror(int status) {
         case HBL_E_WORKSPACE: return "workspace too small";
         case HBL_E_HIP: return "a HIP call failed (see hbl_last_hip_error)";
         case HBL_E_ALIGN: return "pointer not sufficiently aligned";
+        case HBL_E_SCRATCH: return "problem too large for the static scratch of the allocation-free entry point (T <= 64, hbl_workspace_bytes <= 13 MiB)";
         default: return "unknown status";
     }
 }
@@ -190,6 +219,22 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
                                 void* workspace, size_t workspace_bytes, void* stream) {
     return forward(x, x_dtype, T, K, Wq_packed, N, w_scales, n_scale_groups, bits, eps, y, workspace,
                    workspace_bytes, stream, false);
+}
+
+int hbl_bitlinear_forward_small(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
+                                const float* w_scales, int64_t n_scale_groups, int bits, float eps, int hadamard,
+                                void* y, void* stream) {
+    // argument errors first (same order as the other forward calls), with a stand-in workspace pointer
+    int rc = check_forward_args(x, x_dtype, T, K, Wq_packed, N, w_scales, n_scale_groups, bits, y,
+                                reinterpret_cast<const void*>(uintptr_t{256}), hadamard != 0);
+    if (rc != HBL_OK) return rc;
+    if (T == 0) return HBL_OK;
+    if (T > 64 || hbl_workspace_bytes(T, K, N, bits) > kSmallScratchBytes) return HBL_E_SCRATCH;
+    void* ws = nullptr;
+    rc = scratch_of_current_device(&ws);
+    if (rc != HBL_OK) return rc;
+    return forward(x, x_dtype, T, K, Wq_packed, N, w_scales, n_scale_groups, bits, eps, y, ws, kSmallScratchBytes,
+                   stream, hadamard != 0);
 }
 
 size_t hbl_grouped_workspace_bytes(const hbl_problem* problems, int n_problems) {

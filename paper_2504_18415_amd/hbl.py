@@ -20,7 +20,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libhbitlinear.so")
 
 OK = 0
-E_NULL, E_SHAPE, E_BITS, E_DTYPE, E_WORKSPACE, E_HIP, E_ALIGN = -1, -2, -3, -4, -5, -6, -7
+E_NULL, E_SHAPE, E_BITS, E_DTYPE, E_WORKSPACE, E_HIP, E_ALIGN, E_SCRATCH = -1, -2, -3, -4, -5, -6, -7, -8
 F32, BF16 = 0, 1
 CODES_INT8, CODES_UINT4_PLUS8, CODES_BF6 = 0, 8, 6
 EPS = 1e-5
@@ -32,7 +32,7 @@ EXPORTS = [
     "hbl_gemm_dequant_bf16", "hbl_grouped_workspace_bytes", "hbl_bitlinear_forward_grouped", "hbl_fwht",
     "hbl_ln_bitlinear_forward", "hbl_ln_fwht_quant", "hbl_gemm_i32_bf6",
     "hbl_kv_packed_bytes", "hbl_kv_quant_absmax", "hbl_kv_dequant", "hbl_trace_begin", "hbl_trace_end",
-    "hbl_code_bytes",
+    "hbl_code_bytes", "hbl_bitlinear_forward_small",
 ]
 # exports for the test suite only (csrc/hbl_test_exports.h)
 TEST_EXPORTS = ["hbl_test_grouped_plan", "hbl_test_gemm_i32_tile"]
@@ -96,6 +96,7 @@ def lib():
         L.hbl_test_grouped_plan.argtypes = [ctypes.POINTER(Problem), ci, ip, ip, ip, ip]
         L.hbl_test_gemm_i32_tile.argtypes = [vp, ci, i64, i64, vp, i64, vp, ci, vp, sz, vp]
         L.hbl_gemm_i32_bf6.argtypes = [vp, i64, i64, vp, i64, vp, vp, sz, vp]
+        L.hbl_bitlinear_forward_small.argtypes = [vp, ci, i64, i64, vp, i64, vp, i64, ci, f32, ci, vp, vp]
         L.hbl_code_bytes.restype = sz
         L.hbl_code_bytes.argtypes = [i64, i64, ci]
         L.hbl_trace_begin.argtypes = [ci]
@@ -223,6 +224,19 @@ def plain_bitlinear_forward(x: torch.Tensor, Wq_packed: torch.Tensor, N: int, w_
 
 def code_bytes(T: int, K: int, code_form: int) -> int:
     return int(lib().hbl_code_bytes(T, K, code_form))
+
+
+def bitlinear_forward_small(x: torch.Tensor, Wq_packed: torch.Tensor, N: int, w_scales: torch.Tensor, y: torch.Tensor,
+                            bits: int = 4, hadamard: bool = True, eps: float = EPS) -> torch.Tensor:
+    """The forward call that allocates nothing (T <= 64; intermediates in the library's static device scratch).
+    ``y`` bf16 [T,N] is the caller's; calls that may overlap on one GPU race."""
+    _dev_check(x, Wq_packed, w_scales, y)
+    T, K = x.shape
+    _check_projection(T, K, N, Wq_packed, w_scales, y)
+    _check(lib().hbl_bitlinear_forward_small(_ptr(x), _x_dtype(x), T, K, _ptr(Wq_packed), N, _ptr(w_scales),
+                                             w_scales.numel(), bits, eps, int(bool(hadamard)), _ptr(y), _stream()),
+           "bitlinear_forward_small")
+    return y
 
 
 def fwht_quant(x: torch.Tensor, bits: int, hadamard: bool = True, eps: float = EPS, code_offset: int = 0):
