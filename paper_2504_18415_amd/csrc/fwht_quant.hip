@@ -176,19 +176,15 @@ __device__ __forceinline__ uint32_t bf6_pack4(uint32_t packed) {
     return (t2 & 0xFFFu) | ((t2 >> 4) & 0xFFF000u);
 }
 
-// bf6 record output for a lane that holds the 8 features of chunk `chunk8` of its row as two 24-bit
+// bf6 record output for a lane that holds the 8 features of chunk `chunk8` of token `row` as two 24-bit
 // halves, where neighbouring lanes hold neighbouring chunks: the even lane of each pair fetches its
-// partner's halves and writes the pair's 16 features as three dwords.  A record covers 32 features
-// (four chunks) in 32 bytes, the last 8 of them unused.  Every lane of a quad must call this.
-__device__ __forceinline__ void bf6_store_pair(int8_t* row_codes, int chunk8, uint32_t lo, uint32_t hi) {
+// partner's halves and stores the pair's 16 features (96 bits) into the record image (code_records.h).
+// Every lane of a quad must call this.
+__device__ __forceinline__ void bf6_store_pair(int8_t* codes, int64_t row, int K, int chunk8, uint32_t lo, uint32_t hi) {
     const uint32_t p_lo = (uint32_t)__builtin_amdgcn_mov_dpp((int)lo, 0xB1, 0xF, 0xF, false);   // lane ^ 1
     const uint32_t p_hi = (uint32_t)__builtin_amdgcn_mov_dpp((int)hi, 0xB1, 0xF, 0xF, false);
-    if ((chunk8 & 1) == 0) {
-        uint32_t* dst = reinterpret_cast<uint32_t*>(row_codes + 32 * (chunk8 >> 2) + 12 * ((chunk8 >> 1) & 1));
-        dst[0] = lo | (hi << 24);
-        dst[1] = (hi >> 8) | (p_lo << 16);
-        dst[2] = (p_lo >> 16) | (p_hi << 8);
-    }
+    if ((chunk8 & 1) == 0)
+        store_code_quad(codes, row, K, chunk8 >> 1, lo | (hi << 24), (hi >> 8) | (p_lo << 16), (p_lo >> 16) | (p_hi << 8));
 }
 
 // Per-row scalars of the front end: the quantiser's epsilon and, if ln_gain != nullptr, the RMS
@@ -452,7 +448,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
         }
         int8_t* dst = codes + row_off + (int64_t)(g * 64 + lane) * CH;
         if constexpr (CH == 8) {
-            if (bf6) bf6_store_pair(codes + row_off, g * 64 + lane, bf6_pack4(packed[0]), bf6_pack4(packed[1]));
+            if (bf6) bf6_store_pair(codes, row, K, g * 64 + lane, bf6_pack4(packed[0]), bf6_pack4(packed[1]));
             else *reinterpret_cast<uint2*>(dst) = make_uint2(packed[0], packed[1]);
         } else if constexpr (CH == 4) {
             *reinterpret_cast<uint32_t*>(dst) = packed[0];
@@ -590,7 +586,7 @@ __device__ __forceinline__ void quant_generic_body(int64_t row, int tid, const v
                 packed[e / 4] |= (bits & 0xFFu) << (8 * (e % 4));
             }
             // K / 8 is a multiple of 16: the lanes of a quad are in or out of this branch together
-            if (bf6) bf6_store_pair(codes + row_off, ch, bf6_pack4(packed[0]), bf6_pack4(packed[1]));
+            if (bf6) bf6_store_pair(codes, row, K, ch, bf6_pack4(packed[0]), bf6_pack4(packed[1]));
             else *reinterpret_cast<uint2*>(codes + row_off + (int64_t)ch * 8) = make_uint2(packed[0], packed[1]);
         }
     }
@@ -677,8 +673,8 @@ struct BigRowLayout {
 __host__ __device__ constexpr uint32_t swz16(uint32_t q) { return q ^ ((q >> 4) & 15u); }
 
 // BF6OUT (INT4 only): instead of one byte per code, write the form the fp6 x fp4 GEMM reads - per 32
-// consecutive features a 32-byte record whose first 24 bytes hold the 32 codes as bf6 (e3m2) values,
-// feature i at bits [6i, 6i+6); every integer in [-8, 7] is exact in that format.
+// consecutive features a 24-byte record of bf6 (e3m2) values, feature i at bits [6i, 6i+6), placed in the
+// record image of code_records.h; every integer in [-8, 7] is exact in that format.
 // NORM: compiled with the RMS-normalisation prologue (taken when rp.ln_gain is set).  A template switch
 // rather than the run-time test alone: the prologue's presence changes the register allocation of the
 // whole body, and the plain prefill path should not pay for it.
@@ -944,10 +940,10 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
         for (int i = 0; i < 4; ++i) {
             const uint32_t quad = tid + NT * i;
             const uint4 c = *reinterpret_cast<const uint4*>(c24 + 4 * quad);
-            uint32_t* dst = reinterpret_cast<uint32_t*>(codes + row_off + 32 * (quad >> 1) + 12 * (quad & 1));
-            dst[0] = __builtin_amdgcn_perm(c.y, c.x, 0x04020100u);   // x0 x1 x2 y0
-            dst[1] = __builtin_amdgcn_perm(c.z, c.y, 0x05040201u);   // y1 y2 z0 z1
-            dst[2] = __builtin_amdgcn_perm(c.w, c.z, 0x06050402u);   // z2 w0 w1 w2
+            store_code_quad(codes, row, K, (int)quad,
+                            __builtin_amdgcn_perm(c.y, c.x, 0x04020100u),    // x0 x1 x2 y0
+                            __builtin_amdgcn_perm(c.z, c.y, 0x05040201u),    // y1 y2 z0 z1
+                            __builtin_amdgcn_perm(c.w, c.z, 0x06050402u));   // z2 w0 w1 w2
         }
     }
     if (code_sum) {   // uniform: the fp6 x fp4 GEMM needs no code sum

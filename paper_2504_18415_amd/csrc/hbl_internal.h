@@ -8,6 +8,7 @@
 
 #include <atomic>
 
+#include "code_records.h"
 #include "hbitlinear.h"
 
 namespace hbl {
@@ -131,7 +132,10 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
     Workspace w;
     size_t off = 0;
     w.codes = reinterpret_cast<int8_t*>(static_cast<char*>(base) + off);
-    off += round_up(static_cast<size_t>(T) * static_cast<size_t>(K), 256);
+    {   // one byte per code, or the record image (0.75 byte per code, whole panels of 128 tokens)
+        const size_t bytes = static_cast<size_t>(T) * static_cast<size_t>(K), rec = code_record_bytes(T, K);
+        off += round_up(bytes > rec ? bytes : rec, 256);
+    }
     w.s_dequant = reinterpret_cast<float*>(static_cast<char*>(base) + off);
     off += round_up(static_cast<size_t>(T) * sizeof(float), 256);
     w.code_sum = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
@@ -150,8 +154,6 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
 // Codes are stored as code + code_offset (0, or 8 for INT4 so that the stored bytes are 0..15), or -
 // code_offset == kCodesBf6 - as bf6 records (see fwht_quant.hip; INT4 with K >= 512).
 constexpr int kCodesBf6 = 6;
-// bytes of [T, K] codes as bf6 records
-inline size_t code_record_bytes(int64_t T, int64_t K) { return (size_t)T * (size_t)K; }
 inline bool bf6_path_supported(int64_t T, int64_t K, int bits, bool hadamard) {
     (void)hadamard;
     return bits == 4 && T > 64 && K >= 512;

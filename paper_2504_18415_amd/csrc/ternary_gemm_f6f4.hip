@@ -9,8 +9,9 @@
 // Same skeleton as ternary_gemm.hip (256 x 256 tiles, 4 waves of 128 x 128, direct global->LDS copies,
 // one small piece of side work after every MFMA).  Differences:
 //   - a pipeline stage is still 128 features but only two MFMA K-steps of 64;
-//   - activation codes arrive as 32-byte records (24 bytes of bf6 + 8 unused) so a token row of a
-//     stage is 128 bytes as before and an operand is one 16-byte + one 8-byte LDS read;
+//   - activation codes arrive as the record image of code_records.h: 6 bits per code, a token row of a
+//     stage is 96 bytes, a 128-token panel of a stage one contiguous 12 KiB block that is copied to LDS
+//     as it is (twelve 1 KiB pieces), and an operand is one 16-byte + one 8-byte LDS read;
 //   - weights come from the second packed form (sign / magnitude bit pairs): two AND and one shift
 //     turn a packed dword into two operand registers of eight fp4 values each.
 #include <atomic>
@@ -35,12 +36,14 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
     constexpr int NW = WAVES_N * WAVES_T;
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int BT = WAVES_T * TT * 32;
-    constexpr int XBYTES = BT * kBK;               // code records per stage (1 byte of storage per feature)
+    constexpr int XBYTES = BT * kRecordRowBytes;   // code records per stage (0.75 byte per feature)
     constexpr int WBYTES = (BN / 32) * 1024;       // packed weights per stage
     constexpr int STAGE = XBYTES + WBYTES;
-    constexpr int XL = (BT / 8) / NW;              // global->LDS copies per wave per stage: codes
+    constexpr int XPIECES = XBYTES / 1024;         // 1 KiB pieces of the code panels of a stage
+    constexpr int XL = XPIECES / NW;               // global->LDS copies per wave per stage: codes
     constexpr int WL = (BN / 32) / NW;             // ... and weights
-    static_assert((BT / 8) % NW == 0 && (BN / 32) % NW == 0, "stage copies must divide evenly over the waves");
+    static_assert(BT % kPanelTokens == 0 && XPIECES % NW == 0 && (BN / 32) % NW == 0,
+                  "stage copies must divide evenly over the waves");
     static_assert(NSTAGE >= 2, "need at least double buffering");
     constexpr int PENDING = (NSTAGE - 2) * (XL + WL);
 
@@ -79,18 +82,19 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
         wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb_total + kb0) * 1024;
     }
     const uint32_t wlane = lane * 16;
-    // copy q covers tokens 8q..8q+7: lane l -> token 8q + l/8, LDS slot l%8, global 16-byte chunk
-    // (l%8) ^ ((token/2) % 8); tokens past T are clamped to the last row
-    const char* xbase = reinterpret_cast<const char*>(a.codes) + (size_t)t0 * a.K + (size_t)kb0 * kBK;
-    uint32_t xlane[XL];
+    // codes: the stage's panel blocks (one per 128 tokens of the tile, 12 KiB each, contiguous in the record
+    // image) are copied as they are, piece q = 1 KiB; piece q of this wave belongs to panel q / 12
+    const char* xbase = reinterpret_cast<const char*>(a.codes) +
+                        ((size_t)(t0 / kPanelTokens) * nkb_total + kb0) * kRecordBlockBytes;
+    const size_t panel_stride = (size_t)nkb_total * kRecordBlockBytes;
+    const char* xpiece[XL];
 #pragma unroll
     for (int m = 0; m < XL; ++m) {
         const int q = wave + NW * m;
-        const int row = 8 * q + (lane >> 3);
-        int t = t0 + row;
-        t = t < a.T ? t : a.T - 1;
-        const int c = (lane & 7) ^ ((row >> 1) & 7);
-        xlane[m] = (uint32_t)(t - t0) * (uint32_t)a.K + c * 16;
+        int panel = q / 12;
+        const int panel_max = (a.T - 1) / kPanelTokens - t0 / kPanelTokens;   // panels past T do not exist: re-read the last one
+        panel = panel < panel_max ? panel : panel_max;
+        xpiece[m] = xbase + panel * panel_stride + (q % 12) * 1024;
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
 
@@ -98,7 +102,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
         const int kbc = kb < nkb ? kb : nkb - 1;   // past the end: re-read the last block (keeps PENDING valid)
         if (m < XL) {
             const int q = wave + NW * m;
-            lds_dma16(lds0 + slot * STAGE + q * 1024, xbase + (size_t)kbc * kBK, xlane[m]);
+            lds_dma16(lds0 + slot * STAGE + q * 1024, xpiece[m] + (size_t)kbc * kRecordBlockBytes, wlane);
         } else {
             const int wtile = wave + NW * (m - XL);
             lds_dma16(lds0 + slot * STAGE + XBYTES + wtile * 1024, wbase[m - XL] + (size_t)kbc * 1024, wlane);
@@ -117,17 +121,16 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // record of K-step s (64 features) for lane half h = lane >> 5 starts at chunk 4s + 2h of the token's
-    // 128-byte row: 16 bytes there, 8 more at the start of the next chunk
+    // record of K-step s (64 features) for lane half h = lane >> 5: 16 bytes + 8 bytes of the token's 96-byte
+    // row (code_records.h; the tile's rows are whole panels, so row mod 128 and lane agree in bits 3 and 4)
     int xoff_lo[2], xoff_hi[2];
     {
-        const int rowoff = (wt * TT * 32 + (lane & 31)) * kBK;
-        const int sw = (lane >> 1) & 7;
+        const int r = lane & 31;
+        const int rowoff = (wt * TT * 32 + r) * kRecordRowBytes;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            const int c = 4 * s + 2 * (lane >> 5);
-            xoff_lo[s] = rowoff + ((c ^ sw) << 4);
-            xoff_hi[s] = rowoff + (((c + 1) ^ sw) << 4);
+            xoff_lo[s] = rowoff + record_lo_offset(r, s, lane >> 5);
+            xoff_hi[s] = rowoff + record_hi_offset(r, s, lane >> 5);
         }
     }
     const int woff = XBYTES + wn * TN * 1024 + lane * 16;
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
     };
     // half an operand per call: part 0 = the 16-byte piece, part 1 = the 8-byte piece
     auto load_x_part = [&](int slot, int s, int buf, int j, int part) {
-        const char* base = lds + slot * STAGE + j * 32 * kBK;
+        const char* base = lds + slot * STAGE + j * 32 * kRecordRowBytes;
         if (part == 0) {
             const v4i lo = *reinterpret_cast<const v4i*>(base + xoff_lo[s]);
             xop[buf][j][0] = lo[0]; xop[buf][j][1] = lo[1]; xop[buf][j][2] = lo[2]; xop[buf][j][3] = lo[3];
@@ -330,7 +333,7 @@ template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool SPLIT = fal
 int launch_cfg(GemmArgs a, hipStream_t stream) {
     constexpr int BN = WAVES_N * TN * 32;
     constexpr int BT = WAVES_T * TT * 32;
-    constexpr size_t lds = (size_t)NSTAGE * (BT * kBK + (BN / 32) * 1024);
+    constexpr size_t lds = (size_t)NSTAGE * (BT * kRecordRowBytes + (BN / 32) * 1024);
     a.tiles_n = (a.N + BN - 1) / BN;
     a.tiles_t = (a.T + BT - 1) / BT;
     if (!SPLIT) a.split_k = 1;

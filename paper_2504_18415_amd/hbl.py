@@ -239,11 +239,19 @@ def bitlinear_forward_small(x: torch.Tensor, Wq_packed: torch.Tensor, N: int, w_
     return y
 
 
+def _alloc_codes(T: int, K: int, code_form: int, device) -> torch.Tensor:
+    """Byte forms: int8 [T, K].  Record form: the flat record image (0.75 byte per code, whole 128-token panels)."""
+    if code_form == CODES_BF6:
+        return torch.empty(code_bytes(T, K, CODES_BF6), dtype=torch.int8, device=device)
+    return torch.empty((T, K), dtype=torch.int8, device=device)
+
+
 def fwht_quant(x: torch.Tensor, bits: int, hadamard: bool = True, eps: float = EPS, code_offset: int = 0):
-    """Eq. 3-6 only -> (codes int8 [T,K] stored as code+code_offset, s_dequant fp32 [T], code_sum int32 [T])."""
+    """Eq. 3-6 only -> (codes, s_dequant fp32 [T], code_sum int32 [T]); codes int8 [T,K] stored as
+    code+code_offset, or for ``CODES_BF6`` the flat record image of ``code_bytes(T, K, CODES_BF6)`` bytes."""
     _dev_check(x)
     T, K = x.shape
-    codes = torch.empty((T, K), dtype=torch.int8, device=x.device)
+    codes = _alloc_codes(T, K, code_offset, x.device)
     sd = torch.empty(T, dtype=torch.float32, device=x.device)
     cs = torch.empty(T, dtype=torch.int32, device=x.device)
     _check(lib().hbl_fwht_quant(_ptr(x), _x_dtype(x), T, K, bits, eps, int(hadamard), code_offset, _ptr(codes),
@@ -261,12 +269,17 @@ def gemm_i32(codes: torch.Tensor, Wq_packed: torch.Tensor, N: int) -> torch.Tens
     return acc
 
 
-def gemm_i32_bf6(records: torch.Tensor, Wq_packed: torch.Tensor, N: int,
+def _check_records(records: torch.Tensor, T: int, K: int):
+    if records.element_size() != 1 or records.numel() < code_bytes(T, K, CODES_BF6) or code_bytes(T, K, CODES_BF6) == 0:
+        raise ValueError(f"code records for [{T}, {K}] need {code_bytes(T, K, CODES_BF6)} bytes (got {records.numel()})")
+
+
+def gemm_i32_bf6(records: torch.Tensor, Wq_packed: torch.Tensor, N: int, T: int, K: int,
                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """acc int32 [T,N] from bf6 code records [T,K] on the fp6 x fp4 kernel, in the forward call's own launch
-    configuration for the shape (exact integers read out of its fp32 accumulators)."""
+    """acc int32 [T,N] from the record image of [T,K] codes on the fp6 x fp4 kernel, in the forward call's own
+    launch configuration for the shape (exact integers read out of its fp32 accumulators)."""
     _dev_check(records, Wq_packed, workspace)
-    T, K = records.shape
+    _check_records(records, T, K)
     _check_projection(T, K, N, Wq_packed, torch.empty(1), None, workspace)
     acc = torch.empty((T, N), dtype=torch.int32, device=records.device)
     if workspace is None:
@@ -276,11 +289,15 @@ def gemm_i32_bf6(records: torch.Tensor, Wq_packed: torch.Tensor, N: int,
     return acc
 
 
-def gemm_i32_tile_for_tests(codes: torch.Tensor, code_form: int, Wq_packed: torch.Tensor, N: int, tile: int) -> torch.Tensor:
+def gemm_i32_tile_for_tests(codes: torch.Tensor, code_form: int, Wq_packed: torch.Tensor, N: int, tile: int,
+                            T: Optional[int] = None, K: Optional[int] = None) -> torch.Tensor:
     """Test-suite export: the integer contraction through one named workgroup tile (TILE_*) of the int8
-    (``CODES_INT8``) or fp6 x fp4 (``CODES_BF6``) prefill kernel."""
+    (``CODES_INT8``, codes [T,K]) or fp6 x fp4 (``CODES_BF6``, record image; pass T and K) prefill kernel."""
     _dev_check(codes, Wq_packed)
-    T, K = codes.shape
+    if code_form == CODES_BF6:
+        _check_records(codes, T, K)
+    else:
+        T, K = codes.shape
     _check_projection(T, K, N, Wq_packed, torch.empty(1), None)
     acc = torch.empty((T, N), dtype=torch.int32, device=codes.device)
     partial = torch.empty(8 * T * N * 4 if tile == TILE_SPLIT_K else 16, dtype=torch.uint8, device=codes.device)
@@ -319,10 +336,15 @@ class trace:
 
 def gemm_dequant_bf16(codes: torch.Tensor, s_dequant: torch.Tensor, code_sum: torch.Tensor, Wq_packed: torch.Tensor,
                       N: int, w_scales: torch.Tensor, y: Optional[torch.Tensor] = None,
-                      code_offset: int = 0) -> torch.Tensor:
-    """Second launch of the forward on caller-held intermediates: y bf16 [T,N]."""
+                      code_offset: int = 0, K: Optional[int] = None) -> torch.Tensor:
+    """Second launch of the forward on caller-held intermediates: y bf16 [T,N].  With ``CODES_BF6`` the codes are
+    the flat record image and K must be given (T is the length of ``s_dequant``)."""
     _dev_check(codes, s_dequant, code_sum, Wq_packed, w_scales, y)
-    T, K = codes.shape
+    if code_offset == CODES_BF6:
+        T = s_dequant.numel()
+        _check_records(codes, T, K)
+    else:
+        T, K = codes.shape
     _check_projection(T, K, N, Wq_packed, w_scales, y)
     if (s_dequant.dtype != torch.float32 or s_dequant.numel() < T or code_sum.dtype != torch.int32
             or code_sum.numel() < T):
@@ -416,7 +438,7 @@ def ln_fwht_quant(x: torch.Tensor, ln_gain: torch.Tensor, ln_eps: float, bits: i
     """RMS normalisation + Eq. 3-6 -> (codes, s_dequant, code_sum) as :func:`fwht_quant`."""
     _dev_check(x, ln_gain)
     T, K = x.shape
-    codes = torch.empty((T, K), dtype=torch.int8, device=x.device)
+    codes = _alloc_codes(T, K, code_offset, x.device)
     sd = torch.empty(T, dtype=torch.float32, device=x.device)
     cs = torch.empty(T, dtype=torch.int32, device=x.device)
     _check(lib().hbl_ln_fwht_quant(_ptr(x), _x_dtype(x), T, K, _ptr(ln_gain), ln_eps, bits, eps, int(hadamard),

@@ -202,28 +202,51 @@ def test_int4_offset_codes_and_split_calls(hbl, K, hadamard):
         hbl.fwht_quant(xd, 8, hadamard, EPS, code_offset=8)
 
 
-def decode_bf6_records(rec, K):
-    """[T, K] bytes of 32-byte records (24 bytes = 32 six-bit e3m2 floats, feature i at bits [6i, 6i+6)) -> int codes."""
-    T = rec.shape[0]
-    r = rec.reshape(T, K // 32, 32)[:, :, :24].astype(np.uint64)
-    lo = sum(r[:, :, b] << np.uint64(8 * b) for b in range(8))
-    mid = sum(r[:, :, 8 + b] << np.uint64(8 * b) for b in range(8))
-    hi = sum(r[:, :, 16 + b] << np.uint64(8 * b) for b in range(8))
+def _record_image_words(T, K):
+    """Index arithmetic of the record image (HBL_CODES_BF6), restated from its description: for token t and
+    record m (features [32m, 32m+32)) the positions, in 8-byte words of the image, of the record's bits 0..63,
+    64..127 and 128..191.  Tokens in panels of 128, features in blocks of 128, a block = 128 rows of 96 bytes."""
+    t = np.arange(T, dtype=np.int64)[:, None]
+    m = np.arange(K // 32, dtype=np.int64)[None, :]
+    kb, s, h = m >> 2, (m >> 1) & 1, m & 1
+    r = t & 127
+    row = (((t >> 7) * (K // 128)) + kb) * 12288 + r * 96
+    lo = row + (((3 * s + 2 * h) ^ ((r >> 3) & 1)) << 4)
+    hi = row + (((3 * s + 1) ^ ((r >> 3) & 1)) << 4) + ((h ^ ((r >> 4) & 1)) << 3)
+    return lo // 8, lo // 8 + 1, hi // 8
+
+
+def record_image_bytes(T, K):
+    return ((T + 127) // 128) * (K // 128) * 12288
+
+
+def decode_bf6_records(image, T, K):
+    """Record image bytes -> int codes [T, K]: per 32 features a 192-bit record of six-bit e3m2 floats, feature i
+    at bits [6i, 6i+6)."""
+    img = np.ascontiguousarray(image).view(np.uint8).reshape(-1)[:record_image_bytes(T, K)].view(np.uint64)
+    w0, w1, w2 = _record_image_words(T, K)
+    words = (img[w0], img[w1], img[w2])
     out = np.empty((T, K // 32, 32), np.int32)
     for i in range(32):
-        bit = 6 * i
-        word, off = divmod(bit, 64)
-        src = (lo, mid, hi)[word]
-        v = (src >> np.uint64(off)) & np.uint64(0x3F)
+        word, off = divmod(6 * i, 64)
+        v = (words[word] >> np.uint64(off)) & np.uint64(0x3F)
         if off > 58:
-            nxt = (lo, mid, hi)[word + 1]
-            v |= (nxt << np.uint64(64 - off)) & np.uint64(0x3F)
+            v |= (words[word + 1] << np.uint64(64 - off)) & np.uint64(0x3F)
         v = v.astype(np.int32)
-        sign, e, m = v >> 5, (v >> 2) & 7, v & 3
-        mag = np.where(e == 0, m / 16.0, (2.0 ** (e - 3)) * (1 + m / 4.0))
-        out[:, :, i] = np.where(sign == 1, -mag, mag).astype(np.int32)
-        assert np.all(np.where(sign == 1, -mag, mag) == out[:, :, i])       # every stored value is an integer
+        sign, e, mant = v >> 5, (v >> 2) & 7, v & 3
+        mag = np.where(e == 0, mant / 16.0, (2.0 ** (e - 3)) * (1 + mant / 4.0))
+        val = np.where(sign == 1, -mag, mag)
+        out[:, :, i] = val.astype(np.int32)
+        assert np.all(val == out[:, :, i])       # every stored value is an integer
     return out.reshape(T, K)
+
+
+def record_bits(image, T, K):
+    """The 192 bits of every record as three uint64 words [T, K/32, 3] (what a comparison bit for bit looks at:
+    the image also holds rows beyond T that nobody wrote)."""
+    img = np.ascontiguousarray(image).view(np.uint8).reshape(-1)[:record_image_bytes(T, K)].view(np.uint64)
+    w0, w1, w2 = _record_image_words(T, K)
+    return np.stack([img[w0], img[w1], img[w2]], axis=-1)
 
 
 @pytest.mark.parametrize("K,hadamard", [(4096, True), (8192, True), (16384, True), (512, True), (1024, True),
@@ -241,14 +264,15 @@ def test_bf6_code_records_and_f6f4_gemm(hbl, K, hadamard):
     xd = dev_x(x)
     rec, sd, cs = hbl.fwht_quant(xd, 4, hadamard, EPS, code_offset=hbl.CODES_BF6)
     rec_np = rec.cpu().numpy().view(np.uint8)
-    assert np.array_equal(decode_bf6_records(rec_np, K), c_ref.astype(np.int32))
-    # and bit for bit: the 24 data bytes of every record hold the canonical patterns (code 0 is +0, never -0)
+    assert rec_np.size == record_image_bytes(T, K) == hbl.code_bytes(T, K, hbl.CODES_BF6)
+    assert np.array_equal(decode_bf6_records(rec_np, T, K), c_ref.astype(np.int32))
+    # and bit for bit: every record holds the canonical patterns (code 0 is +0, never -0)
     want = encode_bf6_records(c_ref.astype(np.int32))
-    assert np.array_equal(rec_np.reshape(T, K // 32, 32)[:, :, :24], want.reshape(T, K // 32, 32)[:, :, :24])
+    assert np.array_equal(record_bits(rec_np, T, K), record_bits(want, T, K))
     assert np.array_equal(sd.cpu().numpy(), s_ref)
     assert np.array_equal(cs.cpu().numpy(), c_ref.astype(np.int32).sum(1))
     wc_ref, al_ref, wc_d, al_d, packed = setup_weights(hbl, site)
-    y6 = hbl.gemm_dequant_bf16(rec, sd, cs, packed, N, al_d, code_offset=hbl.CODES_BF6)
+    y6 = hbl.gemm_dequant_bf16(rec, sd, cs, packed, N, al_d, code_offset=hbl.CODES_BF6, K=K)
     c8, sd8, cs8 = hbl.fwht_quant(xd, 4, hadamard, EPS, code_offset=8)
     y8 = hbl.gemm_dequant_bf16(c8, sd8, cs8, packed, N, al_d, code_offset=8)
     fn = hbl.hbitlinear_forward if hadamard else hbl.plain_bitlinear_forward
@@ -269,7 +293,8 @@ BF6_OF_CODE = {-8: 0x38, -7: 0x37, -6: 0x36, -5: 0x35, -4: 0x34, -3: 0x32, -2: 0
 
 
 def encode_bf6_records(codes):
-    """int codes [T, K] in [-8, 7] -> [T, K] bytes of 32-byte records (inverse of decode_bf6_records)."""
+    """int codes [T, K] in [-8, 7] -> record image bytes (inverse of decode_bf6_records; rows of the last
+    panel beyond T are zero)."""
     T, K = codes.shape
     lut = np.zeros(16, np.uint64)
     for c, v in BF6_OF_CODE.items():
@@ -278,14 +303,13 @@ def encode_bf6_records(codes):
     words = [np.zeros((T, K // 32), np.uint64) for _ in range(3)]
     for i in range(32):
         word, off = divmod(6 * i, 64)
-        words[word] |= six[:, :, i] << np.uint64(off)
+        words[word] |= (six[:, :, i] << np.uint64(off))
         if off > 58:
             words[word + 1] |= six[:, :, i] >> np.uint64(64 - off)
-    rec = np.zeros((T, K // 32, 32), np.uint8)
-    for w in range(3):
-        for b in range(8):
-            rec[:, :, 8 * w + b] = ((words[w] >> np.uint64(8 * b)) & np.uint64(0xFF)).astype(np.uint8)
-    return rec.reshape(T, K)
+    img = np.zeros(record_image_bytes(T, K) // 8, np.uint64)
+    w0, w1, w2 = _record_image_words(T, K)
+    img[w0], img[w1], img[w2] = words[0], words[1], words[2]
+    return img.view(np.uint8)
 
 
 @pytest.mark.parametrize("K,T", [(16384, 1100), (8192, 2300), (4096, 4500)])
@@ -299,8 +323,8 @@ def test_quantiser_rows_walked_by_resident_workgroups(hbl, K, T):
     xd = dev_x(x)
     c4, s4 = O.fwht_quant(x, 4, hadamard=True, eps=EPS)
     rec, sd, cs = hbl.fwht_quant(xd, 4, True, EPS, code_offset=hbl.CODES_BF6)
-    want = encode_bf6_records(c4.astype(np.int32)).reshape(T, K // 32, 32)[:, :, :24]
-    assert np.array_equal(rec.cpu().numpy().view(np.uint8).reshape(T, K // 32, 32)[:, :, :24], want)
+    want = record_bits(encode_bf6_records(c4.astype(np.int32)), T, K)
+    assert np.array_equal(record_bits(rec.cpu().numpy(), T, K), want)
     assert np.array_equal(sd.cpu().numpy(), s4)
     assert np.array_equal(cs.cpu().numpy(), c4.astype(np.int32).sum(1))
     c, sd, cs = hbl.fwht_quant(xd, 4, True, EPS, code_offset=8)
@@ -322,7 +346,7 @@ def test_f6f4_gemm_extreme_codes(hbl):
     codes = np.full((T, K), -8, np.int8)
     codes[7] = 7
     codes[9] = rng.integers(-8, 8, K)
-    assert np.array_equal(decode_bf6_records(encode_bf6_records(codes), K), codes)
+    assert np.array_equal(decode_bf6_records(encode_bf6_records(codes), T, K), codes)
     wc = np.ones((N, K), np.int8)
     wc[1::2] = -1
     wc[5] = rng.integers(-1, 2, K)
@@ -331,7 +355,7 @@ def test_f6f4_gemm_extreme_codes(hbl):
     sd = torch.ones(T, dtype=torch.float32, device="cuda")
     cs = torch.from_numpy(codes.astype(np.int32).sum(1).astype(np.int32)).cuda()
     rec = torch.from_numpy(encode_bf6_records(codes).view(np.int8)).cuda()
-    y = hbl.gemm_dequant_bf16(rec, sd, cs, packed, N, al, code_offset=hbl.CODES_BF6)
+    y = hbl.gemm_dequant_bf16(rec, sd, cs, packed, N, al, code_offset=hbl.CODES_BF6, K=K)
     acc = O.gemm_i32(codes, wc)
     assert np.abs(acc).max() == 8 * K
     want = O.dequant_bf16(acc, np.ones(T, np.float32), np.ones(1, np.float32))
@@ -411,7 +435,7 @@ def run_site(hbl, site, bits, sample_rows=None):
     acc6 = None
     if bits == 4 and site.T > 64 and site.K >= 512:
         rec, _, _ = hbl.fwht_quant(xd, 4, site.hadamard, EPS, code_offset=hbl.CODES_BF6)
-        acc6 = hbl.gemm_i32_bf6(rec, packed, site.N)
+        acc6 = hbl.gemm_i32_bf6(rec, packed, site.N, site.T, site.K)
         del rec
     torch.cuda.synchronize()
     rows = np.arange(site.T) if sample_rows is None else sample_rows
@@ -523,7 +547,7 @@ def test_prefill_gemm_tiles_raw_accumulators(hbl, T, K, N):
     rec = torch.from_numpy(encode_bf6_records(q.astype(np.int32)).view(np.int8)).cuda()
     qd = torch.from_numpy(q).cuda()
     for tile in (hbl.TILE_SQUARE, hbl.TILE_SMALL, hbl.TILE_WIDE, hbl.TILE_SPLIT_K):
-        got = hbl.gemm_i32_tile_for_tests(rec, hbl.CODES_BF6, packed, N, tile).cpu().numpy()
+        got = hbl.gemm_i32_tile_for_tests(rec, hbl.CODES_BF6, packed, N, tile, T=T, K=K).cpu().numpy()
         assert np.array_equal(got, want), f"fp6 x fp4 kernel, tile {tile}"
     q8 = rng.integers(-128, 128, (T, K)).astype(np.int8)
     want8 = O.gemm_i32(q8, c)
@@ -533,7 +557,7 @@ def test_prefill_gemm_tiles_raw_accumulators(hbl, T, K, N):
         assert np.array_equal(got, want8), f"int8 kernel, tile {tile}"
         got = hbl.gemm_i32_tile_for_tests(qd, hbl.CODES_INT8, packed, N, tile).cpu().numpy()
         assert np.array_equal(got, want), f"int8 kernel on INT4 codes, tile {tile}"
-    assert np.array_equal(hbl.gemm_i32_bf6(rec, packed, N).cpu().numpy(), want)      # the forward's own choice
+    assert np.array_equal(hbl.gemm_i32_bf6(rec, packed, N, T, K).cpu().numpy(), want)      # the forward's own choice
 
 
 def test_f6f4_raw_accumulators_extreme_and_split_k_shapes(hbl):
@@ -552,8 +576,8 @@ def test_f6f4_raw_accumulators_extreme_and_split_k_shapes(hbl):
         assert np.abs(want).max() == 8 * K
         packed = hbl.pack_ternary_2bit(torch.from_numpy(c).cuda())
         rec = torch.from_numpy(encode_bf6_records(q.astype(np.int32)).view(np.int8)).cuda()
-        assert np.array_equal(hbl.gemm_i32_bf6(rec, packed, N).cpu().numpy(), want), (T, K, N)
-        got = hbl.gemm_i32_tile_for_tests(rec, hbl.CODES_BF6, packed, N, hbl.TILE_SPLIT_K).cpu().numpy()
+        assert np.array_equal(hbl.gemm_i32_bf6(rec, packed, N, T, K).cpu().numpy(), want), (T, K, N)
+        got = hbl.gemm_i32_tile_for_tests(rec, hbl.CODES_BF6, packed, N, hbl.TILE_SPLIT_K, T=T, K=K).cpu().numpy()
         assert np.array_equal(got, want), (T, K, N, "split-K tile")
 
 
@@ -739,8 +763,8 @@ def test_ln_quantiser_rows_walked_by_resident_workgroups(hbl, K, T, dtype):
     c4, s4 = O.fwht_quant(O.rmsnorm(x, g, 1e-6), 4, hadamard=True, eps=EPS)
     xd, gd = dev_x(x), torch.from_numpy(g).cuda()
     rec, sd, cs = hbl.ln_fwht_quant(xd, gd, 1e-6, 4, True, EPS, code_offset=hbl.CODES_BF6)
-    want = encode_bf6_records(c4.astype(np.int32)).reshape(T, K // 32, 32)[:, :, :24]
-    assert np.array_equal(rec.cpu().numpy().view(np.uint8).reshape(T, K // 32, 32)[:, :, :24], want)
+    want = record_bits(encode_bf6_records(c4.astype(np.int32)), T, K)
+    assert np.array_equal(record_bits(rec.cpu().numpy(), T, K), want)
     assert np.array_equal(sd.cpu().numpy(), s4) and np.array_equal(cs.cpu().numpy(), c4.astype(np.int32).sum(1))
     c, sd, cs = hbl.ln_fwht_quant(xd, gd, 1e-6, 4, True, EPS, code_offset=8)
     assert np.array_equal(c.cpu().numpy().astype(np.int32) - 8, c4.astype(np.int32))
