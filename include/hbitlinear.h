@@ -82,17 +82,18 @@ size_t hbl_ternarize_workspace_bytes(int64_t N, int64_t K);
 int hbl_ternarize_weights_absmean(const float* W, int64_t N, int64_t K, float eps, int8_t* codes,
                                   float* alpha, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of the packed form of an [N, K] ternary tensor: two 2-bit forms (one per matrix-core path,
- * N*K/4 bytes each; a forward call streams only one of them) + 4*N (row sums). */
+/* Bytes of the packed form of an [N, K] ternary tensor: N*K/4 (2 bits per weight) + 4*N (row sums). */
 size_t hbl_packed_bytes(int64_t N, int64_t K);
 
 /*
  * Pack ternary codes 4 per byte into the library's streaming layout (not in
  * the paper, which describes no storage format).  The layout is opaque to the
  * caller: 1 KiB tiles of 32 output rows x 128 input features, ordered so that
- * one 16-byte load per lane yields matrix-core operands; each weight is
- * stored as code+1 in {0,1,2}; the tiles are followed by the N int32 row sums
- * sum_k c[o][k] that the epilogue uses.  hbl_unpack_ternary_2bit is the exact inverse.
+ * one 16-byte load per lane yields matrix-core operands; each weight is a
+ * (sign, magnitude) bit pair that every GEMM kernel of the library reads (as an
+ * fp4 value or, after a byte look-up, as an int8); the tiles are followed by the
+ * N int32 row sums sum_k c[o][k] that the int8 epilogue uses for offset codes.
+ * hbl_unpack_ternary_2bit is the exact inverse.
  *   codes  [N, K] int8 in {-1,0,1};   packed  hbl_packed_bytes(N, K) bytes, 16-byte aligned
  */
 int hbl_pack_ternary_2bit(const int8_t* codes, int64_t N, int64_t K, void* packed, void* stream);
@@ -103,7 +104,7 @@ int hbl_unpack_ternary_2bit(const void* packed, int64_t N, int64_t K, int8_t* co
  * ------------------------------------------------------------------------- */
 
 /* Device scratch needed by the two forward calls (activation codes, per-token
- * dequantisation scale and per-token code sum). */
+ * dequantisation scale, int32 partial tiles where a K range is split). */
 size_t hbl_workspace_bytes(int64_t T, int64_t K, int64_t N, int bits);
 
 /*

@@ -88,7 +88,6 @@ void fill_decode_problem(DecodeProblem& dp, const Workspace& ws, int32_t* partia
     dp.codes = ws.codes;
     dp.packed = static_cast<const uint32_t*>(Wq_packed);
     dp.s_dequant = ws.s_dequant;
-    dp.code_sum = ws.code_sum;
     dp.w_row_sum = reinterpret_cast<const int32_t*>(static_cast<const char*>(Wq_packed) + packed_tile_bytes(N, K));
     dp.w_scales = w_scales;
     dp.y = static_cast<uint16_t*>(y);
@@ -120,7 +119,7 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
     }
     // otherwise INT4 codes travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs
     const int code_offset = bits == 4 ? 8 : 0;
-    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, ws.code_sum, code_offset, s,
+    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, code_offset, s,
                            ln_gain, ln_eps);
     if (rc != HBL_OK) return rc;
     if (decode_stream_preferred(T, K, N)) {   // a handful of tokens: one weight-streaming launch
@@ -129,8 +128,8 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
         fill_decode_problem(da.p[0], ws, nullptr, T, K, Wq_packed, N, w_scales, groups, code_offset, y);
         return launch_decode_gemm(da, s);
     }
-    return launch_ternary_gemm(ws.codes, code_offset, T, K, Wq_packed, N, ws.s_dequant, ws.code_sum, w_scales, groups,
-                               y, nullptr, ws.partial, s);
+    return launch_ternary_gemm(ws.codes, code_offset, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, nullptr,
+                               ws.partial, s);
 }
 
 // Workspace region of one problem of a grouped call: large enough for the grouped launches (partials
@@ -291,7 +290,7 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
             qp.x = q.x;
             qp.codes = ws.codes;
             qp.s_dequant = ws.s_dequant;
-            qp.code_sum = ws.code_sum;
+            qp.code_sum = nullptr;
             qp.T = (int)q.T;
             qp.K = (int)q.K;
             qp.hadamard = q.hadamard != 0;
@@ -430,8 +429,8 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
     if (T == 0) return HBL_OK;
     if (!codes || !Wq_packed || !acc) return HBL_E_NULL;
     if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(acc)) return HBL_E_ALIGN;
-    return launch_ternary_gemm(codes, 0, T, K, Wq_packed, N, nullptr, nullptr, nullptr, 1, nullptr, acc,
-                               nullptr, static_cast<hipStream_t>(stream));
+    return launch_ternary_gemm(codes, 0, T, K, Wq_packed, N, nullptr, nullptr, 1, nullptr, acc, nullptr,
+                               static_cast<hipStream_t>(stream));
 }
 
 int hbl_gemm_i32_bf6(const void* code_records, int64_t T, int64_t K, const void* Wq_packed, int64_t N, int32_t* acc,
@@ -471,8 +470,8 @@ int hbl_test_gemm_i32_tile(const void* codes, int code_form, int64_t T, int64_t 
         return launch_ternary_gemm_f6f4(static_cast<const int8_t*>(codes), T, K, Wq_packed, N, nullptr, nullptr, 1,
                                         nullptr, s, tile == kTileSplitK ? static_cast<int32_t*>(partial) : nullptr, acc,
                                         tile);
-    return launch_ternary_gemm(static_cast<const int8_t*>(codes), 0, T, K, Wq_packed, N, nullptr, nullptr, nullptr, 1,
-                               nullptr, acc, nullptr, s, tile);
+    return launch_ternary_gemm(static_cast<const int8_t*>(codes), 0, T, K, Wq_packed, N, nullptr, nullptr, 1, nullptr,
+                               acc, nullptr, s, tile);
 }
 
 int hbl_trace_begin(int max_launches) {
@@ -523,13 +522,14 @@ int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_d
     if (rc != HBL_OK) return rc;
     if (n_scale_groups < 1 || (N % n_scale_groups) != 0 || ((N / n_scale_groups) % 32) != 0) return HBL_E_SHAPE;
     if (T == 0) return HBL_OK;
-    if (!codes || !s_dequant || !code_sum || !Wq_packed || !w_scales || !y) return HBL_E_NULL;
+    (void)code_sum;   // no kernel needs it: the packed weights are signed
+    if (!codes || !s_dequant || !Wq_packed || !w_scales || !y) return HBL_E_NULL;
     if (!aligned16(codes) || !aligned16(Wq_packed) || !aligned16(y)) return HBL_E_ALIGN;
     if (code_offset == HBL_CODES_BF6)
         return launch_ternary_gemm_f6f4(codes, T, K, Wq_packed, N, s_dequant, w_scales, n_scale_groups, y,
                                         static_cast<hipStream_t>(stream));
-    return launch_ternary_gemm(codes, code_offset, T, K, Wq_packed, N, s_dequant, code_sum, w_scales,
-                               n_scale_groups, y, nullptr, nullptr, static_cast<hipStream_t>(stream));
+    return launch_ternary_gemm(codes, code_offset, T, K, Wq_packed, N, s_dequant, w_scales, n_scale_groups, y, nullptr,
+                               nullptr, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

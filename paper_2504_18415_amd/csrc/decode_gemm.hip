@@ -5,8 +5,7 @@
 // A wave owns one 32-row weight tile at a time and walks its K range tile by tile (1 KiB of packed
 // weights = 32 rows x 128 features).  Weights and activation codes both arrive by direct global->LDS
 // copies, D = 4 stages deep per wave; per stage a wave expands the 16 packed bytes of each lane into
-// four int8 operands (code + 1, as in the large-T kernel; the epilogue removes the offset in int32)
-// and issues 4 (or 8) 32x32x32 int8 MFMAs.
+// four int8 operands (signed bytes, as in the large-T kernel) and issues 4 (or 8) 32x32x32 int8 MFMAs.
 //
 // Two forms:
 //  - streaming (T <= 16): a wave's code stage is private (8 or 16 rows x 128 B), so the waves never
@@ -24,16 +23,6 @@ namespace {
 
 using namespace gemm;
 typedef int v16i __attribute__((ext_vector_type(16)));
-
-// 16 packed weights -> four registers of four bytes, byte = code + 1 in {0, 1, 2}.
-__device__ __forceinline__ v4i expand_plus1(uint32_t p) {
-    v4i r;
-    r[0] = (int)(p & 0x03030303u);
-    r[1] = (int)((p >> 2) & 0x03030303u);
-    r[2] = (int)((p >> 4) & 0x03030303u);
-    r[3] = (int)((p >> 6) & 0x03030303u);
-    return r;
-}
 
 // The problem a workgroup belongs to: the last one whose first workgroup is not beyond it.
 template <typename BeginOf>
@@ -111,11 +100,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
     };
 
     // operand reads: token row (lane & 31) of tile j (rows beyond the stage wrap onto loaded rows; their
-    // results are never written), 16-byte chunk 2*k4 + (lane >> 5), swizzled like the copy
+    // results are never written), the 16-byte chunk that matches packed dword k4, swizzled like the copy
     const int r0 = (lane & 31) & (ROWS - 1);
     int xoff[4];
 #pragma unroll
-    for (int k4 = 0; k4 < 4; ++k4) xoff[k4] = r0 * kBK + (((2 * k4 + (lane >> 5)) ^ ((r0 >> 1) & 7)) << 4);
+    for (int k4 = 0; k4 < 4; ++k4) xoff[k4] = r0 * kBK + ((code_chunk_of_dword(k4, lane >> 5) ^ ((r0 >> 1) & 7)) << 4);
 
     v16i acc[NACC];
 #pragma unroll
@@ -128,13 +117,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
     const bool write_partial = SHARE && p.ksplit > 1;
     const bool writer = live && (SHARE || ks == 0);
     float alpha = 0.0f, sd[TT];
-    int sx[TT];
     v4i wsum[4];
 #pragma unroll
-    for (int j = 0; j < TT; ++j) {
-        sd[j] = 0.0f;
-        sx[j] = 0;
-    }
+    for (int j = 0; j < TT; ++j) sd[j] = 0.0f;
 #pragma unroll
     for (int g = 0; g < 4; ++g) wsum[g] = v4i{0, 0, 0, 0};
     if (writer && !write_partial) {
@@ -142,10 +127,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
 #pragma unroll
         for (int j = 0; j < TT; ++j) {
             const int t = j * 32 + (lane & 31);
-            if (t < p.T) {
-                sd[j] = p.s_dequant[t];
-                sx[j] = p.code_sum[t];
-            }
+            if (t < p.T) sd[j] = p.s_dequant[t];
         }
         if (p.code_offset != 0) {
 #pragma unroll
@@ -188,7 +170,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
         const v4i wpk = *reinterpret_cast<const v4i*>(st + XW + wave * 1024 + lane * 16);
 #pragma unroll
         for (int k4 = 0; k4 < 4; ++k4) {
-            const v4i wop = expand_plus1((uint32_t)wpk[k4]);
+            const v4i wop = expand_weights_i8((uint32_t)wpk[k4]);
 #pragma unroll
             for (int j = 0; j < TT; ++j) {
                 const v4i xop = *reinterpret_cast<const v4i*>(st + xarea + xoff[k4] + j * 32 * kBK);
@@ -235,7 +217,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
                 *reinterpret_cast<v4i*>(p.partial + ((size_t)ks * p.T + t) * p.N + n) = o;
             } else {
                 *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
-                    dequant_quad_sums(o, sx[j], sd[j], alpha, p.code_offset, wsum[g], p.K);
+                    dequant_quad_sums(o, sd[j], alpha, p.code_offset, wsum[g]);
             }
         }
     }
@@ -255,8 +237,7 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const DecodeArgs arg
     for (int k = 0; k < p.ksplit; ++k)
         sum += *reinterpret_cast<const v4i*>(p.partial + ((size_t)k * p.T + t) * p.N + n);
     *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
-        dequant_quad(sum, p.code_sum[t], p.s_dequant[t], p.w_scales[n / p.rows_per_group], p.code_offset,
-                     p.w_row_sum + n, p.K);
+        dequant_quad(sum, p.s_dequant[t], p.w_scales[n / p.rows_per_group], p.code_offset, p.w_row_sum + n);
 }
 
 template <bool SHARE, int TT, int RQ, int D, int NW = 4>

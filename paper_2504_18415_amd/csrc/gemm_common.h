@@ -43,9 +43,8 @@ __device__ __forceinline__ void store_y16(uint16_t* dst, uint4 val) {
 
 struct GemmArgs {
     const int8_t* codes;      // [T, K]
-    const uint32_t* packed;   // tiles [N/32][K/128][64 lanes][4 dwords]
+    const uint32_t* packed;   // tiles [N/32][K/128][64 lanes][4 dwords], sign / magnitude pairs
     const float* s_dequant;   // [T]
-    const int32_t* code_sum;  // [T] sum_k q[t][k] of the true (un-offset) codes
     const int32_t* w_row_sum; // [N] sum_k c[o][k]
     int code_offset;          // stored code byte = q + code_offset
     const float* w_scales;    // [groups]
@@ -61,18 +60,44 @@ struct GemmArgs {
 };
 
 // Second launch of a split-K GEMM (ternary_gemm.hip): adds the split_k int32 partial tiles and dequantises.
-// code_sum may be null (signed codes, no correction).
 int launch_splitk_reduce(const GemmArgs& a, hipStream_t stream);
 
+// Packed weights (ternary_setup.hip): sign / magnitude bit pairs, 16 weights per dword, placed so that two
+// AND and one shift give fp4 operands.  For the int8 matrix cores the same dword is expanded into four
+// registers of four signed bytes each, features in natural order:
+//   (p >> {0, 1, 4, 5}) & 0x05050505 puts four weights' (magnitude, sign) bits into bits 0 and 2 of four bytes,
+//   one byte-permute look-up turns the byte values {0, 1, 5} into {0, +1, -1}, and two more byte permutes per
+//   register pair interleave the even- and odd-numbered weights.
+__device__ __forceinline__ uint32_t weight_pairs(uint32_t p, int which) {   // which: 0 = b even, 1 = a even, 2 = b odd, 3 = a odd
+    const int sh = which == 0 ? 0 : which == 1 ? 1 : which == 2 ? 4 : 5;
+    return (p >> sh) & 0x05050505u;
+}
+__device__ __forceinline__ uint32_t weight_bytes(uint32_t pairs) {          // {0, 1, 5} -> {0x00, 0x01, 0xFF} per byte
+    return __builtin_amdgcn_perm(0x0000FF00u, 0x00000100u, pairs);
+}
+__device__ __forceinline__ uint32_t weight_interleave(uint32_t odd, uint32_t even, int upper) {
+    return __builtin_amdgcn_perm(odd, even, upper ? 0x07030602u : 0x05010400u);
+}
+// The four int8 operand registers of one packed dword (features 16d + 0..15 of the dword's sixteen).
+__device__ __forceinline__ v4i expand_weights_i8(uint32_t p) {
+    const uint32_t b_even = weight_bytes(weight_pairs(p, 0)), a_even = weight_bytes(weight_pairs(p, 1));
+    const uint32_t b_odd = weight_bytes(weight_pairs(p, 2)), a_odd = weight_bytes(weight_pairs(p, 3));
+    return v4i{(int)weight_interleave(a_odd, a_even, 0), (int)weight_interleave(a_odd, a_even, 1),
+               (int)weight_interleave(b_odd, b_even, 0), (int)weight_interleave(b_odd, b_even, 1)};
+}
+// 16-byte chunk of a token's 128-byte code row that holds the features packed dword j of a weight tile covers
+// for lane half h: features 64 (j >> 1) + 32 h + 16 (j & 1) + 0..15.
+__device__ __forceinline__ int code_chunk_of_dword(int j, int h) { return 4 * (j >> 1) + 2 * h + (j & 1); }
+
 // Outer factors of Eq. 1 and Eq. 5/6 on four consecutive output features of one token:
-// y = bf16(((float)(acc - corr) * s_d) * alpha), corr = sum_k q + code_offset * (sum_k c + K).
-// (ws = the four features' sum_k c, already loaded; ignored when code_offset == 0)
-__device__ __forceinline__ uint2 dequant_quad_sums(v4i acc, int sx, float sd, float alpha, int code_offset, v4i ws,
-                                                   int K) {
-    v4i corr = {sx, sx, sx, sx};
+// y = bf16(((float)(acc - corr) * s_d) * alpha), corr = code_offset * sum_k c: the weights are signed, so only
+// an offset on the stored codes (INT4 codes travel as q + 8 on this path) leaves a term to remove, exactly,
+// in int32.  (ws = the four features' sum_k c, already loaded; ignored when code_offset == 0)
+__device__ __forceinline__ uint2 dequant_quad_sums(v4i acc, float sd, float alpha, int code_offset, v4i ws) {
+    v4i corr = {0, 0, 0, 0};
     if (code_offset != 0) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) corr[r] += code_offset * (ws[r] + K);
+        for (int r = 0; r < 4; ++r) corr[r] = code_offset * ws[r];
     }
     float v[4];
 #pragma unroll
@@ -84,11 +109,11 @@ __device__ __forceinline__ uint2 dequant_quad_sums(v4i acc, int sx, float sd, fl
     const bf16x2 hi = __builtin_convertvector((f32x2){v[2], v[3]}, bf16x2);
     return make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
 }
-__device__ __forceinline__ uint2 dequant_quad(v4i acc, int sx, float sd, float alpha, int code_offset,
-                                              const int32_t* w_row_sum, int K) {
+__device__ __forceinline__ uint2 dequant_quad(v4i acc, float sd, float alpha, int code_offset,
+                                              const int32_t* w_row_sum) {
     v4i ws = {0, 0, 0, 0};
     if (code_offset != 0) ws = *reinterpret_cast<const v4i*>(w_row_sum);
-    return dequant_quad_sums(acc, sx, sd, alpha, code_offset, ws, K);
+    return dequant_quad_sums(acc, sd, alpha, code_offset, ws);
 }
 
 // WAVES_N x WAVES_T waves; each wave owns TN x TT MFMA tiles (32 features x 32 tokens each).

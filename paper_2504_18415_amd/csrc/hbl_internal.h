@@ -106,8 +106,8 @@ inline int decode_split_k(int64_t T, int64_t K, int64_t N) {
     return sk;
 }
 
-// Layout of the forward workspace: int8 codes [T,K] | float s_dequant [T] | int32 code_sum [T], and for
-// T <= 64: | int32 partial [split_k][T][N].
+// Layout of the forward workspace: codes (one byte per code [T,K], or the record image) | float s_dequant [T],
+// and | int32 partial [split_k][T][N] for T <= 64 or a split K range.
 // K split of the fp6 x fp4 prefill GEMM at mid-size batches: between 65 tokens and about a thousand a long-K
 // projection has too few output tiles (128 x 128) to give most CUs a workgroup, so the K range is cut until about
 // 256 workgroups exist, each keeping at least 8 K-blocks of 128; the int32 partial tiles then take one more launch.
@@ -124,7 +124,6 @@ inline int prefill_split_k(int64_t T, int64_t K, int64_t N) {
 struct Workspace {
     int8_t* codes;
     float* s_dequant;
-    int32_t* code_sum;
     int32_t* partial;
     size_t bytes;
 };
@@ -138,8 +137,6 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
     }
     w.s_dequant = reinterpret_cast<float*>(static_cast<char*>(base) + off);
     off += round_up(static_cast<size_t>(T) * sizeof(float), 256);
-    w.code_sum = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
-    off += round_up(static_cast<size_t>(T) * sizeof(int32_t), 256);
     w.partial = nullptr;
     const int split = T <= 64 ? decode_split_k(T, K, N) : prefill_split_k(T, K, N);
     if (T <= 64 || split > 1) {
@@ -180,12 +177,11 @@ constexpr int kTileAuto = -1, kTileSquare = 0 /*256 x 256*/, kTileSmall = 1 /*12
 // GEMM + epilogue. If acc_out != nullptr the raw int32 accumulators are written
 // (no scales, no code_sum needed); otherwise y (bf16) is written.
 int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,
-                        const float* s_dequant, const int32_t* code_sum, const float* w_scales,
+                        const float* s_dequant, const float* w_scales,
                         int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, int32_t* splitk_partial,
                         hipStream_t stream, int tile = kTileAuto);
 
-// GEMM + epilogue on the fp6 x fp4 matrix-core path: codes as bf6 records, weights from the second
-// packed form; exact, INT4 activations only.
+// GEMM + epilogue on the fp6 x fp4 matrix-core path: codes as bf6 records; exact, INT4 activations only.
 // acc_out != nullptr: the raw accumulators as int32 [T, N] instead of y.
 int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, const void* packed, int64_t N,
                              const float* s_dequant, const float* w_scales, int64_t n_scale_groups, void* y_bf16,
@@ -219,9 +215,8 @@ int launch_quant_grouped(const QuantGroupArgs& args, int bits, int x_dtype, hipS
 
 struct DecodeProblem {
     const int8_t* codes;       // [T, K] stored as code + code_offset
-    const uint32_t* packed;    // int8-path weight tiles
+    const uint32_t* packed;    // weight tiles
     const float* s_dequant;    // [T]
-    const int32_t* code_sum;   // [T]
     const int32_t* w_row_sum;  // [N]
     const float* w_scales;     // [groups]
     uint16_t* y;               // [T, N] bf16
@@ -247,11 +242,10 @@ int decode_plan_for_tests(DecodeArgs& args, int* wgs, int* red_wgs);
 // by the split-K pair of launch_ternary_gemm.
 bool decode_stream_preferred(int64_t T, int64_t K, int64_t N);
 
-// Packed weight buffer: N*K/4 bytes of 2-bit tiles for the int8 matrix-core path, N int32 row sums of
-// the ternary codes, then N*K/4 bytes of 2-bit tiles in the form the fp6 x fp4 path reads.
+// Packed weight buffer: N*K/4 bytes of 2-bit tiles (one form, read by every GEMM kernel), then N int32 row sums
+// of the ternary codes.
 inline size_t packed_tile_bytes(int64_t N, int64_t K) { return (size_t)N * (size_t)K / 4; }
-inline size_t packed_f4_offset(int64_t N, int64_t K) { return packed_tile_bytes(N, K) + (size_t)N * sizeof(int32_t); }
-inline size_t packed_total_bytes(int64_t N, int64_t K) { return packed_f4_offset(N, K) + packed_tile_bytes(N, K); }
+inline size_t packed_total_bytes(int64_t N, int64_t K) { return packed_tile_bytes(N, K) + (size_t)N * sizeof(int32_t); }
 
 int launch_ternarize(const float* W, int64_t count, float eps, int8_t* codes, float* alpha, void* workspace,
                      hipStream_t stream);

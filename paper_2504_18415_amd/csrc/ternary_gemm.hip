@@ -6,11 +6,11 @@
 // tile of W (i = output feature), B a 32-token tile of activation codes (j = token), so a lane of D
 // holds 4 consecutive output features of one token per register quad and can store 8 bytes of bf16.
 //
-// Weights arrive 2-bit packed, 16 weights per dword, already in per-lane operand order (see
-// ternary_setup.hip); a 1 KiB tile (32 features x 128 inputs) is one 16-byte read per lane, and
-// shift+and expands it into bytes {0,1,2} = code+1.  The matrix cores therefore compute sum_k q*(c+1); the exact correction
-// sum_k q[t][k] (the per-token code sum written by the quantiser kernel) is subtracted in the
-// epilogue, all in int32.  Both operands are staged through LDS with direct global->LDS 16-byte
+// Weights arrive 2-bit packed (sign / magnitude pairs, 16 weights per dword, per-lane operand order: see
+// ternary_setup.hip); a 1 KiB tile (32 features x 128 inputs) is one 16-byte read per lane, and 15 vector-ALU
+// instructions expand a dword into four registers of signed bytes {-1, 0, +1} (gemm_common.h).  The only
+// correction left is for an offset on the stored codes (INT4 codes travel as q + 8): offset * sum_k c[o][k],
+// removed in the epilogue in int32.  Both operands are staged through LDS with direct global->LDS 16-byte
 // loads, NSTAGE deep: codes into an XOR-swizzled [token][128 B] layout, weights tile by tile.
 #include <atomic>
 #include <type_traits>
@@ -22,23 +22,6 @@ namespace {
 
 using namespace gemm;
 typedef int v16i __attribute__((ext_vector_type(16)));
-
-// Expand one packed dword into the four operand registers of a lane.
-template <bool SUBTRACT_ONE>
-__device__ __forceinline__ v4i expand(uint32_t p) {
-    v4i r;
-    r[0] = (int)(p & 0x03030303u);
-    r[1] = (int)((p >> 2) & 0x03030303u);
-    r[2] = (int)((p >> 4) & 0x03030303u);
-    r[3] = (int)((p >> 6) & 0x03030303u);
-    if constexpr (SUBTRACT_ONE) {
-        // bytes {0,1,2} -> {-1,0,1}: set bit 7 so the per-byte decrement cannot borrow, then clear it
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            r[j] = (int)((((uint32_t)r[j] | 0x80808080u) - 0x01010101u) ^ 0x80808080u);
-    }
-    return r;
-}
 
 // OCC = waves per SIMD the register budget must allow (2: two workgroups of 4 waves share a CU).
 template <int WAVES_N, int WAVES_T, int TN, int TT, int NSTAGE, bool RAW, bool SPLIT, int OCC>
@@ -142,11 +125,12 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    // LDS read offsets: token row = tile*32 + (lane & 31), chunk = 2*ks + (lane >> 5), swizzled by (row/2) % 8
+    // LDS read offsets: token row = tile*32 + (lane & 31), the 16-byte chunk that matches packed dword ks of the
+    // weight tile for this lane half, swizzled by (row/2) % 8
     int xoff[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-        xoff[ks] = (wt * TT * 32 + (lane & 31)) * kBK + (((2 * ks + (lane >> 5)) ^ ((lane >> 1) & 7)) << 4);
+        xoff[ks] = (wt * TT * 32 + (lane & 31)) * kBK + ((code_chunk_of_dword(ks, lane >> 5) ^ ((lane >> 1) & 7)) << 4);
     const int woff = XBYTES + wn * TN * 1024 + lane * 16;
 
     // Register pipeline.  With one or two waves per SIMD, whatever a wave issues between two MFMAs is
@@ -157,22 +141,24 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
     v4i wpk[TN];      // packed weights of the current stage (reloaded for the next one in its last K-step)
     v4i xop[2][TT];   // code operands of the current / next K-step
     v4i wop[2][TN];   // expanded weight operands of the current / next K-step
+    uint32_t wtmp[TN][4];   // the four groups of weight bytes of the dword being expanded (gemm_common.h)
     constexpr int NMF = TN * TT;                 // MFMAs per K-step
-    constexpr int EOPS = RAW ? 19 : 7;           // VALU instructions to expand one packed dword
-    // one VALU instruction of the expansion of wpk[wbuf][i][ks] into wop[obuf][i]
+    constexpr int EOPS = 15;                     // VALU instructions to expand one packed dword
+    // one VALU instruction of the expansion of wpk[i][ks] into wop[obuf][i]: 7 to separate the four groups of
+    // (magnitude, sign) pairs, 4 look-ups to signed bytes, 4 interleaves into natural feature order
     auto expand_op = [&](int ks, int obuf, int i, int op) {
         const uint32_t p = (uint32_t)wpk[i][ks];
-        if (op == 0) wop[obuf][i][0] = (int)(p & 0x03030303u);
+        if (op == 0) wtmp[i][0] = p & 0x05050505u;
         else if (op <= 6) {
-            const int r = (op + 1) / 2;
-            if (op & 1) wop[obuf][i][r] = (int)(p >> (2 * r));
-            else wop[obuf][i][r] = (int)((uint32_t)wop[obuf][i][r] & 0x03030303u);
+            const int g = (op + 1) / 2;               // groups 1..3: shift, then mask
+            if (op & 1) wtmp[i][g] = p >> (g == 1 ? 1 : g == 2 ? 4 : 5);
+            else wtmp[i][g] &= 0x05050505u;
+        } else if (op <= 10) {
+            wtmp[i][op - 7] = weight_bytes(wtmp[i][op - 7]);
         } else {
-            // RAW only: bytes {0,1,2} -> {-1,0,1}, three instructions per register
-            const int r = (op - 7) / 3, st = (op - 7) % 3;
-            uint32_t v = (uint32_t)wop[obuf][i][r];
-            v = st == 0 ? (v | 0x80808080u) : st == 1 ? (v - 0x01010101u) : (v ^ 0x80808080u);
-            wop[obuf][i][r] = (int)v;
+            // groups: 0 = b even, 1 = a even, 2 = b odd, 3 = a odd; a = features 0..7, b = features 8..15
+            const int r = op - 11;
+            wop[obuf][i][r] = (int)weight_interleave(wtmp[i][r < 2 ? 3 : 2], wtmp[i][r < 2 ? 1 : 0], r & 1);
         }
     };
     auto expand_all = [&](int ks, int obuf) {
@@ -315,7 +301,6 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
                 const int j = jg + jj;
                 const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
                 const float sd = t < a.T ? a.s_dequant[t] : 0.0f;
-                const int sx = t < a.T ? a.code_sum[t] : 0;
 #pragma unroll
                 for (int i = 0; i < TN; ++i) {
                     __builtin_amdgcn_sched_barrier(0);   // one accumulator tile at a time (register pressure)
@@ -332,7 +317,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
                         if (a.code_offset != 0 && in_n) ws = *reinterpret_cast<const v4i*>(a.w_row_sum + n);
                         *reinterpret_cast<uint2*>(obuf + (jj * 32 + (lane & 31)) * ROWB +
                                                   (i * 32 + 8 * g + 4 * (lane >> 5)) * 2) =
-                            dequant_quad_sums(o, sx, sd, alpha, a.code_offset, ws, a.K);
+                            dequant_quad_sums(o, sd, alpha, a.code_offset, ws);
                     }
                 }
             }
@@ -369,8 +354,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs a) {
             continue;
         }
         *reinterpret_cast<uint2*>(a.y + (size_t)t * a.N + n) =
-            dequant_quad(sum, a.code_sum ? a.code_sum[t] : 0, a.s_dequant[t], a.w_scales[n / a.rows_per_group], a.code_offset,
-                         a.w_row_sum + n, a.K);
+            dequant_quad(sum, a.s_dequant[t], a.w_scales[n / a.rows_per_group], a.code_offset, a.w_row_sum + n);
     }
 }
 
@@ -440,7 +424,7 @@ int choose(const GemmArgs& a, hipStream_t stream, int tile) {
 }  // namespace
 
 int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t K, const void* packed, int64_t N,
-                        const float* s_dequant, const int32_t* code_sum, const float* w_scales,
+                        const float* s_dequant, const float* w_scales,
                         int64_t n_scale_groups, void* y_bf16, int32_t* acc_out, int32_t* splitk_partial,
                         hipStream_t stream, int tile) {
     if (T == 0) return HBL_OK;
@@ -448,7 +432,6 @@ int launch_ternary_gemm(const int8_t* codes, int code_offset, int64_t T, int64_t
     a.codes = codes;
     a.packed = static_cast<const uint32_t*>(packed);
     a.s_dequant = s_dequant;
-    a.code_sum = code_sum;
     a.w_row_sum = reinterpret_cast<const int32_t*>(static_cast<const char*>(packed) + packed_tile_bytes(N, K));
     a.code_offset = code_offset;
     a.w_scales = w_scales;

@@ -12,8 +12,8 @@
 //   - activation codes arrive as the record image of code_records.h: 6 bits per code, a token row of a
 //     stage is 96 bytes, a 128-token panel of a stage one contiguous 12 KiB block that is copied to LDS
 //     as it is (twelve 1 KiB pieces), and an operand is one 16-byte + one 8-byte LDS read;
-//   - weights come from the second packed form (sign / magnitude bit pairs): two AND and one shift
-//     turn a packed dword into two operand registers of eight fp4 values each.
+//   - the packed weights (sign / magnitude bit pairs) become fp4 operands with two AND and one shift per
+//     dword: two operand registers of eight fp4 values each.
 #include <atomic>
 #include <type_traits>
 
@@ -355,7 +355,7 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
     if (T == 0) return HBL_OK;
     GemmArgs a = {};
     a.codes = code_records;
-    a.packed = reinterpret_cast<const uint32_t*>(static_cast<const char*>(packed) + packed_f4_offset(N, K));
+    a.packed = static_cast<const uint32_t*>(packed);
     a.s_dequant = s_dequant;
     a.w_scales = w_scales;
     a.y = static_cast<uint16_t*>(y_bf16);
@@ -366,8 +366,7 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
     a.rows_per_group = n_scale_groups > 0 ? (int)(N / n_scale_groups) : (int)N;
     a.split_k = splitk_partial ? prefill_split_k(T, K, N) : 1;
     a.partial = splitk_partial;
-    a.code_sum = nullptr;   // signed operands: no correction terms
-    a.code_offset = 0;
+    a.code_offset = 0;      // signed operands: no correction terms
     // Workgroup tile: 64 K outputs either way (the 256 accumulator registers of four waves).  512 features x 128
     // tokens moves 32 KB per 128-feature stage through L2 and LDS (16 KB of codes + 16 KB of packed weights) against
     // 40 KB for 256 x 256 (32 + 8): measured 4 % faster on the GEMM at N = 4096 and 12288, equal at N = 32768.  The

@@ -1,17 +1,21 @@
 // Weight set-up kernels: the per-tensor absmean ternary quantiser (Eq. 1-2) and the
 // 2-bit packing of its codes into the streaming layout the GEMM kernels read.
 //
-// Packed layout.  The [N, K] code matrix is cut into tiles of 32 output rows x 128
-// input features, stored tile after tile with the K direction fastest:
+// Packed layout (one form, 2 bits per weight, read by every GEMM kernel).  The [N, K] code matrix is cut into
+// tiles of 32 output rows x 128 input features, stored tile after tile with the K direction fastest:
 //   tile(nt, kb) at byte ((nt * (K/128) + kb) * 1024), nt = o / 32, kb = k / 128.
-// A tile is 64 lanes x 4 dwords (lane-major, 16 bytes per lane).  Lane l, dword s
-// holds the 16 weights of row 32*nt + (l & 31) at features
-//   k = 128*kb + 32*s + 16*(l >> 5) + i,  i = 0..15,
-// i.e. exactly one lane's share of a 32x32x32 int8 matrix-core operand for K-step s.
-// Weight i = 4*j + b of that group sits at bits [8*b + 2*j, 8*b + 2*j + 1] as code+1,
-// so that (dword >> 2*j) & 0x03030303 is operand register j (bytes b = 0..3).
-// After the N*K/4 bytes of tiles come N int32 row sums sum_k c[o][k], then the second packed form
-// (pack_f4_kernel below).
+// A tile is 64 lanes x 4 dwords (lane-major, 16 bytes per lane).  Lane l, dword j holds the 16 weights of
+// row 32*nt + (l & 31) at features
+//   k = 128*kb + 64*(j >> 1) + 32*(l >> 5) + 16*(j & 1) + i,  i = 0..15,
+// i.e. dwords 2s, 2s+1 are one lane's share of the A operand of a 32x32x64 fp6/fp4 MFMA for K-step s, and
+// dword j one lane's share of a 32x32x32 int8 MFMA operand.  A weight is a (sign, magnitude) bit pair:
+// weight i < 8 has its magnitude at bit 4*i + 1 and its sign at bit 4*i + 3, weight i >= 8 its magnitude at
+// bit 4*(i-8) and its sign at bit 4*(i-8) + 2.  Then
+//   p & 0xAAAAAAAA  and  (p << 1) & 0xAAAAAAAA
+// are eight fp4 (e2m1) values each (+-1.0 = s010, 0 = 0000), and (p >> {0,1,4,5}) & 0x05050505 are four
+// weights each as byte values {0, 1, 5} that one byte-permute look-up turns into int8 {0, +1, -1}.
+// After the N*K/4 bytes of tiles come N int32 row sums sum_k c[o][k] (the epilogue of the int8 path needs
+// them when activation codes are stored with an offset).
 #include "hbl_internal.h"
 
 namespace hbl {
@@ -71,72 +75,44 @@ __global__ __launch_bounds__(256) void ternarize_kernel(const float* __restrict_
     }
 }
 
-__global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ codes, int64_t N, int64_t K,
-                                                   uint32_t* __restrict__ packed) {
+// dword d of the packed stream -> (row, first feature) of its 16 weights
+__device__ __forceinline__ void packed_dword_origin(int64_t d, int64_t K, int64_t* row, int64_t* k0) {
     const int64_t kblocks = K / 128;
-    const int64_t total = (N / 32) * kblocks * 256;  // dwords
-    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (d >= total) return;
-    const int s = (int)(d & 3);
-    const int lane = (int)((d >> 2) & 63);
-    const int64_t tile = d >> 8;
-    const int64_t kb = tile % kblocks, nt = tile / kblocks;
-    const int64_t row = nt * 32 + (lane & 31);
-    const int64_t k0 = kb * 128 + s * 32 + (lane >> 5) * 16;
-    const uint4 raw = *reinterpret_cast<const uint4*>(codes + row * K + k0);
-    const int8_t* c = reinterpret_cast<const int8_t*>(&raw);
-    uint32_t out = 0;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int j = i >> 2, b = i & 3;
-        out |= (uint32_t)((int)c[i] + 1) << (8 * b + 2 * j);
-    }
-    packed[d] = out;
-}
-
-__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict__ packed, int64_t N, int64_t K,
-                                                     int8_t* __restrict__ codes) {
-    const int64_t kblocks = K / 128;
-    const int64_t total = (N / 32) * kblocks * 256;
-    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (d >= total) return;
-    const int s = (int)(d & 3);
-    const int lane = (int)((d >> 2) & 63);
-    const int64_t tile = d >> 8;
-    const int64_t kb = tile % kblocks, nt = tile / kblocks;
-    const int64_t row = nt * 32 + (lane & 31);
-    const int64_t k0 = kb * 128 + s * 32 + (lane >> 5) * 16;
-    const uint32_t p = packed[d];
-    uint4 raw;
-    int8_t* c = reinterpret_cast<int8_t*>(&raw);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int j = i >> 2, b = i & 3;
-        c[i] = (int8_t)((int)((p >> (8 * b + 2 * j)) & 3u) - 1);
-    }
-    *reinterpret_cast<uint4*>(codes + row * K + k0) = raw;
-}
-
-// Second packed form, for the fp6 x fp4 matrix-core path (INT4 activations at prefill sizes): the same
-// 1 KiB tiles of 32 rows x 128 features and the same lane order, but lane l's 16 bytes are
-//   dword 2*s + d (s = 64-feature K-step 0..1, d = 0..1): the 16 weights of row 32*nt + (l & 31) at
-//   features 128*kb + 64*s + 32*(l >> 5) + 16*d + i, i = 0..15,
-// stored sign/magnitude: weight i < 8 has its magnitude at bit 4*i + 1 and its sign at bit 4*i + 3,
-// weight i >= 8 its magnitude at bit 4*(i-8) and its sign at bit 4*(i-8) + 2.  Then
-//   p & 0xAAAAAAAA  and  (p << 1) & 0xAAAAAAAA
-// are eight fp4 (e2m1) values each (+-1.0 = s010, 0 = 0000): operand registers of the 32x32x64 MFMA.
-__global__ __launch_bounds__(256) void pack_f4_kernel(const int8_t* __restrict__ codes, int64_t N, int64_t K,
-                                                      uint32_t* __restrict__ packed) {
-    const int64_t kblocks = K / 128;
-    const int64_t total = (N / 32) * kblocks * 256;  // dwords
-    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (d >= total) return;
     const int dd = (int)(d & 3);
     const int lane = (int)((d >> 2) & 63);
     const int64_t tile = d >> 8;
     const int64_t kb = tile % kblocks, nt = tile / kblocks;
-    const int64_t row = nt * 32 + (lane & 31);
-    const int64_t k0 = kb * 128 + (dd >> 1) * 64 + (lane >> 5) * 32 + (dd & 1) * 16;
+    *row = nt * 32 + (lane & 31);
+    *k0 = kb * 128 + (dd >> 1) * 64 + (lane >> 5) * 32 + (dd & 1) * 16;
+}
+
+__global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict__ packed, int64_t N, int64_t K,
+                                                     int8_t* __restrict__ codes) {
+    const int64_t total = (N / 32) * (K / 128) * 256;
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d >= total) return;
+    int64_t row, k0;
+    packed_dword_origin(d, K, &row, &k0);
+    const uint32_t p = packed[d];
+    uint4 raw;
+    int8_t* c = reinterpret_cast<int8_t*>(&raw);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+        const int ma = (p >> (4 * n + 1)) & 1, sa = (p >> (4 * n + 3)) & 1;
+        const int mb = (p >> (4 * n)) & 1, sb = (p >> (4 * n + 2)) & 1;
+        c[n] = (int8_t)(sa ? -ma : ma);
+        c[8 + n] = (int8_t)(sb ? -mb : mb);
+    }
+    *reinterpret_cast<uint4*>(codes + row * K + k0) = raw;
+}
+
+__global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ codes, int64_t N, int64_t K,
+                                                      uint32_t* __restrict__ packed) {
+    const int64_t total = (N / 32) * (K / 128) * 256;  // dwords
+    const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (d >= total) return;
+    int64_t row, k0;
+    packed_dword_origin(d, K, &row, &k0);
     const uint4 raw = *reinterpret_cast<const uint4*>(codes + row * K + k0);
     const int8_t* c = reinterpret_cast<const int8_t*>(&raw);
     uint32_t out = 0;
@@ -151,8 +127,7 @@ __global__ __launch_bounds__(256) void pack_f4_kernel(const int8_t* __restrict__
     packed[d] = out;
 }
 
-// Row sums of the ternary codes, sum_k c[o][k], one wave per output row: the GEMM epilogue needs them
-// when activation codes are stored with an offset.
+// Row sums of the ternary codes, sum_k c[o][k], one wave per output row.
 __global__ __launch_bounds__(256) void row_sum_kernel(const int8_t* __restrict__ codes, int64_t N, int64_t K,
                                                       int32_t* __restrict__ row_sum) {
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -195,15 +170,11 @@ int launch_ternarize(const float* W, int64_t count, float eps, int8_t* codes, fl
 int launch_pack(const int8_t* codes, int64_t N, int64_t K, void* packed, hipStream_t stream) {
     const int64_t total = (N / 32) * (K / 128) * 256;
     launch_kernel("pack_kernel", pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
-                       static_cast<uint32_t*>(packed));
+                  static_cast<uint32_t*>(packed));
     int rc = after_launch();
     if (rc != HBL_OK) return rc;
     int32_t* row_sum = reinterpret_cast<int32_t*>(static_cast<char*>(packed) + packed_tile_bytes(N, K));
     launch_kernel("row_sum_kernel", row_sum_kernel, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, stream, codes, N, K, row_sum);
-    rc = after_launch();
-    if (rc != HBL_OK) return rc;
-    launch_kernel("pack_f4_kernel", pack_f4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, codes, N, K,
-                       reinterpret_cast<uint32_t*>(static_cast<char*>(packed) + packed_f4_offset(N, K)));
     return after_launch();
 }
 

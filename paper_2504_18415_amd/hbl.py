@@ -170,7 +170,7 @@ def packed_bytes(N: int, K: int) -> int:
 
 
 def pack_ternary_2bit(codes: torch.Tensor) -> torch.Tensor:
-    """codes int8 [N,K] in {-1,0,1} -> opaque packed uint8 [N*K/2 + 4*N]."""
+    """codes int8 [N,K] in {-1,0,1} -> opaque packed uint8 [N*K/4 + 4*N] (2 bits per weight + row sums)."""
     _dev_check(codes)
     N, K = codes.shape
     packed = torch.empty(packed_bytes(N, K), dtype=torch.uint8, device=codes.device)

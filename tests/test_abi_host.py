@@ -46,11 +46,11 @@ def test_status_text(L):
 
 
 def test_size_queries(L):
-    assert L.hbl_packed_bytes(4096, 16384) == 4096 * 16384 // 2 + 4 * 4096   # two 2-bit forms + int32 row sums
-    assert L.hbl_packed_bytes(256, 256) == 32768 + 1024
+    assert L.hbl_packed_bytes(4096, 16384) == 4096 * 16384 // 4 + 4 * 4096   # 2 bits per weight + int32 row sums
+    assert L.hbl_packed_bytes(256, 256) == 16384 + 1024
     ws = L.hbl_workspace_bytes(8192, 16384, 4096, 4)
-    assert ws >= 8192 * 16384 + 8 * 8192 and ws % 256 == 0
-    assert L.hbl_workspace_bytes(17, 256, 256, 8) >= 17 * 256 + 8 * 17
+    assert ws >= 8192 * 16384 + 4 * 8192 and ws % 256 == 0
+    assert L.hbl_workspace_bytes(17, 256, 256, 8) >= 17 * 256 + 4 * 17
     assert L.hbl_workspace_bytes(17, 256, 0, 8) == 256 and L.hbl_workspace_bytes(17, 256, -32, 8) == 256
     # a mid-size batch on a long K brings room for the split-K partial tiles (4 slices of [T, N] int32 here)
     assert L.hbl_workspace_bytes(256, 16384, 4096, 4) >= 256 * 16384 + 4 * 256 * 4096 * 4
