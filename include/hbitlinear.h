@@ -144,11 +144,12 @@ int hbl_plain_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K
  * The forward call for callers that cannot allocate device memory or carry a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation and the same
  * kernels as hbl_hbitlinear_forward (hadamard != 0) / hbl_plain_bitlinear_forward (hadamard == 0), with
- * bit-identical output; the intermediates (activation codes, per-token scale and code sum, int32 partial
- * tiles of a split K range) live in a 13 MiB array in the library's own device image, one copy per GPU,
- * held until the process ends.  The call allocates nothing and frees nothing.
- *   Limits: T <= 64 (decode batches) and hbl_workspace_bytes(T, K, N, bits) <= 13 MiB, which covers every
- *   K <= 16384 with N <= 32768 at T = 64; beyond them HBL_E_SCRATCH and nothing is launched.
+ * bit-identical output; the intermediates (activation codes, per-token scales) live in a 2 MiB array in the
+ * library's own device image, one copy per GPU, held until the process ends.  There is no room for partial
+ * tiles, so a K range is never split over workgroups (integer sums: same result, possibly a slower launch on
+ * long-K, few-row shapes).  The call allocates nothing and frees nothing.
+ *   Limit: T <= 64 (decode batches; every K and N the library accepts fits); beyond it HBL_E_SCRATCH and
+ *   nothing is launched.
  *   Every call on a GPU shares that GPU's array, on whatever stream: two calls that may run at the same
  *   time on one GPU race (calls on one stream are ordered and safe).  Nothing in the array has to start
  *   at zero: a call writes every byte it later reads.

@@ -22,10 +22,11 @@ thread_local TraceState g_trace;
 LaunchTrace* current_trace() { return g_trace.open ? &g_trace.view : nullptr; }
 
 // Scratch of hbl_bitlinear_forward_small, the entry point that allocates nothing: it plays the part the
-// caller's workspace plays in the other forward calls (activation codes, per-token scale and code sum, int32
-// partial tiles of a split K range).  One copy per GPU, held until the process ends.  In host code the array's
-// name is only a handle for hipGetSymbolAddress: the device address, asked once per device, is what is passed on.
-constexpr size_t kSmallScratchBytes = (size_t)13 << 20;   // largest hbl_workspace_bytes(64, K, N) over K <= 16384, N <= 32768: 12.94 MiB
+// caller's workspace plays in the other forward calls (activation codes and per-token scales; no room for partial
+// tiles, so the kernels keep every K range inside one workgroup).  One copy per GPU, held until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the device address, asked once per
+// device, is what is passed on.
+constexpr size_t kSmallScratchBytes = (size_t)2 << 20;   // codes of 64 tokens x 16384 features: 1.5 MiB as records
 static __device__ __align__(256) unsigned char scratch[kSmallScratchBytes];
 
 namespace {
@@ -56,6 +57,9 @@ int note_hip_error(hipError_t e) {
 
 namespace {
 
+// INT4 codes on the int8 path travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs.
+int small_code_offset(int bits) { return bits == 4 ? 8 : 0; }
+
 int check_gemm_shape(int64_t T, int64_t K, int64_t N, bool hadamard) {
     if (T < 0 || T > (1 << 24)) return HBL_E_SHAPE;
     if (K < 128 || K > 16384 || (K % 128) != 0) return HBL_E_SHAPE;
@@ -82,53 +86,53 @@ int check_forward_args(const void* x, int x_dtype, int64_t T, int64_t K, const v
     return HBL_OK;
 }
 
-void fill_decode_problem(DecodeProblem& dp, const Workspace& ws, int32_t* partial, int64_t T, int64_t K,
-                         const void* Wq_packed, int64_t N, const float* w_scales, int64_t groups, int code_offset,
-                         void* y) {
+void fill_decode_problem(DecodeProblem& dp, const Workspace& ws, int64_t T, int64_t K, const void* Wq_packed,
+                         int64_t N, const float* w_scales, int64_t groups, int bits, void* y) {
     dp.codes = ws.codes;
     dp.packed = static_cast<const uint32_t*>(Wq_packed);
     dp.s_dequant = ws.s_dequant;
     dp.w_row_sum = reinterpret_cast<const int32_t*>(static_cast<const char*>(Wq_packed) + packed_tile_bytes(N, K));
     dp.w_scales = w_scales;
     dp.y = static_cast<uint16_t*>(y);
-    dp.partial = partial;
+    dp.partial = ws.partial;
     dp.T = (int)T;
     dp.K = (int)K;
     dp.N = (int)N;
     dp.rows_per_group = (int)(N / groups);
-    dp.code_offset = code_offset;
+    dp.f6 = bf6_path_supported(K, bits) ? 1 : 0;
+    dp.code_offset = dp.f6 ? 0 : small_code_offset(bits);
 }
+
+// Form of the codes between the two launches of a forward call.
+int code_form_for(int64_t K, int bits) { return bf6_path_supported(K, bits) ? kCodesBf6 : small_code_offset(bits); }
 
 int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_packed, int64_t N,
             const float* w_scales, int64_t groups, int bits, float eps, void* y, void* workspace,
             size_t workspace_bytes, void* stream, bool hadamard, const float* ln_gain = nullptr,
-            float ln_eps = 0.0f) {
+            float ln_eps = 0.0f, bool with_partial = true) {
     int rc = check_forward_args(x, x_dtype, T, K, Wq_packed, N, w_scales, groups, bits, y, workspace, hadamard);
     if (rc != HBL_OK) return rc;
     if (T == 0) return HBL_OK;
-    if (workspace_bytes < hbl_workspace_bytes(T, K, N, bits)) return HBL_E_WORKSPACE;
+    if (workspace_bytes < carve_workspace(nullptr, T, K, N, with_partial).bytes) return HBL_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const Workspace ws = carve_workspace(workspace, T, K, N);
-    // INT4 at prefill sizes: bf6 code records and the fp6 x fp4 matrix cores (exact, twice the int8
-    // MFMA rate).
-    if (bf6_path_supported(T, K, bits, hadamard)) {
-        rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, kCodesBf6, s,
-                               ln_gain, ln_eps);
-        if (rc != HBL_OK) return rc;
-        return launch_ternary_gemm_f6f4(ws.codes, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, s, ws.partial);
-    }
-    // otherwise INT4 codes travel as code + 8 (bytes 0..15): same results, fewer toggling multiplier inputs
-    const int code_offset = bits == 4 ? 8 : 0;
-    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, code_offset, s,
-                           ln_gain, ln_eps);
+    const Workspace ws = carve_workspace(workspace, T, K, N, with_partial);
+    const int code_form = code_form_for(K, bits);
+    rc = launch_fwht_quant(x, x_dtype, T, K, bits, eps, hadamard, ws.codes, ws.s_dequant, nullptr, code_form, s, ln_gain,
+                           ln_eps);
     if (rc != HBL_OK) return rc;
-    if (decode_stream_preferred(T, K, N)) {   // a handful of tokens: one weight-streaming launch
+    // a small batch: the weight-streaming kernel (always on the record path; on the byte path unless the plain
+    // split-K pair suits the shape better)
+    if (T <= 64 && (code_form == kCodesBf6 || decode_stream_preferred(T, K, N))) {
         DecodeArgs da = {};
         da.n = 1;
-        fill_decode_problem(da.p[0], ws, nullptr, T, K, Wq_packed, N, w_scales, groups, code_offset, y);
+        fill_decode_problem(da.p[0], ws, T, K, Wq_packed, N, w_scales, groups, bits, y);
+        if (code_form != kCodesBf6) da.p[0].partial = nullptr;   // byte path: the streaming form only
         return launch_decode_gemm(da, s);
     }
-    return launch_ternary_gemm(ws.codes, code_offset, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, nullptr,
+    // INT4 at prefill sizes: bf6 code records and the fp6 x fp4 matrix cores (exact, twice the int8 MFMA rate)
+    if (code_form == kCodesBf6)
+        return launch_ternary_gemm_f6f4(ws.codes, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, s, ws.partial);
+    return launch_ternary_gemm(ws.codes, code_form, T, K, Wq_packed, N, ws.s_dequant, w_scales, groups, y, nullptr,
                                ws.partial, s);
 }
 
@@ -136,9 +140,7 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
 // for the largest K split they may choose) and for the stand-alone forward call.
 size_t group_region_bytes(const hbl_problem& q) {
     if (q.T <= 0 || q.K <= 0 || q.N <= 0) return 256;
-    size_t b = carve_workspace(nullptr, q.T, q.K, q.N).bytes;
-    if (q.T <= 64) b += round_up((size_t)kMaxDecodeSplit * q.T * q.N * sizeof(int32_t), 256);
-    return b;
+    return carve_workspace(nullptr, q.T, q.K, q.N).bytes;
 }
 
 }  // namespace
@@ -158,7 +160,7 @@ const char* hbl_strerror(int status) {
         case HBL_E_WORKSPACE: return "workspace too small";
         case HBL_E_HIP: return "a HIP call failed (see hbl_last_hip_error)";
         case HBL_E_ALIGN: return "pointer not sufficiently aligned";
-        case HBL_E_SCRATCH: return "problem too large for the static scratch of the allocation-free entry point (T <= 64, hbl_workspace_bytes <= 13 MiB)";
+        case HBL_E_SCRATCH: return "problem too large for the static scratch of the allocation-free entry point (T <= 64)";
         default: return "unknown status";
     }
 }
@@ -228,12 +230,12 @@ int hbl_bitlinear_forward_small(const void* x, int x_dtype, int64_t T, int64_t K
                                 reinterpret_cast<const void*>(uintptr_t{256}), hadamard != 0);
     if (rc != HBL_OK) return rc;
     if (T == 0) return HBL_OK;
-    if (T > 64 || hbl_workspace_bytes(T, K, N, bits) > kSmallScratchBytes) return HBL_E_SCRATCH;
+    if (T > 64 || carve_workspace(nullptr, T, K, N, false).bytes > kSmallScratchBytes) return HBL_E_SCRATCH;
     void* ws = nullptr;
     rc = scratch_of_current_device(&ws);
     if (rc != HBL_OK) return rc;
     return forward(x, x_dtype, T, K, Wq_packed, N, w_scales, n_scale_groups, bits, eps, y, ws, kSmallScratchBytes,
-                   stream, hadamard != 0);
+                   stream, hadamard != 0, nullptr, 0.0f, false);
 }
 
 size_t hbl_grouped_workspace_bytes(const hbl_problem* problems, int n_problems) {
@@ -284,8 +286,6 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
         const size_t region = group_region_bytes(q);
         if (q.T > 0) {
             const Workspace ws = carve_workspace(base, q.T, q.K, q.N);
-            int32_t* partial = reinterpret_cast<int32_t*>(base + carve_workspace(nullptr, q.T, q.K, q.N).bytes);
-            const int code_offset = q.bits == 4 ? 8 : 0;   // INT4 codes travel as code + 8 (bytes 0..15)
             QuantProblem& qp = qa.p[qa.n++];
             qp.x = q.x;
             qp.codes = ws.codes;
@@ -294,13 +294,12 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
             qp.T = (int)q.T;
             qp.K = (int)q.K;
             qp.hadamard = q.hadamard != 0;
-            qp.code_offset = code_offset;
+            qp.code_offset = code_form_for(q.K, q.bits);
             qp.row_begin = rows;
             qp.ln_gain = q.ln_gain;
             qp.ln_eps = q.ln_eps;
             rows += (int)q.T;
-            fill_decode_problem(da.p[da.n++], ws, partial, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups,
-                                code_offset, q.y);
+            fill_decode_problem(da.p[da.n++], ws, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups, q.bits, q.y);
         }
         base += region;
     }

@@ -4,16 +4,20 @@
 //
 // A wave owns one 32-row weight tile at a time and walks its K range tile by tile (1 KiB of packed
 // weights = 32 rows x 128 features).  Weights and activation codes both arrive by direct global->LDS
-// copies, D = 4 stages deep per wave; per stage a wave expands the 16 packed bytes of each lane into
-// four int8 operands (signed bytes, as in the large-T kernel) and issues 4 (or 8) 32x32x32 int8 MFMAs.
+// copies, D = 4 stages deep per wave.  Per problem one of two operand paths:
+//  - fp6 x fp4 (INT4 activations, K >= 512): codes from the record image (96 bytes per token and stage),
+//    weights to fp4 with 3 vector-ALU instructions per 16; two 16x16x128 MFMAs per tile for up to 16 tokens,
+//    two 32x32x64 per tile and 32 tokens above that.  fp32 accumulators hold exact integers.
+//  - int8 (INT8 activations, short rows): codes as bytes (128 per token and stage), weights to signed bytes
+//    (15 instructions per 16), four 32x32x32 MFMAs per tile and 32 tokens.
 //
 // Two forms:
-//  - streaming (T <= 16): a wave's code stage is private (8 or 16 rows x 128 B), so the waves never
-//    meet at a barrier.  The K range of one row tile may be split over the 2 or 4 waves of a workgroup;
-//    their int32 accumulators are added through LDS at the end (exact).
+//  - streaming (T <= 16): a wave's code stage is private (8 or 16 rows), so the waves never meet at a
+//    barrier.  The K range of one row tile may be split over the 2 or 4 waves of a workgroup; their
+//    accumulators are added through LDS at the end (exact).
 //  - shared (T <= 64): the four waves take four row tiles over one K range and share the code stage
-//    (32 or 64 rows x 128 B): one barrier per stage.  A K range split over workgroups leaves int32
-//    partial tiles that a second launch adds and dequantises.
+//    (32 or 64 rows): one barrier per stage.  A K range split over workgroups leaves int32 partial tiles that
+//    a second launch adds and dequantises.
 #include <atomic>
 
 #include "gemm_common.h"
@@ -23,6 +27,38 @@ namespace {
 
 using namespace gemm;
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// The 16-byte-per-lane global -> LDS copy of gemm_common.h by the first 48 lanes only: 768 contiguous bytes, eight
+// 96-byte rows of the record image.  (The 12-byte-per-lane form of the instruction strides the LDS side by 16
+// bytes per lane - measured - so it cannot lay down contiguous rows.)  The execution mask is narrowed around
+// the copy inside one asm block and put back.
+__device__ __forceinline__ void lds_dma16_first48(uint32_t lds_addr, const void* base, uint32_t voff) {
+    uint64_t saved;
+    asm volatile(
+        "s_mov_b64 %0, exec\n\ts_bfm_b64 exec, 48, 0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
+        : "=&s"(saved)
+        : "s"(lds_addr), "v"(voff), "s"(base)
+        : "memory", "m0");
+}
+
+// Two packed dwords (32 weights) -> the four fp4 operand registers of a lane.
+__device__ __forceinline__ v8i fp4_operand(uint32_t p0, uint32_t p1) {
+    return v8i{(int)(p0 & 0xAAAAAAAAu), (int)((p0 << 1) & 0xAAAAAAAAu), (int)(p1 & 0xAAAAAAAAu),
+               (int)((p1 << 1) & 0xAAAAAAAAu), 0, 0, 0, 0};
+}
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+// y = bf16((acc * s_d) * alpha) for four consecutive features; acc holds exact integers.
+__device__ __forceinline__ uint2 dequant_quad_f32(float a0, float a1, float a2, float a3, float sd, float alpha) {
+    const bf16x2 lo = __builtin_convertvector((f32x2){(a0 * sd) * alpha, (a1 * sd) * alpha}, bf16x2);
+    const bf16x2 hi = __builtin_convertvector((f32x2){(a2 * sd) * alpha, (a3 * sd) * alpha}, bf16x2);
+    return make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+}
 
 // The problem a workgroup belongs to: the last one whose first workgroup is not beyond it.
 template <typename BeginOf>
@@ -37,22 +73,20 @@ __device__ __forceinline__ DecodeProblem select_problem(const DecodeArgs& args, 
 // NW = waves per workgroup.  Four everywhere except the streaming form on a single long-K problem with few row
 // tiles (W_down alone): there 8 waves share a row tile's K range, which shortens each wave's serial chain of
 // tiles (128 workgroups cannot be made more without narrower row tiles).
-template <bool SHARE, int TT, int RQ, int D, int NW = 4>
-__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(const DecodeArgs args) {
+// F6: the problem's codes are bf6 records and the fp6 x fp4 matrix cores do the work.
+template <bool SHARE, int TT, int RQ, int D, int NW, bool F6>
+__device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w, char* lds) {
     constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;    // token rows of one code stage
-    constexpr int XB = ROWS * kBK;                    // bytes of one code stage
+    constexpr int ROWB = F6 ? kRecordRowBytes : kBK;  // bytes of one token row of a stage
+    constexpr int XB = ROWS * ROWB;                   // bytes of one code stage
     constexpr int XW = SHARE ? XB : NW * XB;          // code bytes per stage in the workgroup
     constexpr int STAGE = XW + NW * 1024;             // + one packed weight tile per wave
-    constexpr int XL = SHARE ? TT : RQ;               // code copies per wave per stage
+    constexpr int XL = SHARE ? TT : RQ;               // code copies per wave per stage (8 rows each)
     constexpr int NACC = TT == 1 ? 2 : TT;
     static_assert(D >= 3 && (ROWS & (ROWS - 1)) == 0, "pipeline depth / row count");
     static_assert(!SHARE || NW == 4, "the shared form is written for four waves");
     static_assert(NW * 4096 <= D * STAGE, "the in-workgroup reduction reuses the stage buffers");
 
-    extern __shared__ __attribute__((aligned(1024))) char lds[];
-
-    const DecodeProblem p = select_problem(args, (int)blockIdx.x, [](const DecodeProblem& q) { return q.wg_begin; });
-    const int w = (int)blockIdx.x - p.wg_begin;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -72,19 +106,29 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
     const int ntc = live ? nt : nt_max;
     const int kb0 = ks * nkb;
 
-    const char* wbase = reinterpret_cast<const char*>(p.packed) + ((size_t)ntc * nkb_total + kb0) * 1024;
+    // packed tiles are stored K-block-major (tile (nt, kb) at (kb * N/32 + nt) KiB): at any moment the waves
+    // of a launch, all at about the same kb, read one window of consecutive addresses
+    const size_t wstride = (size_t)(p.N / 32) * 1024;
+    const char* wbase = reinterpret_cast<const char*>(p.packed) + (size_t)kb0 * wstride + (size_t)ntc * 1024;
     const uint32_t wlane = lane * 16;
-    // code copy m of a stage covers rows 8q..8q+7: lane l -> row 8q + l/8, LDS slot l%8 of that row,
-    // global 16-byte chunk (l%8) ^ ((row/2) % 8); rows past T re-read the last token
-    const char* xbase = reinterpret_cast<const char*>(p.codes) + (size_t)kb0 * kBK;
+    // Code copy m of a stage covers rows 8q..8q+7.
+    //  bytes: lane l -> row 8q + l/8, LDS slot l%8 of that row, global 16-byte chunk (l%8) ^ ((row/2) % 8); rows
+    //         past T re-read the last token;
+    //  records: the rows are 768 contiguous bytes of the stage's block of the record image (rows past T exist
+    //         there and hold finite garbage that is never stored).
+    const char* xbase = reinterpret_cast<const char*>(p.codes) + (size_t)kb0 * (F6 ? kRecordBlockBytes : kBK);
     uint32_t xlane[XL];
 #pragma unroll
     for (int m = 0; m < XL; ++m) {
         const int q = SHARE ? wave + 4 * m : m;
-        const int row = 8 * q + (lane >> 3);
-        const int t = row < p.T ? row : p.T - 1;
-        const int c = (lane & 7) ^ ((row >> 1) & 7);
-        xlane[m] = (uint32_t)t * (uint32_t)p.K + c * 16;
+        if constexpr (F6) {
+            xlane[m] = q * 768 + lane * 16;   // 8 rows of 96 bytes: the first 48 lanes of a 16-byte-per-lane copy
+        } else {
+            const int row = 8 * q + (lane >> 3);
+            const int t = row < p.T ? row : p.T - 1;
+            const int c = (lane & 7) ^ ((row >> 1) & 7);
+            xlane[m] = (uint32_t)t * (uint32_t)p.K + c * 16;
+        }
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
     const uint32_t xarea = SHARE ? 0 : wave * XB;
@@ -94,28 +138,59 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
 #pragma unroll
         for (int m = 0; m < XL; ++m) {
             const int q = SHARE ? wave + 4 * m : m;
-            lds_dma16(lds0 + slot * STAGE + xarea + q * 1024, xbase + (size_t)kb * kBK, xlane[m]);
+            if constexpr (F6) lds_dma16_first48(lds0 + slot * STAGE + xarea + q * 768, xbase + (size_t)kb * kRecordBlockBytes, xlane[m]);
+            else lds_dma16(lds0 + slot * STAGE + xarea + q * 1024, xbase + (size_t)kb * kBK, xlane[m]);
         }
-        lds_dma16(lds0 + slot * STAGE + XW + wave * 1024, wbase + (size_t)kb * 1024, wlane);
+        lds_dma16(lds0 + slot * STAGE + XW + wave * 1024, wbase + (size_t)kb * wstride, wlane);
     };
 
-    // operand reads: token row (lane & 31) of tile j (rows beyond the stage wrap onto loaded rows; their
-    // results are never written), the 16-byte chunk that matches packed dword k4, swizzled like the copy
-    const int r0 = (lane & 31) & (ROWS - 1);
+    // Operand read offsets inside a stage.
+    //  int8: token row (lane & 31) of tile j (rows beyond the stage wrap onto loaded rows; their results are
+    //        never written), the 16-byte chunk that matches packed dword k4, swizzled like the copy.
+    //  fp6 x fp4, streaming: 16x16x128 MFMA - lane = (token lane & 15, feature group g = lane >> 4 of 32);
+    //        the weights of row 16 hf + (lane & 15), features 32 g + 0..31, are dwords 2 (g >> 1), +1 of tile
+    //        lane row + 32 (g & 1).
+    //  fp6 x fp4, shared: 32x32x64 MFMA as in the prefill kernel - lane = (token lane & 31, half lane >> 5).
     int xoff[4];
+    int xo_lo[2], xo_hi[2], wo[2];
+    if constexpr (!F6) {
+        const int r0 = (lane & 31) & (ROWS - 1);
 #pragma unroll
-    for (int k4 = 0; k4 < 4; ++k4) xoff[k4] = r0 * kBK + ((code_chunk_of_dword(k4, lane >> 5) ^ ((r0 >> 1) & 7)) << 4);
+        for (int k4 = 0; k4 < 4; ++k4) xoff[k4] = r0 * kBK + ((code_chunk_of_dword(k4, lane >> 5) ^ ((r0 >> 1) & 7)) << 4);
+    } else if constexpr (!SHARE) {
+        const int r0 = (lane & 15) & (ROWS - 1), g = lane >> 4;
+        xo_lo[0] = r0 * kRecordRowBytes + record_lo_offset(r0, g >> 1, g & 1);
+        xo_hi[0] = r0 * kRecordRowBytes + record_hi_offset(r0, g >> 1, g & 1);
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) wo[hf] = (16 * hf + (lane & 15) + 32 * (g & 1)) * 16 + 8 * (g >> 1);
+    } else {
+        const int r0 = lane & 31;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            xo_lo[s] = r0 * kRecordRowBytes + record_lo_offset(r0, s, lane >> 5);
+            xo_hi[s] = r0 * kRecordRowBytes + record_hi_offset(r0, s, lane >> 5);
+        }
+    }
 
-    v16i acc[NACC];
+    v16i acc[NACC];          // int8 path
+    v4f facc[2];             // fp6 x fp4, streaming: row halves 0..15, 16..31 of the tile
+    v16f wacc[TT];           // fp6 x fp4, shared: one 32 x 32 tile per token tile
 #pragma unroll
     for (int i = 0; i < NACC; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) facc[i] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int i = 0; i < TT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) wacc[i][r] = 0.0f;
 
     // Epilogue operands, requested before the stream starts: under a saturated memory system a load
     // issued after the loop would add its whole latency to the workgroup's run time.
     const bool write_partial = SHARE && p.ksplit > 1;
     const bool writer = live && (SHARE || ks == 0);
+    constexpr bool TOK16 = F6 && !SHARE;     // the 16x16 accumulator layout: token = lane & 15
     float alpha = 0.0f, sd[TT];
     v4i wsum[4];
 #pragma unroll
@@ -126,10 +201,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
         alpha = p.w_scales[(nt * 32) / p.rows_per_group];
 #pragma unroll
         for (int j = 0; j < TT; ++j) {
-            const int t = j * 32 + (lane & 31);
+            const int t = TOK16 ? (lane & 15) : j * 32 + (lane & 31);
             if (t < p.T) sd[j] = p.s_dequant[t];
         }
-        if (p.code_offset != 0) {
+        if (!F6 && p.code_offset != 0) {
 #pragma unroll
             for (int g = 0; g < 4; ++g)
                 wsum[g] = *reinterpret_cast<const v4i*>(p.w_row_sum + nt * 32 + 8 * g + 4 * (lane >> 5));
@@ -167,41 +242,91 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
         if constexpr (SHARE) asm volatile("s_barrier" ::: "memory");
         if (kb + D - 1 < nkb) issue(kb + D - 1, slot == 0 ? D - 1 : slot - 1);
         const char* st = lds + slot * STAGE;
-        const v4i wpk = *reinterpret_cast<const v4i*>(st + XW + wave * 1024 + lane * 16);
+        if constexpr (!F6) {
+            const v4i wpk = *reinterpret_cast<const v4i*>(st + XW + wave * 1024 + lane * 16);
 #pragma unroll
-        for (int k4 = 0; k4 < 4; ++k4) {
-            const v4i wop = expand_weights_i8((uint32_t)wpk[k4]);
+            for (int k4 = 0; k4 < 4; ++k4) {
+                const v4i wop = expand_weights_i8((uint32_t)wpk[k4]);
 #pragma unroll
-            for (int j = 0; j < TT; ++j) {
-                const v4i xop = *reinterpret_cast<const v4i*>(st + xarea + xoff[k4] + j * 32 * kBK);
-                // TT == 1: two accumulators take turns so that consecutive MFMAs do not depend on each other
-                const int ai = TT == 1 ? (k4 & 1) : j;
-                acc[ai] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop, xop, acc[ai], 0, 0, 0);
+                for (int j = 0; j < TT; ++j) {
+                    const v4i xop = *reinterpret_cast<const v4i*>(st + xarea + xoff[k4] + j * 32 * kBK);
+                    // TT == 1: two accumulators take turns so that consecutive MFMAs do not depend on each other
+                    const int ai = TT == 1 ? (k4 & 1) : j;
+                    acc[ai] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wop, xop, acc[ai], 0, 0, 0);
+                }
+            }
+        } else if constexpr (!SHARE) {
+            const v4i lo = *reinterpret_cast<const v4i*>(st + xarea + xo_lo[0]);
+            const int2 hi = *reinterpret_cast<const int2*>(st + xarea + xo_hi[0]);
+            const v8i xop = {lo[0], lo[1], lo[2], lo[3], hi.x, hi.y, 0, 0};
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const uint2 wp = *reinterpret_cast<const uint2*>(st + XW + wave * 1024 + wo[hf]);
+                facc[hf] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fp4_operand(wp.x, wp.y), xop, facc[hf],
+                                                                            4 /*A: fp4*/, 3 /*B: bf6*/, 0, 0, 0, 0);
+            }
+        } else {
+            const v4i wpk = *reinterpret_cast<const v4i*>(st + XW + wave * 1024 + lane * 16);
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const v8i wop = fp4_operand((uint32_t)wpk[2 * s], (uint32_t)wpk[2 * s + 1]);
+#pragma unroll
+                for (int j = 0; j < TT; ++j) {
+                    const char* rows = st + j * 32 * kRecordRowBytes;
+                    const v4i lo = *reinterpret_cast<const v4i*>(rows + xo_lo[s]);
+                    const int2 hi = *reinterpret_cast<const int2*>(rows + xo_hi[s]);
+                    const v8i xop = {lo[0], lo[1], lo[2], lo[3], hi.x, hi.y, 0, 0};
+                    wacc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wop, xop, wacc[j], 4, 3, 0, 0, 0, 0);
+                }
             }
         }
         slot = slot + 1 == D ? 0 : slot + 1;
     }
-    if constexpr (TT == 1) acc[0] += acc[1];
+    if constexpr (!F6 && TT == 1) acc[0] += acc[1];
 
     if constexpr (!SHARE) {
         if (p.ksplit > 1) {   // uniform over the workgroup
             __syncthreads();  // every wave is done with the stage buffers
             int* red = reinterpret_cast<int*>(lds);
+            float* fred = reinterpret_cast<float*>(lds);
             if (ks != 0) {
+                if constexpr (F6) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[0][r];
+                    for (int r = 0; r < 8; ++r) fred[(wave * 8 + r) * 64 + lane] = facc[r >> 2][r & 3];
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[0][r];
+                }
             }
             __syncthreads();
             if (ks == 0) {
-                for (int kk = 1; kk < p.ksplit; ++kk)
+                for (int kk = 1; kk < p.ksplit; ++kk) {
+                    if constexpr (F6) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[0][r] += red[((wave + kk) * 16 + r) * 64 + lane];
+                        for (int r = 0; r < 8; ++r) facc[r >> 2][r & 3] += fred[((wave + kk) * 8 + r) * 64 + lane];
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) acc[0][r] += red[((wave + kk) * 16 + r) * 64 + lane];
+                    }
+                }
             }
         }
         if (ks != 0) return;
     }
     if (!writer) return;
 
+    if constexpr (TOK16) {
+        // lane holds token lane & 15; facc[hf] holds features 16 hf + 4 (lane >> 4) + 0..3 of the row tile
+        const int t = lane & 15;
+        if (t >= p.T) return;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) {
+            const int n = nt * 32 + 16 * hf + 4 * (lane >> 4);
+            *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
+                dequant_quad_f32(facc[hf][0], facc[hf][1], facc[hf][2], facc[hf][3], sd[0], alpha);
+        }
+        return;
+    }
     // lane holds token 32j + (lane & 31); register quad g holds features 8g + 4*(lane >> 5) + 0..3
 #pragma unroll
     for (int j = 0; j < TT; ++j) {
@@ -211,16 +336,33 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
         for (int g = 0; g < 4; ++g) {
             const int n = nt * 32 + 8 * g + 4 * (lane >> 5);
             v4i o;
+            if constexpr (F6) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = acc[TT == 1 ? 0 : j][4 * g + r];
+                for (int r = 0; r < 4; ++r) o[r] = (int)wacc[j][4 * g + r];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[r] = acc[TT == 1 ? 0 : j][4 * g + r];
+            }
             if (write_partial) {
                 *reinterpret_cast<v4i*>(p.partial + ((size_t)ks * p.T + t) * p.N + n) = o;
+            } else if constexpr (F6) {
+                *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
+                    dequant_quad_f32(wacc[j][4 * g], wacc[j][4 * g + 1], wacc[j][4 * g + 2], wacc[j][4 * g + 3], sd[j], alpha);
             } else {
                 *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
                     dequant_quad_sums(o, sd[j], alpha, p.code_offset, wsum[g]);
             }
         }
     }
+}
+
+template <bool SHARE, int TT, int RQ, int D, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(const DecodeArgs args) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const DecodeProblem p = select_problem(args, (int)blockIdx.x, [](const DecodeProblem& q) { return q.wg_begin; });
+    const int w = (int)blockIdx.x - p.wg_begin;
+    if (p.f6) decode_body<SHARE, TT, RQ, D, NW, true>(p, w, lds);      // uniform over the workgroup
+    else decode_body<SHARE, TT, RQ, D, NW, false>(p, w, lds);
 }
 
 // Second launch of the shared form when some K range was split over workgroups: adds the int32 partial

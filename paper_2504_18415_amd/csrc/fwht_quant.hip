@@ -1093,8 +1093,15 @@ __global__ __launch_bounds__(256) void quant_grouped_kernel(const QuantGroupArgs
         if (tid < (1 << L2K) / 64) {                                                                          \
             BigRowRaw<BF16> raw;                                                                              \
             bigrow_load<L2K, BF16>(p.x, row, tid, raw);                                                       \
-            fwht_quant_bigrow_body<L2K, BITS, BF16, false, true>(row, tid, raw, p.codes, p.s_dequant, p.code_sum, \
-                                                                 RowParams{a.eps, p.ln_gain, p.ln_eps, 1}, p.code_offset); \
+            const RowParams rp{a.eps, p.ln_gain, p.ln_eps, 1};                                                \
+            if constexpr (BITS == 4) {                                                                        \
+                if (p.code_offset == kCodesBf6) {                                                             \
+                    fwht_quant_bigrow_body<L2K, 4, BF16, true, true>(row, tid, raw, p.codes, p.s_dequant, p.code_sum, rp, 8); \
+                    return;                                                                                   \
+                }                                                                                             \
+            }                                                                                                 \
+            fwht_quant_bigrow_body<L2K, BITS, BF16, false, true>(row, tid, raw, p.codes, p.s_dequant, p.code_sum, rp, \
+                                                                 p.code_offset);                              \
         }                                                                                                     \
         return;
     switch (p.K) {

@@ -121,13 +121,17 @@ inline int prefill_split_k(int64_t T, int64_t K, int64_t N) {
     return sk;
 }
 
+// Largest K split the small-batch streaming GEMM may choose (sizes the partial buffers).
+constexpr int kMaxDecodeSplit = 4;
+
 struct Workspace {
     int8_t* codes;
     float* s_dequant;
     int32_t* partial;
     size_t bytes;
 };
-inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
+// with_partial = false: no room for partial tiles (the kernels then keep every K range in one workgroup).
+inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N, bool with_partial = true) {
     Workspace w;
     size_t off = 0;
     w.codes = reinterpret_cast<int8_t*>(static_cast<char*>(base) + off);
@@ -138,8 +142,11 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
     w.s_dequant = reinterpret_cast<float*>(static_cast<char*>(base) + off);
     off += round_up(static_cast<size_t>(T) * sizeof(float), 256);
     w.partial = nullptr;
-    const int split = T <= 64 ? decode_split_k(T, K, N) : prefill_split_k(T, K, N);
-    if (T <= 64 || split > 1) {
+    // small batches: room for the K split of either small-batch kernel pair (the streaming kernel's plan cuts a
+    // K range into at most kMaxDecodeSplit slices)
+    int split = T <= 64 ? decode_split_k(T, K, N) : prefill_split_k(T, K, N);
+    if (T <= 64 && split < kMaxDecodeSplit) split = kMaxDecodeSplit;
+    if (with_partial && (T <= 64 || split > 1)) {
         w.partial = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
         off += round_up(static_cast<size_t>(split) * T * N * sizeof(int32_t), 256);
     }
@@ -151,10 +158,9 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N) {
 // Codes are stored as code + code_offset (0, or 8 for INT4 so that the stored bytes are 0..15), or -
 // code_offset == kCodesBf6 - as bf6 records (see fwht_quant.hip; INT4 with K >= 512).
 constexpr int kCodesBf6 = 6;
-inline bool bf6_path_supported(int64_t T, int64_t K, int bits, bool hadamard) {
-    (void)hadamard;
-    return bits == 4 && T > 64 && K >= 512;
-}
+// INT4 activations on rows of 512 features and more travel as bf6 records and meet the weights on the fp6 x fp4
+// matrix cores, at every batch size; INT8 activations and shorter rows travel as bytes to the int8 matrix cores.
+inline bool bf6_path_supported(int64_t K, int bits) { return bits == 4 && K >= 512; }
 // ln_gain != nullptr: RMS-normalise each row with that gain vector [K] and ln_eps first (LN of Eq. 7).
 int launch_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, int bits, float eps, bool hadamard,
                       int8_t* codes, float* s_dequant, int32_t* code_sum, int code_offset, hipStream_t stream,
@@ -223,7 +229,8 @@ struct DecodeProblem {
     int32_t* partial;          // [ksplit][T][N] when the K range is split over workgroups, else unused
     int T, K, N;
     int rows_per_group;
-    int code_offset;
+    int code_offset;           // int8 path: stored code byte = q + code_offset
+    int f6;                    // codes are bf6 records (record image): the fp6 x fp4 matrix cores do the work
     int ksplit;                // K slices per row tile
     int wg_begin;              // first workgroup of this problem in the GEMM grid
     int red_begin;             // first workgroup of this problem in the reduction grid
@@ -232,8 +239,6 @@ struct DecodeArgs {
     DecodeProblem p[kMaxGroup];
     int n;
 };
-// Largest K split the grouped GEMM may choose (sizes the partial buffers).
-constexpr int kMaxDecodeSplit = 4;
 // Fills ksplit / wg_begin / red_begin and launches.  Every problem needs T <= 64.
 int launch_decode_gemm(DecodeArgs& args, hipStream_t stream);
 // The launch plan launch_decode_gemm would use (K splits, grid sizes), without launching: host logic only.

@@ -73,13 +73,15 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
     // advancing along K is scalar arithmetic only.
     // weights: this wave copies tiles wave + NW*m of the workgroup tile; tiles past N are clamped (their
     // results are dropped in the epilogue)
+    // (K-block-major tiles: a stage's BN/32 tiles of this workgroup are consecutive KiB)
+    const size_t wstride = (size_t)(a.N / 32) * 1024;
     const char* wbase[WL];
 #pragma unroll
     for (int m = 0; m < WL; ++m) {
         int nt = n0 / 32 + wave + NW * m;
         const int nt_max = a.N / 32 - 1;
         nt = nt < nt_max ? nt : nt_max;
-        wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb_total + kb_first) * 1024;
+        wbase[m] = reinterpret_cast<const char*>(a.packed) + (size_t)kb_first * wstride + (size_t)nt * 1024;
     }
     const uint32_t wlane = lane * 16;
     // activation codes: instruction q covers tokens 8q..8q+7, lane l -> token 8q + l/8, LDS slot l%8,
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
         } else {
             const int wtile = wave + NW * (m - XL);
             if ((BN / 32) % NW == 0 || wtile < BN / 32)
-                lds_dma16(lds0 + slot * STAGE + XBYTES + wtile * 1024, wbase[m - XL] + (size_t)kbc * 1024, wlane);
+                lds_dma16(lds0 + slot * STAGE + XBYTES + wtile * 1024, wbase[m - XL] + (size_t)kbc * wstride, wlane);
         }
     };
     auto issue = [&](int kb, int slot) {

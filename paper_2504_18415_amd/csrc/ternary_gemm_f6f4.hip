@@ -73,13 +73,15 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
     const int nkb = SPLIT ? nkb_total / a.split_k : nkb_total;   // K-blocks of this workgroup
     const int kb0 = ks * nkb;
 
+    // (K-block-major tiles: a stage's BN/32 tiles of this workgroup are consecutive KiB)
+    const size_t wstride = (size_t)(a.N / 32) * 1024;
     const char* wbase[WL];
 #pragma unroll
     for (int m = 0; m < WL; ++m) {
         int nt = n0 / 32 + wave + NW * m;
         const int nt_max = a.N / 32 - 1;
         nt = nt < nt_max ? nt : nt_max;
-        wbase[m] = reinterpret_cast<const char*>(a.packed) + ((size_t)nt * nkb_total + kb0) * 1024;
+        wbase[m] = reinterpret_cast<const char*>(a.packed) + (size_t)kb0 * wstride + (size_t)nt * 1024;
     }
     const uint32_t wlane = lane * 16;
     // codes: the stage's panel blocks (one per 128 tokens of the tile, 12 KiB each, contiguous in the record
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T) void ternary_gemm_f6f4_kern
             lds_dma16(lds0 + slot * STAGE + q * 1024, xpiece[m] + (size_t)kbc * kRecordBlockBytes, wlane);
         } else {
             const int wtile = wave + NW * (m - XL);
-            lds_dma16(lds0 + slot * STAGE + XBYTES + wtile * 1024, wbase[m - XL] + (size_t)kbc * 1024, wlane);
+            lds_dma16(lds0 + slot * STAGE + XBYTES + wtile * 1024, wbase[m - XL] + (size_t)kbc * wstride, wlane);
         }
     };
     auto issue = [&](int kb, int slot) {

@@ -2,8 +2,11 @@
 // 2-bit packing of its codes into the streaming layout the GEMM kernels read.
 //
 // Packed layout (one form, 2 bits per weight, read by every GEMM kernel).  The [N, K] code matrix is cut into
-// tiles of 32 output rows x 128 input features, stored tile after tile with the K direction fastest:
-//   tile(nt, kb) at byte ((nt * (K/128) + kb) * 1024), nt = o / 32, kb = k / 128.
+// tiles of 32 output rows x 128 input features, stored K-block-major (all row tiles of features 0..127, then
+// all of 128..255, ...):
+//   tile(nt, kb) at byte ((kb * (N/32) + nt) * 1024), nt = o / 32, kb = k / 128,
+// so that a prefill workgroup's stage (16 row tiles of one K-block) is one contiguous 16 KiB piece and the waves
+// of a small-batch launch, each walking the K range of its own row tile, together sweep memory linearly.
 // A tile is 64 lanes x 4 dwords (lane-major, 16 bytes per lane).  Lane l, dword j holds the 16 weights of
 // row 32*nt + (l & 31) at features
 //   k = 128*kb + 64*(j >> 1) + 32*(l >> 5) + 16*(j & 1) + i,  i = 0..15,
@@ -76,12 +79,12 @@ __global__ __launch_bounds__(256) void ternarize_kernel(const float* __restrict_
 }
 
 // dword d of the packed stream -> (row, first feature) of its 16 weights
-__device__ __forceinline__ void packed_dword_origin(int64_t d, int64_t K, int64_t* row, int64_t* k0) {
-    const int64_t kblocks = K / 128;
+__device__ __forceinline__ void packed_dword_origin(int64_t d, int64_t N, int64_t* row, int64_t* k0) {
+    const int64_t ntiles = N / 32;
     const int dd = (int)(d & 3);
     const int lane = (int)((d >> 2) & 63);
     const int64_t tile = d >> 8;
-    const int64_t kb = tile % kblocks, nt = tile / kblocks;
+    const int64_t kb = tile / ntiles, nt = tile % ntiles;
     *row = nt * 32 + (lane & 31);
     *k0 = kb * 128 + (dd >> 1) * 64 + (lane >> 5) * 32 + (dd & 1) * 16;
 }
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
     const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (d >= total) return;
     int64_t row, k0;
-    packed_dword_origin(d, K, &row, &k0);
+    packed_dword_origin(d, N, &row, &k0);
     const uint32_t p = packed[d];
     uint4 raw;
     int8_t* c = reinterpret_cast<int8_t*>(&raw);
@@ -112,7 +115,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ co
     const int64_t d = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (d >= total) return;
     int64_t row, k0;
-    packed_dword_origin(d, K, &row, &k0);
+    packed_dword_origin(d, N, &row, &k0);
     const uint4 raw = *reinterpret_cast<const uint4*>(codes + row * K + k0);
     const int8_t* c = reinterpret_cast<const int8_t*>(&raw);
     uint32_t out = 0;
