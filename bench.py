@@ -6,12 +6,12 @@ A step = one pass of the whole hot path over one batch: the FWHT+quantiser launc
 launches hbl_hbitlinear_forward() makes - on the 7B-shaped prefill W_down site:
 X bf16 [8192 x 16384] -> 4096, INT4 activations (configuration 4, the shape the
 target "% of INT8 MFMA peak" is quoted on).  Inputs are resident in HBM before
-the timed region, which is K calls of hbl_hbitlinear_forward.  One JSON line is
-printed; it also carries the roofline of the dominant kernel (the GEMM; per-kernel
-durations come from K more steps of the same two launches through the stage-level
-calls, with events on the launch stream around each launch), the oracle timed on
-the host cores on a bounded sample, and the batched-decode layer figures
-(configuration 5).
+the timed region, which is K calls of hbl_hbitlinear_forward after W warm-up calls.
+One JSON line is printed; it also carries the roofline of the dominant kernel (the
+GEMM; per-kernel durations come from K more calls of the same public function, every
+launch timed by an event pair of its own through hbl_trace_begin / hbl_trace_end), the
+other prefill configurations, the oracle timed on the host cores on a bounded sample,
+and the batched-decode layer figures (configuration 5).
 """
 import argparse
 import json

@@ -51,11 +51,14 @@ extern "C" {
 #define HBL_BF16 1
 
 /* forms in which the quantised activation codes travel between the two launches (stage-level calls) */
-#define HBL_CODES_INT8 0        /* one signed byte per code                                              */
-#define HBL_CODES_UINT4_PLUS8 8 /* INT4 only: byte = code + 8 in 0..15                                   */
-#define HBL_CODES_BF6 6         /* INT4 only, K >= 512: per 32 features a
-                                   32-byte record, first 24 bytes = the 32 codes as 6-bit floats (e3m2,
-                                   feature i at bits [6i, 6i+6)), every integer in [-8, 7] exact          */
+#define HBL_CODES_INT8 0        /* one signed byte per code, [T, K] in natural feature order             */
+#define HBL_CODES_UINT4_PLUS8 8 /* INT4 only: byte = code + 8 in 0..15, [T, K]                           */
+#define HBL_CODES_BF6 6         /* INT4 only, K >= 512: 6 bits per code.  Per 32 features a 24-byte record
+                                   of 6-bit floats (e3m2, feature i at bits [6i, 6i+6); every integer in
+                                   [-8, 7] is exact), the records laid out as the GEMM holds them in LDS:
+                                   tokens in panels of 128, features in blocks of 128, a block = 128 token
+                                   rows of 96 bytes.  hbl_code_bytes() gives the buffer size (whole panels:
+                                   ceil(T/128) * 128 * 0.75 K); the layout is the library's own              */
 
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* hbl_strerror(int status);
@@ -221,9 +224,9 @@ size_t hbl_code_bytes(int64_t T, int64_t K, int code_form);
  *              path, because unsigned nibbles toggle far fewer multiplier input bits than
  *              sign-extended bytes and the matrix cores are power-limited (the GEMM epilogue removes
  *              the offset exactly in int32); HBL_CODES_BF6 writes the records the fp6 x fp4
- *              matrix-core path reads - the form the forward calls use for INT4 when T > 64 and
- *              K >= 512.
- *   codes      [T, K] int8 out in natural feature order
+ *              matrix-core path reads - the form the forward calls use for INT4 whenever K >= 512.
+ *   codes      out, hbl_code_bytes(T, K, code_offset) bytes: [T, K] bytes in natural feature order, or the
+ *              record image
  *   s_dequant  [T] fp32 out: gamma/127 or beta/sqrt7
  *   code_sum   [T] int32 out or NULL: sum_k code[t][k] of the true codes (without the offset)
  */
@@ -254,7 +257,7 @@ int hbl_gemm_i32(const int8_t* codes, int64_t T, int64_t K, const void* Wq_packe
                  int32_t* acc, void* stream);
 
 /*
- * The same contraction on the fp6 x fp4 matrix-core kernel, the one every INT4 forward call with T > 64 and
+ * The same contraction on the fp6 x fp4 prefill kernel, the one every INT4 forward call with T > 64 and
  * K >= 512 runs: acc[t][o] = sum_k q[t][k] * c[o][k] as int32 [T, N], read out of that kernel's fp32
  * accumulators (exact integers) with no dequantisation, in the launch configuration (workgroup tile,
  * K split over workgroups at mid-size batches) hbl_hbitlinear_forward takes for the same T, K, N.
@@ -270,9 +273,11 @@ int hbl_gemm_i32_bf6(const void* code_records, int64_t T, int64_t K, const void*
  * two launches the forward calls make, on caller-held intermediates.
  *   codes [T, K] int8, s_dequant [T] fp32, code_sum [T] int32: as written by hbl_fwht_quant with
  *   the same code_offset;  y [T, N] bf16 out
- * A forward call is hbl_fwht_quant(x, ..., hadamard, code_offset) into the workspace followed by this
- * call, with code_offset = HBL_CODES_BF6 for INT4 activations when T > 64 and K >= 512 (fp6 x fp4
- * matrix cores), HBL_CODES_UINT4_PLUS8 for INT4 otherwise, HBL_CODES_INT8 for INT8 activations.
+ * A forward call with T > 64 is hbl_fwht_quant(x, ..., hadamard, code_offset) into the workspace followed by
+ * this call, with code_offset = HBL_CODES_BF6 for INT4 activations with K >= 512 (fp6 x fp4 matrix cores),
+ * HBL_CODES_UINT4_PLUS8 for INT4 on shorter rows, HBL_CODES_INT8 for INT8 activations (smaller batches run the
+ * weight-streaming kernel on the same code forms).  code_sum is not read (the packed weights are signed) and
+ * may be NULL.
  */
 int hbl_gemm_dequant_bf16(const int8_t* codes, int code_offset, const float* s_dequant,
                           const int32_t* code_sum, int64_t T, int64_t K, const void* Wq_packed, int64_t N,

@@ -81,6 +81,65 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// Skeleton of the small-batch weight-streaming kernel: 512 workgroups of 4 waves, every wave walking its own run
+// of 1 KiB tiles through a ring of D global->LDS copies (16 bytes per lane), optionally with a second, 768-byte
+// copy per stage from a small cache-resident buffer (the activation codes) and with the LDS operand reads and two
+// 16x16x128 fp6 x fp4 MFMAs per tile that the real kernel issues.  What a launch of one decode layer's size can
+// reach at all with this structure, before any of the library's own bookkeeping.
+__device__ __forceinline__ void lds_dma16(unsigned lds_addr, const void* base, unsigned voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(base)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ void lds_dma16_first48(unsigned lds_addr, const void* base, unsigned voff) {
+    unsigned long long saved;
+    asm volatile(
+        "s_mov_b64 %0, exec\n\ts_bfm_b64 exec, 48, 0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, %0"
+        : "=&s"(saved)
+        : "s"(lds_addr), "v"(voff), "s"(base)
+        : "memory", "m0");
+}
+template <int D, bool CODES, bool WORK>
+__global__ __launch_bounds__(256, 2) void stream_skeleton_kernel(const char* __restrict__ src, const char* __restrict__ codes,
+                                                                 int tiles_per_wave, uint4* sink) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds + wave * D * 2048;
+    const size_t wid = (size_t)blockIdx.x * 4 + wave;
+    auto issue = [&](int it, int slot) {
+        if (CODES) lds_dma16_first48(lds0 + slot * 2048 + 1024, codes + (size_t)it * 12288, lane * 16);
+        lds_dma16(lds0 + slot * 2048, src + (wid * tiles_per_wave + it) * 1024, lane * 16);
+    };
+    constexpr int PER = CODES ? 2 : 1;
+    for (int s = 0; s < D - 1; ++s)
+        if (s < tiles_per_wave) issue(s, s);
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    v4f acc[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+    unsigned x = 0;
+    int slot = 0;
+    for (int it = 0; it < tiles_per_wave; ++it) {
+        if (tiles_per_wave - 1 - it >= D - 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 2) * PER) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        if (it + D - 1 < tiles_per_wave) issue(it + D - 1, slot == 0 ? D - 1 : slot - 1);
+        const char* st = lds + wave * D * 2048 + slot * 2048;
+        if (WORK) {
+            const uint4 lo = *reinterpret_cast<const uint4*>(st + 1024 + (lane & 15) * 48);
+            const uint2 hi = *reinterpret_cast<const uint2*>(st + 1024 + (lane & 15) * 48 + 16);
+            const v8i b = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, 0, 0};
+            for (int hf = 0; hf < 2; ++hf) {
+                const uint2 wp = *reinterpret_cast<const uint2*>(st + hf * 512 + lane * 8);
+                const v8i a = {(int)(wp.x & 0xAAAAAAAAu), (int)((wp.x << 1) & 0xAAAAAAAAu), (int)(wp.y & 0xAAAAAAAAu),
+                               (int)((wp.y << 1) & 0xAAAAAAAAu), 0, 0, 0, 0};
+                acc[hf] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, acc[hf], 4, 3, 0, 0, 0, 0);
+            }
+        } else {
+            x ^= *reinterpret_cast<const unsigned*>(st + lane * 16);
+        }
+        slot = slot + 1 == D ? 0 : slot + 1;
+    }
+    if (x == 0x12345678u || acc[0][0] + acc[1][1] == 1.2345f) sink[0] = make_uint4(x, 0, 0, 0);
+}
+
 template <class F>
 float time_ms(F launch, int reps) {
     hipEvent_t e0, e1;
@@ -138,6 +197,26 @@ int main() {
         }, 3) / 24;
         printf("HBM read, 64 MiB per launch, %4d workgroups      %8.1f GB/s (%.1f us per launch)\n", wgs,
                chunk / t / 1e6, t * 1e3);
+    }
+    {   // the weight-streaming skeleton on the same 64 MiB chunks
+        const int wgs = 512, tpw = (int)(((size_t)64 << 20) / 1024 / (wgs * 4));
+        char* codes;
+        CHECK(hipMalloc(&codes, 12288 * 64));
+        CHECK(hipMemset(codes, 0, 12288 * 64));
+        const size_t chunk = (size_t)64 << 20;
+        const char* base = reinterpret_cast<const char*>(src);
+        auto run = [&](const char* name, auto launch_one) {
+            const float t = time_ms([&] { for (int i = 0; i < 24; ++i) launch_one(base + i * chunk); }, 3) / 24;
+            printf("%-64s %6.2f us per 64 MiB launch, %7.1f GB/s\n", name, t * 1e3, chunk / t / 1e6);
+        };
+        run("stream skeleton: LDS copy ring D=4, 512 wgs", [&](const char* p) {
+            stream_skeleton_kernel<4, false, false><<<wgs, 256, 4 * 4 * 2048>>>(p, codes, tpw, dst); });
+        run("stream skeleton: + 768 B code copy per tile", [&](const char* p) {
+            stream_skeleton_kernel<4, true, false><<<wgs, 256, 4 * 4 * 2048>>>(p, codes, tpw, dst); });
+        run("stream skeleton: + code copy, LDS operand reads, 2 MFMA per tile", [&](const char* p) {
+            stream_skeleton_kernel<4, true, true><<<wgs, 256, 4 * 4 * 2048>>>(p, codes, tpw, dst); });
+        run("stream skeleton: ring D=8, + code copy, reads, MFMA", [&](const char* p) {
+            stream_skeleton_kernel<8, true, true><<<wgs, 256, 4 * 8 * 2048>>>(p, codes, tpw, dst); });
     }
     const float c = time_ms([&] { copy_kernel<<<4096, 256>>>(src, dst, bytes / 16); }, 5);
     printf("%-48s %8.1f GB/s (read + write)\n", "HBM copy, 2 GiB -> 2 GiB", 2.0 * bytes / c / 1e6);
