@@ -254,6 +254,22 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
         kstep_last(kb, slot);
         slot = slot + 1 == NSTAGE ? 0 : slot + 1;
     }
+    // (the epilogue's scales are requested first, so that their latency passes under the drain: behind the
+    // scheduling fences of the epilogue every one of them would cost its whole round trip)
+    float sd_of[TT], alpha_of[TN];
+    if (!RAW && !(SPLIT && a.split_k > 1)) {   // (the int32 forms have no scales: the pointers may be null)
+#pragma unroll
+        for (int j = 0; j < TT; ++j) {
+            const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
+            sd_of[j] = t < a.T ? a.s_dequant[t] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            const int nb = n0 + (wn * TN + i) * 32;
+            alpha_of[i] = nb < a.N ? a.w_scales[a.rows_per_group == a.N ? 0 : nb / a.rows_per_group] : 0.0f;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
     // drain the clamped tail loads, and wait until every wave is done with the stage buffers: the bf16
     // epilogue reuses them
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -301,14 +317,13 @@ __global__ __launch_bounds__(64 * WAVES_N * WAVES_T, OCC) void ternary_gemm_kern
 #pragma unroll
             for (int jj = 0; jj < JG; ++jj) {
                 const int j = jg + jj;
-                const int t = t0 + (wt * TT + j) * 32 + (lane & 31);
-                const float sd = t < a.T ? a.s_dequant[t] : 0.0f;
+                const float sd = sd_of[j];
 #pragma unroll
                 for (int i = 0; i < TN; ++i) {
                     __builtin_amdgcn_sched_barrier(0);   // one accumulator tile at a time (register pressure)
                     const int nb = n0 + (wn * TN + i) * 32;
                     const bool in_n = nb < a.N;
-                    const float alpha = in_n ? a.w_scales[nb / a.rows_per_group] : 0.0f;
+                    const float alpha = alpha_of[i];
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int n = nb + 8 * g + 4 * (lane >> 5);
