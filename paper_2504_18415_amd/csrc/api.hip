@@ -295,7 +295,7 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
             qp.K = (int)q.K;
             qp.hadamard = q.hadamard != 0;
             qp.code_offset = code_form_for(q.K, q.bits);
-            qp.row_begin = rows;
+            qp.row_begin = qa.row_begin[qa.n - 1] = rows;
             qp.ln_gain = q.ln_gain;
             qp.ln_eps = q.ln_eps;
             rows += (int)q.T;

@@ -60,16 +60,6 @@ __device__ __forceinline__ uint2 dequant_quad_f32(float a0, float a1, float a2, 
     return make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
 }
 
-// The problem a workgroup belongs to: the last one whose first workgroup is not beyond it.
-template <typename BeginOf>
-__device__ __forceinline__ DecodeProblem select_problem(const DecodeArgs& args, int wg, BeginOf begin_of) {
-    DecodeProblem p = args.p[0];
-#pragma unroll
-    for (int i = 1; i < kMaxGroup; ++i)
-        if (i < args.n && wg >= begin_of(args.p[i])) p = args.p[i];
-    return p;
-}
-
 // NW = waves per workgroup.  Four everywhere except the streaming form on a single long-K problem with few row
 // tiles (W_down alone): there 8 waves share a row tile's K range, which shortens each wave's serial chain of
 // tiles (128 workgroups cannot be made more without narrower row tiles).
@@ -90,7 +80,7 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kl = __builtin_ctz((unsigned)p.ksplit);   // ksplit is a power of two, at most NW
+    const int kl = __builtin_ctz((unsigned)p.ksplit);   // p.ksplit is a power of two, at most NW
     const int nkb_total = p.K / kBK;
     const int nkb = nkb_total >> kl;
     int nt, ks;
@@ -186,8 +176,33 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
 #pragma unroll
         for (int r = 0; r < 16; ++r) wacc[i][r] = 0.0f;
 
-    // Epilogue operands, requested before the stream starts: under a saturated memory system a load
-    // issued after the loop would add its whole latency to the workgroup's run time.
+    // Stage kb may be consumed once at most min(D - 2, nkb - 1 - kb) later stages are still in flight
+    // (copies return in order).  Nothing is requested past the end of the K range, so the count
+    // shrinks over the last D - 2 stages: those take the switch.
+    auto wait_stage = [&](int later) {
+        if (later >= D - 2) {
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 2) * (XL + 1)) : "memory");
+            return;
+        }
+        switch (later) {
+            case 0: asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); break;
+            case 1: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(1 * (XL + 1)) : "memory"); break;
+            case 2: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * (XL + 1)) : "memory"); break;
+            case 3: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(3 * (XL + 1)) : "memory"); break;
+            case 4: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(4 * (XL + 1)) : "memory"); break;
+            default: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(5 * (XL + 1)) : "memory"); break;
+        }
+    };
+    static_assert(D - 2 <= 6, "wait_stage covers up to 5 later stages below the steady state");
+
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s)
+        if (s < nkb) issue(s, s);
+
+    // Epilogue operands, requested right behind the first stages: under a saturated memory system a load
+    // issued after the loop would add its whole latency to the workgroup's run time, and ahead of the first
+    // copies they would delay the stream.  (They return in order behind the D - 1 stages in flight, which
+    // only makes the first waits below stricter than they need to be.)
     const bool write_partial = SHARE && p.ksplit > 1;
     const bool writer = live && (SHARE || ks == 0);
     constexpr bool TOK16 = F6 && !SHARE;     // the 16x16 accumulator layout: token = lane & 15
@@ -211,28 +226,6 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
         }
     }
 
-    // Stage kb may be consumed once at most min(D - 2, nkb - 1 - kb) later stages are still in flight
-    // (copies return in order).  Nothing is requested past the end of the K range, so the count
-    // shrinks over the last D - 2 stages: those take the switch.
-    auto wait_stage = [&](int later) {
-        if (later >= D - 2) {
-            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((D - 2) * (XL + 1)) : "memory");
-            return;
-        }
-        switch (later) {
-            case 0: asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); break;
-            case 1: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(1 * (XL + 1)) : "memory"); break;
-            case 2: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * (XL + 1)) : "memory"); break;
-            case 3: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(3 * (XL + 1)) : "memory"); break;
-            case 4: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(4 * (XL + 1)) : "memory"); break;
-            default: asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(5 * (XL + 1)) : "memory"); break;
-        }
-    };
-    static_assert(D - 2 <= 6, "wait_stage covers up to 5 later stages below the steady state");
-
-#pragma unroll
-    for (int s = 0; s < D - 1; ++s)
-        if (s < nkb) issue(s, s);
 
     int slot = 0;
     for (int kb = 0; kb < nkb; ++kb) {
@@ -359,7 +352,7 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
 template <bool SHARE, int TT, int RQ, int D, int NW = 4>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(const DecodeArgs args) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const DecodeProblem p = select_problem(args, (int)blockIdx.x, [](const DecodeProblem& q) { return q.wg_begin; });
+    const DecodeProblem p = args.p[group_index_of(args.wg_begin, args.n, (int)blockIdx.x)];
     const int w = (int)blockIdx.x - p.wg_begin;
     if (p.f6) decode_body<SHARE, TT, RQ, D, NW, true>(p, w, lds);      // uniform over the workgroup
     else decode_body<SHARE, TT, RQ, D, NW, false>(p, w, lds);
@@ -369,7 +362,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
 // tiles in fixed order (exact) and applies the dequantising epilogue.  The kernel boundary is what makes
 // the partials of workgroups on other XCDs visible.
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const DecodeArgs args) {
-    const DecodeProblem p = select_problem(args, (int)blockIdx.x, [](const DecodeProblem& q) { return q.red_begin; });
+    const DecodeProblem p = args.p[group_index_of(args.red_begin, args.n, (int)blockIdx.x)];
     const int quads = p.N / 4;
     const int64_t idx = (int64_t)((int)blockIdx.x - p.red_begin) * 256 + threadIdx.x;
     if (p.ksplit <= 1 || idx >= (int64_t)p.T * quads) return;
@@ -434,9 +427,9 @@ void plan(DecodeArgs& a, bool share, int* wgs_out, int* red_out) {
     int wgs = 0, red = 0;
     for (int i = 0; i < a.n; ++i) {
         DecodeProblem& p = a.p[i];
-        p.wg_begin = wgs;
+        p.wg_begin = a.wg_begin[i] = wgs;
         wgs += problem_wgs(p, share);
-        p.red_begin = red;
+        p.red_begin = a.red_begin[i] = red;
         if (share && p.ksplit > 1) red += (int)(((int64_t)p.T * (p.N / 4) + 255) / 256);
     }
     *wgs_out = wgs;
@@ -456,8 +449,8 @@ int wide_waves(const DecodeArgs& a, int max_t) {
 void plan_wide(DecodeArgs& a, int nw, int* wgs_out) {
     DecodeProblem& p = a.p[0];
     p.ksplit = nw;   // one row tile per workgroup, its K range over all waves: 8 tiles or more per wave (nkb >= 64)
-    p.wg_begin = 0;
-    p.red_begin = 0;
+    p.wg_begin = a.wg_begin[0] = 0;
+    p.red_begin = a.red_begin[0] = 0;
     *wgs_out = (p.N / 32 * p.ksplit + nw - 1) / nw;
 }
 

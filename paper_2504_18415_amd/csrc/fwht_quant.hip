@@ -18,6 +18,7 @@
 // the stage order e -> lane -> r -> wave is ascending.  The wave stages swap
 // the wave bits with the low r bits through LDS once, then run in registers.
 #include <atomic>
+#include <type_traits>
 
 #include "hbl_internal.h"
 
@@ -56,6 +57,24 @@ __device__ __forceinline__ float lane_xor(float v) {
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_move(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xF, 0xF, false);
+}
+// v <- v(partner lane) * c + v for the four registers of a chunk, the partner reached by DPP permutation CTRL:
+// v_fmac_f32 with a DPP source, which the compiler does not form by itself (it emits a DPP move and a separate
+// multiply-add).  A DPP operand must not be read within two wait states of a vector-ALU write to the same
+// register, and the compiler does not look inside an asm statement: the leading s_nop covers whatever
+// precedes the block, and inside it the four instructions touch four different registers.  (Blocks of 16
+// with one s_nop measured slower: the compiler can no longer place other work between the chunks.)
+template <int CTRL>
+__device__ __forceinline__ void lane_butterfly4(float (&a)[4], float c) {
+    static_assert(CTRL == 0xB1 || CTRL == 0x4E || CTRL == 0x141 || CTRL == 0x128, "lane xor 1, 2, 7 or 8");
+#define HBL_F(N, SEL) "v_fmac_f32_dpp %" #N ", %" #N ", %4 " SEL " row_mask:0xf bank_mask:0xf\n\t"
+#define HBL_LANE_FMAC4(SEL) asm("s_nop 1\n\t" HBL_F(0, SEL) HBL_F(1, SEL) HBL_F(2, SEL) HBL_F(3, SEL) : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]) : "v"(c))
+    if constexpr (CTRL == 0xB1) HBL_LANE_FMAC4("quad_perm:[1,0,3,2]");
+    else if constexpr (CTRL == 0x4E) HBL_LANE_FMAC4("quad_perm:[2,3,0,1]");
+    else if constexpr (CTRL == 0x141) HBL_LANE_FMAC4("row_half_mirror");
+    else HBL_LANE_FMAC4("row_ror:8");
+#undef HBL_LANE_FMAC4
+#undef HBL_F
 }
 template <int CTRL>
 __device__ __forceinline__ double dpp_move(double v) {
@@ -640,16 +659,28 @@ int launch_generic(const void* x, int x_dtype, int64_t T, int64_t K, int bits, R
 // Large rows (K = 4096, 8192, 16384): every butterfly stage runs in registers.
 //
 // A thread holds 64 values = 16 float4 "chunks"; a chunk is 4 consecutive elements (index bits 0-1)
-// and the chunk number j carries four more index bits.  Three layouts follow one another, each putting
-// the next four index bits into j; between them the row is exchanged through LDS (one float per
-// element, 16-byte accesses, XOR-swizzled so that both sides are conflict free):
+// and the chunk number j carries four more index bits.  Two or three register layouts, with the row exchanged through
+// LDS between them (one float per element, 16-byte accesses, XOR-swizzled so that both sides are conflict
+// free), and four stages between lanes in the middle:
 //   layout A: j = index bits 2-5,   thread = bits 6..m-1   stages 0-5   (64 contiguous elements / thread)
-//   layout B: j = index bits 6-9,   thread = bits 2-5,10..  stages 6-9
+//   K = 16384: index bits 6-9 are the low four bits of A's thread number: stages 6-9 run lane to lane (below)
+//   K < 16384: layout B: j = index bits 6-9, thread = bits 2-5, 10.. stages 6-9, after an exchange of its own
 //   layout C: j = index bits 10..   (+ finished low bits when m < 14)   stages 10..m-1
 // Stage order stays ascending, so every value equals the one the reference order produces.
 // In float4 units (q = index >> 2) every layout is q = q_t(thread) ^ q_j(j) with disjoint bit sets,
 // and the swizzle q ^ ((q >> 4) & 15) is linear over xor: an LDS address is one xor of a per-thread
 // base with a compile-time constant.
+//
+// Lane stages.  The butterfly on a lane bit is one instruction per element: v <- partner * c + v with the
+// partner read through a DPP lane permutation and c = +1 where the bit is 0 (a + b) and -1 where it is 1
+// (b - a): the product is exact and the sum rounds once, so the lower lane holds the reference's a + b and
+// the upper lane the negative of its a - b.  Negation commutes with every later rounding, so a lane simply
+// carries the sign (-1)^(number of its index bits 6-9 that are set); in layout C those bits belong to the
+// thread number, all 64 values of a thread share the sign, the butterflies among them keep it, and it
+// leaves through the factor the values are multiplied with anyway (1/sqrt(K) or the quantiser's gain).
+// DPP offers xor 1, xor 2 (quad permutes), xor 7 (half-row mirror) and xor 8 (row rotation by 8) inside a row
+// of 16 lanes, so the thread that takes segment t of layout A is lane t ^ (3 if bit 2 of t is set): flipping
+// index bit 8 (bit 2 of t) then flips lane bits 0-2 together.
 template <int LOG2K, int LAYOUT>
 struct BigRowLayout {
     static constexpr int M = LOG2K;
@@ -683,10 +714,21 @@ template <bool BF16>
 struct BigRowRaw {
     uint4 q[BF16 ? 8 : 16];
 };
+// Whether stages 6-9 run between lanes (one exchange through LDS) or in registers after an exchange of their
+// own (two exchanges).  With the four waves of a K = 16384 row an exchange costs two workgroup barriers and the
+// lane form is 5-6 % faster; the one or two waves of a K = 4096 / 8192 row exchange cheaply, and there the lane
+// form measured 3 % / 7 % slower (a DPP multiply-add issues more slowly than an add).
+template <int LOG2K>
+constexpr bool kLaneStages = LOG2K >= 14;
+// Segment of layout A (64 contiguous elements) that thread `tid` holds; its own inverse.
+template <int LOG2K>
+__device__ __forceinline__ uint32_t bigrow_segment(uint32_t tid) {
+    return kLaneStages<LOG2K> ? tid ^ (((tid >> 2) & 1u) * 3u) : tid;
+}
 template <int LOG2K, bool BF16>
 __device__ __forceinline__ void bigrow_load(const void* __restrict__ x, int64_t row, uint32_t tid, BigRowRaw<BF16>& raw) {
     constexpr int K = 1 << LOG2K;
-    const int64_t first = row * (int64_t)K + tid * 64;
+    const int64_t first = row * (int64_t)K + bigrow_segment<LOG2K>(tid) * 64;
     const uint4* src = BF16 ? reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(x) + first)
                             : reinterpret_cast<const uint4*>(static_cast<const float*>(x) + first);
 #pragma unroll
@@ -747,7 +789,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
 #pragma unroll
             for (int e = 0; e < 4; ++e) ss += (double)v[j][e] * (double)v[j][e];
         const float rn = rms_factor<W>(ss, red_n, lane, wave, K, rp.ln_eps, few_rows);
-        const float4* gsrc = reinterpret_cast<const float4*>(rp.ln_gain + tid * 64);
+        const float4* gsrc = reinterpret_cast<const float4*>(rp.ln_gain + bigrow_segment<LOG2K>(tid) * 64);
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const float4 gq = gsrc[j];
@@ -783,9 +825,17 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
                 }
         }
     };
-    auto lds_write = [&](auto layout_tag) {
+    // index bits 6-9: between lanes (see above); CTRL = the DPP permutation that reaches the partner, `upper` =
+    // this lane's index bit is set
+    auto stage_lane = [&](auto ctrl_tag, bool upper) {
+        constexpr int CTRL = decltype(ctrl_tag)::value;
+        const float c = upper ? -1.0f : 1.0f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) lane_butterfly4<CTRL>(v[j], c);
+    };
+    auto lds_write = [&](auto layout_tag, uint32_t thread) {
         using L = decltype(layout_tag);
-        const uint32_t base = swz16(L::qt(tid)) << 4;   // bytes
+        const uint32_t base = swz16(L::qt(thread)) << 4;   // bytes
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             constexpr uint32_t dummy = 0;
@@ -807,12 +857,22 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
 
     stages_e();
     stages_j(4);              // index bits 2-5
-    if constexpr (ROWLOOP) __syncthreads();   // after this row's first stages: the wait is mostly over by then
-    lds_write(LA{});
-    __syncthreads();
-    lds_read(LB{});
-    stages_j(4);              // index bits 6-9
-    lds_write(LB{});          // to the very addresses this thread has just read: no barrier needed before it
+    if constexpr (kLaneStages<LOG2K>) {
+        const uint32_t seg = bigrow_segment<LOG2K>(tid);
+        stage_lane(std::integral_constant<int, 0xB1>{}, seg & 1u);    // index bit 6: lane ^ 1 (quad_perm [1,0,3,2])
+        stage_lane(std::integral_constant<int, 0x4E>{}, seg & 2u);    // index bit 7: lane ^ 2 (quad_perm [2,3,0,1])
+        stage_lane(std::integral_constant<int, 0x141>{}, seg & 4u);   // index bit 8: lane ^ 7 (row_half_mirror)
+        stage_lane(std::integral_constant<int, 0x128>{}, seg & 8u);   // index bit 9: lane ^ 8 (row_ror:8)
+        if constexpr (ROWLOOP) __syncthreads();   // after this row's first stages: the wait is mostly over by then
+        lds_write(LA{}, seg);
+    } else {
+        if constexpr (ROWLOOP) __syncthreads();
+        lds_write(LA{}, tid);
+        __syncthreads();
+        lds_read(LB{});
+        stages_j(4);              // index bits 6-9
+        lds_write(LB{}, tid);     // to the very addresses this thread has just read: no barrier needed before it
+    }
     __syncthreads();
     lds_read(LC{});
     before_tail();
@@ -822,12 +882,15 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
     // with every later rounding (max, fp64 sum, the gain product), so it is applied to the row
     // statistics and folded into the gain instead of costing one multiply per element.
     const float c_n = (float)(1.0 / sqrt((double)K));
+    // the sign this thread's values carry out of the lane stages: parity of index bits 6-9, which in layout C
+    // are bits 4-7 of q_t(thread); it leaves with the factor below (exactly: a sign flip)
+    const float c_s = (kLaneStages<LOG2K> && (__builtin_popcount((LC::qt(tid) >> 4) & 15u) & 1)) ? -c_n : c_n;
     constexpr bool FOLD = (LOG2K % 2) == 0 && BITS != 0;
     if constexpr (!FOLD) {
 #pragma unroll
         for (int j = 0; j < 16; ++j)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[j][e] = v[j][e] * c_n;
+            for (int e = 0; e < 4; ++e) v[j][e] = v[j][e] * c_s;
     }
 
     if constexpr (BITS == 0) {
@@ -880,7 +943,7 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
     constexpr float hi = BITS == 8 ? 127.0f : 7.0f;
     static_assert(!BF6OUT || BITS == 4 || BITS == 0, "bf6 records carry INT4 codes only");
     const float magic = kMagic + (float)code_offset;   // byte forms: the low byte of t + magic is code + offset
-    if constexpr (FOLD) gain = gain * c_n;
+    if constexpr (FOLD) gain = gain * c_s;   // (the statistics above took |v| and the positive c_n)
     int isum = 0;
     int8_t* out = codes + row_off + (LC::qt(tid) << 2);
     uint32_t* c24 = reinterpret_cast<uint32_t*>(row_lds);   // BF6OUT: 24 bits of bf6 per chunk, by chunk number
@@ -1072,10 +1135,7 @@ int dispatch(const void* x, int x_dtype, int64_t T, int bits, RowParams rp, bool
 // waves that have not ended.
 template <int BITS, bool BF16>
 __global__ __launch_bounds__(256) void quant_grouped_kernel(const QuantGroupArgs a) {
-    QuantProblem p = a.p[0];
-#pragma unroll
-    for (int i = 1; i < kMaxGroup; ++i)
-        if (i < a.n && (int)blockIdx.x >= a.p[i].row_begin) p = a.p[i];
+    const QuantProblem p = a.p[group_index_of(a.row_begin, a.n, (int)blockIdx.x)];
     const int64_t row = (int)blockIdx.x - p.row_begin;
     const int tid = threadIdx.x;
     if (!p.hadamard) {

@@ -212,10 +212,13 @@ struct QuantProblem {
     const float* ln_gain; // [K] RMS-norm gain ahead of the transform, or nullptr
     float ln_eps;
 };
+// (n and the begin arrays come first: a workgroup finds its problem from one cache line of the argument
+// block and then loads that problem only - reading all kMaxGroup problems cost ~0.7 us at kernel start)
 struct QuantGroupArgs {
-    QuantProblem p[kMaxGroup];
     int n;
     float eps;
+    int row_begin[kMaxGroup];   // = p[i].row_begin
+    QuantProblem p[kMaxGroup];
 };
 int launch_quant_grouped(const QuantGroupArgs& args, int bits, int x_dtype, hipStream_t stream);
 
@@ -236,9 +239,19 @@ struct DecodeProblem {
     int red_begin;             // first workgroup of this problem in the reduction grid
 };
 struct DecodeArgs {
-    DecodeProblem p[kMaxGroup];
     int n;
+    int wg_begin[kMaxGroup];    // = p[i].wg_begin, p[i].red_begin (filled with them by the launch plan)
+    int red_begin[kMaxGroup];
+    DecodeProblem p[kMaxGroup];
 };
+// Index of the problem workgroup `wg` belongs to: the last one whose first workgroup is not beyond it.
+__host__ __device__ inline int group_index_of(const int* begin, int n, int wg) {
+    int idx = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i)
+        if (i < n && wg >= begin[i]) idx = i;
+    return idx;
+}
 // Fills ksplit / wg_begin / red_begin and launches.  Every problem needs T <= 64.
 int launch_decode_gemm(DecodeArgs& args, hipStream_t stream);
 // The launch plan launch_decode_gemm would use (K splits, grid sizes), without launching: host logic only.
