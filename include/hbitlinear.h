@@ -183,8 +183,9 @@ int hbl_ln_bitlinear_forward(const void* x, int x_dtype, int64_t T, int64_t K, c
  * Meant for small batches (decode), where one projection's launches are too short to keep HBM
  * busy: when every T <= 64, n_problems <= 8 and all problems share bits and x_dtype, the rows of
  * all problems are quantised by one launch and all packed weights are streamed by one launch
- * (plus one reduction launch for 16 < T <= 64 when a K range is split); otherwise the problems
- * run one after the other through the calls above.
+ * (for 16 < T <= 64 a K range may be split over workgroups; the last of them to finish adds the
+ * slices, counted in a small static device array of which overlapping calls on one GPU take
+ * different slots, 128 in all); otherwise the problems run one after the other through the calls above.
  *   problems   host array, read during the call only; fields as the arguments of the forward
  *              calls above (hadamard != 0 selects H-BitLinear, eps is shared)
  *   workspace  device, >= hbl_grouped_workspace_bytes(problems, n_problems), 256-byte aligned

@@ -138,9 +138,17 @@ int forward(const void* x, int x_dtype, int64_t T, int64_t K, const void* Wq_pac
 
 // Workspace region of one problem of a grouped call: large enough for the grouped launches (partials
 // for the largest K split they may choose) and for the stand-alone forward call.
-size_t group_region_bytes(const hbl_problem& q) {
+size_t group_region_bytes(const hbl_problem& q, int tile_rows) {
     if (q.T <= 0 || q.K <= 0 || q.N <= 0) return 256;
-    return carve_workspace(nullptr, q.T, q.K, q.N).bytes;
+    return carve_workspace(nullptr, q.T, q.K, q.N, true, tile_rows).bytes;
+}
+// Token rows of the slices the small-batch kernel keeps for a group: set by the largest member that takes that
+// kernel (0: at most 16 tokens everywhere, no slices).
+int group_tile_rows(const hbl_problem* problems, int n) {
+    int64_t max_t = 0;
+    for (int i = 0; i < n; ++i)
+        if (problems[i].T <= 64 && problems[i].T > max_t) max_t = problems[i].T;
+    return max_t <= 16 ? 0 : (max_t <= 32 ? 32 : 64);
 }
 
 }  // namespace
@@ -241,7 +249,8 @@ int hbl_bitlinear_forward_small(const void* x, int x_dtype, int64_t T, int64_t K
 size_t hbl_grouped_workspace_bytes(const hbl_problem* problems, int n_problems) {
     size_t total = 256;
     if (!problems) return total;
-    for (int i = 0; i < n_problems; ++i) total += group_region_bytes(problems[i]);
+    const int tile_rows = group_tile_rows(problems, n_problems);
+    for (int i = 0; i < n_problems; ++i) total += group_region_bytes(problems[i], tile_rows);
     return total;
 }
 
@@ -266,10 +275,11 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return HBL_E_ALIGN;
     if (workspace_bytes < hbl_grouped_workspace_bytes(problems, n_problems)) return HBL_E_WORKSPACE;
     char* base = static_cast<char*>(workspace);
+    const int tile_rows = group_tile_rows(problems, n_problems);
     if (!grouped) {
         for (int i = 0; i < n_problems; ++i) {
             const hbl_problem& q = problems[i];
-            const size_t region = group_region_bytes(q);
+            const size_t region = group_region_bytes(q, tile_rows);
             const int rc = forward(q.x, q.x_dtype, q.T, q.K, q.Wq_packed, q.N, q.w_scales, q.n_scale_groups, q.bits, eps,
                                    q.y, base, region, stream, q.hadamard != 0, q.ln_gain, q.ln_eps);
             if (rc != HBL_OK) return rc;
@@ -283,9 +293,9 @@ int hbl_bitlinear_forward_grouped(const hbl_problem* problems, int n_problems, f
     int rows = 0;
     for (int i = 0; i < n_problems; ++i) {
         const hbl_problem& q = problems[i];
-        const size_t region = group_region_bytes(q);
+        const size_t region = group_region_bytes(q, tile_rows);
         if (q.T > 0) {
-            const Workspace ws = carve_workspace(base, q.T, q.K, q.N);
+            const Workspace ws = carve_workspace(base, q.T, q.K, q.N, true, tile_rows);
             QuantProblem& qp = qa.p[qa.n++];
             qp.x = q.x;
             qp.codes = ws.codes;

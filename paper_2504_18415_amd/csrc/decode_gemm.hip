@@ -16,8 +16,10 @@
 //    barrier.  The K range of one row tile may be split over the 2 or 4 waves of a workgroup; their
 //    accumulators are added through LDS at the end (exact).
 //  - shared (T <= 64): the four waves take four row tiles over one K range and share the code stage
-//    (32 or 64 rows): one barrier per stage.  A K range split over workgroups leaves int32 partial tiles that
-//    a second launch adds and dequantises.
+//    (32 or 64 rows): one barrier per stage.  A K range split over workgroups leaves int32 slices in the
+//    workspace; the workgroup of a K range that finishes last (an arrival counter) adds the others' slices to
+//    its own accumulators and dequantises.  (A launch with more split row groups than there are counters in a
+//    slot falls back to a second launch that adds the slices.)
 #include <atomic>
 
 #include "gemm_common.h"
@@ -65,7 +67,7 @@ __device__ __forceinline__ uint2 dequant_quad_f32(float a0, float a1, float a2, 
 // tiles (128 workgroups cannot be made more without narrower row tiles).
 // F6: the problem's codes are bf6 records and the fp6 x fp4 matrix cores do the work.
 template <bool SHARE, int TT, int RQ, int D, int NW, bool F6>
-__device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w, char* lds) {
+__device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w, char* lds, unsigned int* p_arrive) {
     constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;    // token rows of one code stage
     constexpr int ROWB = F6 ? kRecordRowBytes : kBK;  // bytes of one token row of a stage
     constexpr int XB = ROWS * ROWB;                   // bytes of one code stage
@@ -212,7 +214,8 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     for (int j = 0; j < TT; ++j) sd[j] = 0.0f;
 #pragma unroll
     for (int g = 0; g < 4; ++g) wsum[g] = v4i{0, 0, 0, 0};
-    if (writer && !write_partial) {
+    const bool reduce_here = write_partial && p.arrive_begin >= 0;   // (uniform) the last workgroup of a K range to arrive adds the slices
+    if (writer && (!write_partial || reduce_here)) {
         alpha = p.w_scales[(nt * 32) / p.rows_per_group];
 #pragma unroll
         for (int j = 0; j < TT; ++j) {
@@ -306,7 +309,9 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
         }
         if (ks != 0) return;
     }
-    if (!writer) return;
+    if constexpr (!SHARE) {
+        if (!writer) return;
+    }
 
     if constexpr (TOK16) {
         // lane holds token lane & 15; facc[hf] holds features 16 hf + 4 (lane >> 4) + 0..3 of the row tile
@@ -321,6 +326,64 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
         return;
     }
     // lane holds token 32j + (lane & 31); register quad g holds features 8g + 4*(lane >> 5) + 0..3
+    v4i tot[TT][4];
+#pragma unroll
+    for (int j = 0; j < TT; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if constexpr (F6) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tot[j][g][r] = (int)wacc[j][4 * g + r];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tot[j][g][r] = acc[TT == 1 ? 0 : j][4 * g + r];
+            }
+        }
+    if constexpr (SHARE) {
+        if (write_partial) {   // uniform over the workgroup
+            // this workgroup's slice of the K range, as int32 tiles (exact)
+            if (!reduce_here) {   // [ksplit][T][N] for the reduction launch
+                if (writer) {
+#pragma unroll
+                    for (int j = 0; j < TT; ++j) {
+                        const int t = j * 32 + (lane & 31);
+                        if (t >= p.T) continue;
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            *reinterpret_cast<v4i*>(p.partial + ((size_t)ks * p.T + t) * p.N + nt * 32 + 8 * g + 4 * (lane >> 5)) = tot[j][g];
+                    }
+                }
+                return;
+            }
+            // Reduced here: the slices are only ever read by a workgroup of the same shape, so they are kept as the
+            // lanes hold them - quad (j, g) of wave `wave` of slice k at v4i index (((k * groups + group) * 4 + wave) *
+            // 4 TT + 4 j + g) * 64 + lane: every store and load instruction moves 1 KiB of consecutive bytes.  The
+            // stores are device-scope (write-through): readable from the other XCDs without a write-back of this L2.
+            const int groups = (p.N / 32 + 3) / 4;
+            v4i* const frag = reinterpret_cast<v4i*>(p.partial);
+            auto frag_index = [&](int k, int q) { return ((((size_t)k * groups + (w >> kl)) * 4 + wave) * (4 * TT) + q) * 64 + lane; };
+#pragma unroll
+            for (int q = 0; q < 4 * TT; ++q)
+                asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(frag + frag_index(ks, q)), "v"(tot[q >> 2][q & 3]) : "memory");
+            // Arrival: once a workgroup's stores have completed it counts itself in; the counter wraps at ksplit, so
+            // the workgroup that brings it back to zero is the last of its K range and every slice is in memory.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();   // (every wave of the workgroup is here: the stage buffers are free)
+            unsigned int* arrived = reinterpret_cast<unsigned int*>(lds);
+            if (tid == 0) *arrived = atomicInc(p_arrive + p.arrive_begin + (w >> kl), (unsigned)p.ksplit - 1u);
+            __syncthreads();
+            if (*arrived != (unsigned)p.ksplit - 1u || !writer) return;
+            // Plain loads: a launch starts with clean caches and this workgroup reads these lines for the first time
+            // in it, after their writers' stores completed in memory - they miss every cache on their way.
+            for (int k = 0; k < p.ksplit; ++k) {
+                if (k == ks) continue;   // (uniform)
+#pragma unroll
+                for (int q = 0; q < 4 * TT; ++q) tot[q >> 2][q & 3] += frag[frag_index(k, q)];
+            }
+        } else if (!writer) {
+            return;
+        }
+    }
 #pragma unroll
     for (int j = 0; j < TT; ++j) {
         const int t = j * 32 + (lane & 31);
@@ -328,22 +391,11 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int n = nt * 32 + 8 * g + 4 * (lane >> 5);
-            v4i o;
             if constexpr (F6) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = (int)wacc[j][4 * g + r];
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = acc[TT == 1 ? 0 : j][4 * g + r];
-            }
-            if (write_partial) {
-                *reinterpret_cast<v4i*>(p.partial + ((size_t)ks * p.T + t) * p.N + n) = o;
-            } else if constexpr (F6) {
                 *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
-                    dequant_quad_f32(wacc[j][4 * g], wacc[j][4 * g + 1], wacc[j][4 * g + 2], wacc[j][4 * g + 3], sd[j], alpha);
+                    dequant_quad_f32((float)tot[j][g][0], (float)tot[j][g][1], (float)tot[j][g][2], (float)tot[j][g][3], sd[j], alpha);
             } else {
-                *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
-                    dequant_quad_sums(o, sd[j], alpha, p.code_offset, wsum[g]);
+                *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) = dequant_quad_sums(tot[j][g], sd[j], alpha, p.code_offset, wsum[g]);
             }
         }
     }
@@ -354,13 +406,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const DecodeProblem p = args.p[group_index_of(args.wg_begin, args.n, (int)blockIdx.x)];
     const int w = (int)blockIdx.x - p.wg_begin;
-    if (p.f6) decode_body<SHARE, TT, RQ, D, NW, true>(p, w, lds);      // uniform over the workgroup
-    else decode_body<SHARE, TT, RQ, D, NW, false>(p, w, lds);
+    if (p.f6) decode_body<SHARE, TT, RQ, D, NW, true>(p, w, lds, args.arrive);      // uniform over the workgroup
+    else decode_body<SHARE, TT, RQ, D, NW, false>(p, w, lds, args.arrive);
 }
 
-// Second launch of the shared form when some K range was split over workgroups: adds the int32 partial
-// tiles in fixed order (exact) and applies the dequantising epilogue.  The kernel boundary is what makes
-// the partials of workgroups on other XCDs visible.
+// Second launch of the shared form, taken only when a launch has more split row groups than arrival counters:
+// adds the int32 partial tiles in fixed order (exact) and applies the dequantising epilogue.
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const DecodeArgs args) {
     const DecodeProblem p = args.p[group_index_of(args.red_begin, args.n, (int)blockIdx.x)];
     const int quads = p.N / 4;
@@ -375,8 +426,50 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const DecodeArgs arg
         dequant_quad(sum, p.s_dequant[t], p.w_scales[n / p.rows_per_group], p.code_offset, p.w_row_sum + n);
 }
 
+// Arrival counters of the shared form's in-kernel reduction: one per group of four row tiles whose K range is split
+// over workgroups.  A counter wraps at the number of slices, so it is back at zero when its launch is over and needs
+// no initialisation beyond the zeros the array is loaded with.  The host hands the kArriveSlots slots out round-robin:
+// launches that overlap on one GPU (other streams) count in different words unless more than that many are in flight.
+constexpr int kArriveWords = 2048;
+constexpr int kArriveSlots = 128;
+__device__ __attribute__((aligned(256))) unsigned int g_arrive[kArriveSlots * kArriveWords];
+
+// This device's copy of the array (each GPU holds its own, at its own address), advanced to the next slot.
+int next_arrive_slot(unsigned int** out) {
+    static std::atomic<unsigned int*> base[64];
+    static std::atomic<unsigned int> next{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return note_hip_error(e);
+    unsigned int* ptr = base[dev & 63].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(g_arrive));
+        if (e != hipSuccess) return note_hip_error(e);
+        base[dev & 63].store(ptr, std::memory_order_release);
+    }
+    *out = ptr + (size_t)(next.fetch_add(1, std::memory_order_relaxed) % kArriveSlots) * kArriveWords;
+    return HBL_OK;
+}
+
 template <bool SHARE, int TT, int RQ, int D, int NW = 4>
-int launch_form(const DecodeArgs& a, int wgs, int red_wgs, hipStream_t stream) {
+int launch_form(const DecodeArgs& planned, int wgs, int red_wgs, hipStream_t stream) {
+    DecodeArgs a = planned;
+    a.arrive = nullptr;
+    for (int i = 0; i < a.n; ++i) a.p[i].arrive_begin = -1;
+    if (SHARE && red_wgs != 0) {   // some K range is split over workgroups: reduce in the kernel if the counters suffice
+        int words = 0;
+        for (int i = 0; i < a.n; ++i)
+            if (a.p[i].ksplit > 1) {
+                a.p[i].arrive_begin = words;
+                words += (a.p[i].N / 32 + 3) / 4;
+            }
+        if (words <= kArriveWords) {
+            if (const int rc = next_arrive_slot(&a.arrive); rc != HBL_OK) return rc;
+            red_wgs = 0;
+        } else {
+            for (int i = 0; i < a.n; ++i) a.p[i].arrive_begin = -1;
+        }
+    }
     constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;
     constexpr size_t lds = (size_t)D * ((SHARE ? 1 : NW) * ROWS * kBK + NW * 1024);
     auto kern = decode_gemm_kernel<SHARE, TT, RQ, D, NW>;

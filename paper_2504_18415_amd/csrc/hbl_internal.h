@@ -131,7 +131,9 @@ struct Workspace {
     size_t bytes;
 };
 // with_partial = false: no room for partial tiles (the kernels then keep every K range in one workgroup).
-inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N, bool with_partial = true) {
+// tile_rows: 32 or 64 when the projection runs in a group whose largest member has 17-32 / 33-64 tokens (the
+// small-batch kernel's form, and with it the shape of its slices, follows the largest member), else 0.
+inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N, bool with_partial = true, int tile_rows = 0) {
     Workspace w;
     size_t off = 0;
     w.codes = reinterpret_cast<int8_t*>(static_cast<char*>(base) + off);
@@ -148,7 +150,15 @@ inline Workspace carve_workspace(void* base, int64_t T, int64_t K, int64_t N, bo
     if (T <= 64 && split < kMaxDecodeSplit) split = kMaxDecodeSplit;
     if (with_partial && (T <= 64 || split > 1)) {
         w.partial = reinterpret_cast<int32_t*>(static_cast<char*>(base) + off);
-        off += round_up(static_cast<size_t>(split) * T * N * sizeof(int32_t), 256);
+        // (17 to 64 tokens: the small-batch kernel keeps its slices as whole tiles of 32 tokens x 128 features)
+        size_t rows = static_cast<size_t>(T);
+        if (T <= 64) {
+            int tr = T > 16 ? (T <= 32 ? 32 : 64) : 0;
+            if (tile_rows > tr) tr = tile_rows;
+            if (tr != 0) rows = static_cast<size_t>(tr);
+        }
+        const size_t cols = T <= 64 ? round_up(static_cast<size_t>(N), 128) : static_cast<size_t>(N);
+        off += round_up(static_cast<size_t>(split) * rows * cols * sizeof(int32_t), 256);
     }
     w.bytes = off;
     return w;
@@ -237,11 +247,13 @@ struct DecodeProblem {
     int ksplit;                // K slices per row tile
     int wg_begin;              // first workgroup of this problem in the GEMM grid
     int red_begin;             // first workgroup of this problem in the reduction grid
+    int arrive_begin;          // first arrival counter of this problem (K split over workgroups, reduced in the kernel)
 };
 struct DecodeArgs {
     int n;
     int wg_begin[kMaxGroup];    // = p[i].wg_begin, p[i].red_begin (filled with them by the launch plan)
     int red_begin[kMaxGroup];
+    unsigned int* arrive;       // arrival counters of this launch, or nullptr: split K ranges go to the reduction launch
     DecodeProblem p[kMaxGroup];
 };
 // Index of the problem workgroup `wg` belongs to: the last one whose first workgroup is not beyond it.

@@ -448,7 +448,8 @@ def ln_fwht_quant(x: torch.Tensor, ln_gain: torch.Tensor, ln_eps: float, bits: i
 
 def grouped_plan(shapes):
     """Host-only: launch plan of the small-batch GEMM for [(T, K, N, hadamard), ...] ->
-    (ksplit list, gemm workgroups, reduce workgroups, list of "single call streams" flags)."""
+    (ksplit list, gemm workgroups, workgroups of the reduction launch that a K split over workgroups would need
+    if it were not reduced inside the GEMM launch, list of "single call streams" flags)."""
     n = len(shapes)
     arr = (Problem * n)(*[Problem(0, BF16, 4, int(bool(h)), 0, T, K, N, 0, 0, 1, 0) for (T, K, N, h) in shapes])
     ks = (ctypes.c_int * n)()
