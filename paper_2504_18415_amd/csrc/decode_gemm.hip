@@ -373,12 +373,16 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
             if (tid == 0) *arrived = atomicInc(p_arrive + p.arrive_begin + (w >> kl), (unsigned)p.ksplit - 1u);
             __syncthreads();
             if (*arrived != (unsigned)p.ksplit - 1u || !writer) return;
-            // Plain loads: a launch starts with clean caches and this workgroup reads these lines for the first time
-            // in it, after their writers' stores completed in memory - they miss every cache on their way.
+            // (device-scope loads, 8 bytes each: they do not stop at this XCD's L2)
             for (int k = 0; k < p.ksplit; ++k) {
                 if (k == ks) continue;   // (uniform)
 #pragma unroll
-                for (int q = 0; q < 4 * TT; ++q) tot[q >> 2][q & 3] += frag[frag_index(k, q)];
+                for (int q = 0; q < 4 * TT; ++q) {
+                    const uint64_t* src = reinterpret_cast<const uint64_t*>(frag + frag_index(k, q));
+                    const uint64_t lo = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const uint64_t hi = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    tot[q >> 2][q & 3] += v4i{(int)(uint32_t)lo, (int)(uint32_t)(lo >> 32), (int)(uint32_t)hi, (int)(uint32_t)(hi >> 32)};
+                }
             }
         } else if (!writer) {
             return;
