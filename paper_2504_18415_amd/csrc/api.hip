@@ -347,8 +347,8 @@ int hbl_ln_fwht_quant(const void* x, int x_dtype, int64_t T, int64_t K, const fl
 }
 
 int hbl_test_grouped_plan(const hbl_problem* problems, int n_problems, int* ksplit, int* gemm_workgroups,
-                           int* reduce_workgroups, int* single_call_streams) {
-    if (!problems || !ksplit || !gemm_workgroups || !reduce_workgroups || !single_call_streams) return HBL_E_NULL;
+                           int* arrival_counters, int* single_call_streams) {
+    if (!problems || !ksplit || !gemm_workgroups || !arrival_counters || !single_call_streams) return HBL_E_NULL;
     if (n_problems < 1 || n_problems > kMaxGroup) return HBL_E_SHAPE;
     DecodeArgs da = {};
     static int32_t dummy_partial;
@@ -364,7 +364,7 @@ int hbl_test_grouped_plan(const hbl_problem* problems, int n_problems, int* kspl
         dp.partial = &dummy_partial;   // the grouped call always brings a partial buffer
         single_call_streams[i] = decode_stream_preferred(q.T, q.K, q.N) ? 1 : 0;
     }
-    const int rc = decode_plan_for_tests(da, gemm_workgroups, reduce_workgroups);
+    const int rc = decode_plan_for_tests(da, gemm_workgroups, arrival_counters);
     if (rc != HBL_OK) return rc;
     for (int i = 0; i < n_problems; ++i) ksplit[i] = da.p[i].ksplit;
     return HBL_OK;

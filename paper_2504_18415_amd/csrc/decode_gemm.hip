@@ -18,8 +18,8 @@
 //  - shared (T <= 64): the four waves take four row tiles over one K range and share the code stage
 //    (32 or 64 rows): one barrier per stage.  A K range split over workgroups leaves int32 slices in the
 //    workspace; the workgroup of a K range that finishes last (an arrival counter) adds the others' slices to
-//    its own accumulators and dequantises.  (A launch with more split row groups than there are counters in a
-//    slot falls back to a second launch that adds the slices.)
+//    its own accumulators and dequantises.  (A group with more split row groups than a slot has counters runs
+//    without the split.)
 #include <atomic>
 
 #include "gemm_common.h"
@@ -214,8 +214,7 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     for (int j = 0; j < TT; ++j) sd[j] = 0.0f;
 #pragma unroll
     for (int g = 0; g < 4; ++g) wsum[g] = v4i{0, 0, 0, 0};
-    const bool reduce_here = write_partial && p.arrive_begin >= 0;   // (uniform) the last workgroup of a K range to arrive adds the slices
-    if (writer && (!write_partial || reduce_here)) {
+    if (writer) {   // (with a K range split over workgroups any of them may turn out to be the one that dequantises)
         alpha = p.w_scales[(nt * 32) / p.rows_per_group];
 #pragma unroll
         for (int j = 0; j < TT; ++j) {
@@ -341,22 +340,8 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
         }
     if constexpr (SHARE) {
         if (write_partial) {   // uniform over the workgroup
-            // this workgroup's slice of the K range, as int32 tiles (exact)
-            if (!reduce_here) {   // [ksplit][T][N] for the reduction launch
-                if (writer) {
-#pragma unroll
-                    for (int j = 0; j < TT; ++j) {
-                        const int t = j * 32 + (lane & 31);
-                        if (t >= p.T) continue;
-#pragma unroll
-                        for (int g = 0; g < 4; ++g)
-                            *reinterpret_cast<v4i*>(p.partial + ((size_t)ks * p.T + t) * p.N + nt * 32 + 8 * g + 4 * (lane >> 5)) = tot[j][g];
-                    }
-                }
-                return;
-            }
-            // Reduced here: the slices are only ever read by a workgroup of the same shape, so they are kept as the
-            // lanes hold them - quad (j, g) of wave `wave` of slice k at v4i index (((k * groups + group) * 4 + wave) *
+            // This workgroup's slice of the K range, as int32 tiles (exact).  A slice is only ever read by a workgroup
+            // of the same shape, so it is kept as the lanes hold it - quad (j, g) of wave `wave` of slice k at v4i index (((k * groups + group) * 4 + wave) *
             // 4 TT + 4 j + g) * 64 + lane: every store and load instruction moves 1 KiB of consecutive bytes.  The
             // stores are device-scope (write-through): readable from the other XCDs without a write-back of this L2.
             const int groups = (p.N / 32 + 3) / 4;
@@ -414,22 +399,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_gemm_kernel(c
     else decode_body<SHARE, TT, RQ, D, NW, false>(p, w, lds, args.arrive);
 }
 
-// Second launch of the shared form, taken only when a launch has more split row groups than arrival counters:
-// adds the int32 partial tiles in fixed order (exact) and applies the dequantising epilogue.
-__global__ __launch_bounds__(256) void decode_reduce_kernel(const DecodeArgs args) {
-    const DecodeProblem p = args.p[group_index_of(args.red_begin, args.n, (int)blockIdx.x)];
-    const int quads = p.N / 4;
-    const int64_t idx = (int64_t)((int)blockIdx.x - p.red_begin) * 256 + threadIdx.x;
-    if (p.ksplit <= 1 || idx >= (int64_t)p.T * quads) return;
-    const int t = (int)(idx / quads);
-    const int n = (int)(idx % quads) * 4;
-    v4i sum = {0, 0, 0, 0};
-    for (int k = 0; k < p.ksplit; ++k)
-        sum += *reinterpret_cast<const v4i*>(p.partial + ((size_t)k * p.T + t) * p.N + n);
-    *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
-        dequant_quad(sum, p.s_dequant[t], p.w_scales[n / p.rows_per_group], p.code_offset, p.w_row_sum + n);
-}
-
 // Arrival counters of the shared form's in-kernel reduction: one per group of four row tiles whose K range is split
 // over workgroups.  A counter wraps at the number of slices, so it is back at zero when its launch is over and needs
 // no initialisation beyond the zeros the array is loaded with.  The host hands the kArriveSlots slots out round-robin:
@@ -456,23 +425,11 @@ int next_arrive_slot(unsigned int** out) {
 }
 
 template <bool SHARE, int TT, int RQ, int D, int NW = 4>
-int launch_form(const DecodeArgs& planned, int wgs, int red_wgs, hipStream_t stream) {
+int launch_form(const DecodeArgs& planned, int wgs, int counters, hipStream_t stream) {
     DecodeArgs a = planned;
     a.arrive = nullptr;
-    for (int i = 0; i < a.n; ++i) a.p[i].arrive_begin = -1;
-    if (SHARE && red_wgs != 0) {   // some K range is split over workgroups: reduce in the kernel if the counters suffice
-        int words = 0;
-        for (int i = 0; i < a.n; ++i)
-            if (a.p[i].ksplit > 1) {
-                a.p[i].arrive_begin = words;
-                words += (a.p[i].N / 32 + 3) / 4;
-            }
-        if (words <= kArriveWords) {
-            if (const int rc = next_arrive_slot(&a.arrive); rc != HBL_OK) return rc;
-            red_wgs = 0;
-        } else {
-            for (int i = 0; i < a.n; ++i) a.p[i].arrive_begin = -1;
-        }
+    if (counters != 0) {   // some K range is split over workgroups
+        if (const int rc = next_arrive_slot(&a.arrive); rc != HBL_OK) return rc;
     }
     constexpr int ROWS = SHARE ? TT * 32 : RQ * 8;
     constexpr size_t lds = (size_t)D * ((SHARE ? 1 : NW) * ROWS * kBK + NW * 1024);
@@ -480,9 +437,6 @@ int launch_form(const DecodeArgs& planned, int wgs, int red_wgs, hipStream_t str
     static std::atomic<uint64_t> lds_allowed{0};   // per instantiation: devices already set up
     if (const int rc = allow_dynamic_lds(kern, lds, lds_allowed); rc != HBL_OK) return rc;
     launch_kernel("decode_gemm_kernel", kern, dim3((unsigned)wgs), dim3(64 * NW), lds, stream, a);
-    int rc = after_launch();
-    if (rc != HBL_OK || red_wgs == 0) return rc;
-    launch_kernel("decode_reduce_kernel", decode_reduce_kernel, dim3((unsigned)red_wgs), dim3(256), 0, stream, a);
     return after_launch();
 }
 
@@ -498,7 +452,7 @@ int problem_wgs(const DecodeProblem& p, bool share) {
 // 2 workgroups) split further, down to 8 tiles per wave.  The streaming form adds the slices inside a
 // workgroup, so a split is free; the shared form needs the partial buffer and a second launch, so it
 // splits further only when less than three quarters of the CUs would get a workgroup.
-void plan(DecodeArgs& a, bool share, int* wgs_out, int* red_out) {
+void plan(DecodeArgs& a, bool share, int* wgs_out, int* counters_out) {
     const int enough = share ? 192 : 384;
     int total = 0;
     for (int i = 0; i < a.n; ++i) {
@@ -521,16 +475,25 @@ void plan(DecodeArgs& a, bool share, int* wgs_out, int* red_out) {
             total += problem_wgs(p, share);
         }
     }
-    int wgs = 0, red = 0;
+    // a K range split over workgroups (shared form) needs one arrival counter per group of four row tiles; a group
+    // with more of them than a slot holds runs without that split
+    int counters = 0;
+    for (int i = 0; i < a.n; ++i)
+        if (share && a.p[i].ksplit > 1) counters += (a.p[i].N / 32 + 3) / 4;
+    if (counters > kArriveWords) {
+        for (int i = 0; i < a.n; ++i) a.p[i].ksplit = 1;
+        counters = 0;
+    }
+    int wgs = 0, next_counter = 0;
     for (int i = 0; i < a.n; ++i) {
         DecodeProblem& p = a.p[i];
         p.wg_begin = a.wg_begin[i] = wgs;
         wgs += problem_wgs(p, share);
-        p.red_begin = a.red_begin[i] = red;
-        if (share && p.ksplit > 1) red += (int)(((int64_t)p.T * (p.N / 4) + 255) / 256);
+        p.arrive_begin = next_counter;
+        if (share && p.ksplit > 1) next_counter += (p.N / 32 + 3) / 4;
     }
     *wgs_out = wgs;
-    *red_out = red;
+    *counters_out = counters;
 }
 
 // A single streaming-form problem whose four-wave plan would leave long serial chains of tiles on few
@@ -547,7 +510,7 @@ void plan_wide(DecodeArgs& a, int nw, int* wgs_out) {
     DecodeProblem& p = a.p[0];
     p.ksplit = nw;   // one row tile per workgroup, its K range over all waves: 8 tiles or more per wave (nkb >= 64)
     p.wg_begin = a.wg_begin[0] = 0;
-    p.red_begin = a.red_begin[0] = 0;
+    p.arrive_begin = 0;
     *wgs_out = (p.N / 32 * p.ksplit + nw - 1) / nw;
 }
 
@@ -561,22 +524,22 @@ bool decode_stream_preferred(int64_t T, int64_t K, int64_t N) {
     a.p[0].K = (int)K;
     a.p[0].N = (int)N;
     if (wide_waves(a, (int)T) != 0) return true;
-    int wgs, red;
-    plan(a, false, &wgs, &red);
+    int wgs, counters;
+    plan(a, false, &wgs, &counters);
     // a wave's tiles are a serial chain: few workgroups with long chains leave most of the chip idle
     return (K / 128) / a.p[0].ksplit <= 16 || wgs >= 256;
 }
 
-int decode_plan_for_tests(DecodeArgs& a, int* wgs, int* red_wgs) {
+int decode_plan_for_tests(DecodeArgs& a, int* wgs, int* counters) {
     int max_t = 0;
     for (int i = 0; i < a.n; ++i) max_t = a.p[i].T > max_t ? a.p[i].T : max_t;
     if (a.n <= 0 || max_t > 64) return HBL_E_SHAPE;
     if (const int nw = wide_waves(a, max_t); nw != 0) {
         plan_wide(a, nw, wgs);
-        *red_wgs = 0;
+        *counters = 0;
         return HBL_OK;
     }
-    plan(a, max_t > 16, wgs, red_wgs);
+    plan(a, max_t > 16, wgs, counters);
     return HBL_OK;
 }
 
@@ -585,19 +548,19 @@ int launch_decode_gemm(DecodeArgs& a, hipStream_t stream) {
     int max_t = 0;
     for (int i = 0; i < a.n; ++i) max_t = a.p[i].T > max_t ? a.p[i].T : max_t;
     if (max_t > 64) return HBL_E_SHAPE;
-    int wgs, red;
+    int wgs, counters;
     if (const int nw = wide_waves(a, max_t); nw != 0) {
         plan_wide(a, nw, &wgs);
         return max_t <= 8 ? launch_form<false, 1, 1, 4, 8>(a, wgs, 0, stream)
                           : launch_form<false, 1, 2, 4, 8>(a, wgs, 0, stream);
     }
-    plan(a, max_t > 16, &wgs, &red);
+    plan(a, max_t > 16, &wgs, &counters);
     // Stages in flight per wave: 4.  Shallow is best (3 to 8 measured): the memory-level parallelism comes from
     // the 2048 waves of a full grid, and deeper rings only cost LDS and queueing.
     if (max_t <= 8) return launch_form<false, 1, 1, 4>(a, wgs, 0, stream);
     if (max_t <= 16) return launch_form<false, 1, 2, 4>(a, wgs, 0, stream);
-    if (max_t <= 32) return launch_form<true, 1, 1, 4>(a, wgs, red, stream);
-    return launch_form<true, 2, 1, 4>(a, wgs, red, stream);
+    if (max_t <= 32) return launch_form<true, 1, 1, 4>(a, wgs, counters, stream);
+    return launch_form<true, 2, 1, 4>(a, wgs, counters, stream);
 }
 
 }  // namespace hbl

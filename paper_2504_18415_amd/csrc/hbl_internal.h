@@ -246,14 +246,12 @@ struct DecodeProblem {
     int f6;                    // codes are bf6 records (record image): the fp6 x fp4 matrix cores do the work
     int ksplit;                // K slices per row tile
     int wg_begin;              // first workgroup of this problem in the GEMM grid
-    int red_begin;             // first workgroup of this problem in the reduction grid
     int arrive_begin;          // first arrival counter of this problem (K split over workgroups, reduced in the kernel)
 };
 struct DecodeArgs {
     int n;
-    int wg_begin[kMaxGroup];    // = p[i].wg_begin, p[i].red_begin (filled with them by the launch plan)
-    int red_begin[kMaxGroup];
-    unsigned int* arrive;       // arrival counters of this launch, or nullptr: split K ranges go to the reduction launch
+    int wg_begin[kMaxGroup];    // = p[i].wg_begin (filled with it by the launch plan)
+    unsigned int* arrive;       // arrival counters of this launch (set by the launch when some K range is split over workgroups)
     DecodeProblem p[kMaxGroup];
 };
 // Index of the problem workgroup `wg` belongs to: the last one whose first workgroup is not beyond it.
@@ -264,10 +262,10 @@ __host__ __device__ inline int group_index_of(const int* begin, int n, int wg) {
         if (i < n && wg >= begin[i]) idx = i;
     return idx;
 }
-// Fills ksplit / wg_begin / red_begin and launches.  Every problem needs T <= 64.
+// Fills ksplit / wg_begin / arrive_begin and launches.  Every problem needs T <= 64.
 int launch_decode_gemm(DecodeArgs& args, hipStream_t stream);
 // The launch plan launch_decode_gemm would use (K splits, grid sizes), without launching: host logic only.
-int decode_plan_for_tests(DecodeArgs& args, int* wgs, int* red_wgs);
+int decode_plan_for_tests(DecodeArgs& args, int* wgs, int* arrival_counters);
 // Whether a single projection with T <= 16 is better served by the streaming form of that launch than
 // by the split-K pair of launch_ternary_gemm.
 bool decode_stream_preferred(int64_t T, int64_t K, int64_t N);

@@ -15,12 +15,13 @@ extern "C" {
  * Host only (no launch, no device access): the plan the small-batch GEMM launch of a grouped call would
  * use for these problems (every T in 1..64, n_problems <= 8; only T, K, N and hadamard are read).
  *   ksplit[i]              K slices per 32-row weight tile of problem i (inside a workgroup when every
- *                          T <= 16, over workgroups plus a reduction launch otherwise)
- *   gemm_workgroups        grid size of the GEMM launch;  reduce_workgroups  of the reduction (0 = none)
+ *                          T <= 16, over workgroups otherwise - the last of them to finish adds the slices)
+ *   gemm_workgroups        grid size of the GEMM launch
+ *   arrival_counters       groups of four row tiles whose K range is split over workgroups (0 = none)
  *   single_call_streams[i] 1 if a single forward call on problem i uses the weight-streaming kernel
  */
 int hbl_test_grouped_plan(const hbl_problem* problems, int n_problems, int* ksplit, int* gemm_workgroups,
-                          int* reduce_workgroups, int* single_call_streams);
+                          int* arrival_counters, int* single_call_streams);
 
 /*
  * The integer contraction of Eq. 7 through one named workgroup tile of a prefill GEMM kernel (T > 64):

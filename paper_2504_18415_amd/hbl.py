@@ -448,15 +448,15 @@ def ln_fwht_quant(x: torch.Tensor, ln_gain: torch.Tensor, ln_eps: float, bits: i
 
 def grouped_plan(shapes):
     """Host-only: launch plan of the small-batch GEMM for [(T, K, N, hadamard), ...] ->
-    (ksplit list, gemm workgroups, workgroups of the reduction launch that a K split over workgroups would need
-    if it were not reduced inside the GEMM launch, list of "single call streams" flags)."""
+    (ksplit list, gemm workgroups, arrival counters = groups of four row tiles whose K range is split over
+    workgroups and reduced by the last of them, list of "single call streams" flags)."""
     n = len(shapes)
     arr = (Problem * n)(*[Problem(0, BF16, 4, int(bool(h)), 0, T, K, N, 0, 0, 1, 0) for (T, K, N, h) in shapes])
     ks = (ctypes.c_int * n)()
     st = (ctypes.c_int * n)()
-    wgs, red = ctypes.c_int(0), ctypes.c_int(0)
-    _check(lib().hbl_test_grouped_plan(arr, n, ks, ctypes.byref(wgs), ctypes.byref(red), st), "grouped_plan")
-    return list(ks), wgs.value, red.value, [bool(v) for v in st]
+    wgs, counters = ctypes.c_int(0), ctypes.c_int(0)
+    _check(lib().hbl_test_grouped_plan(arr, n, ks, ctypes.byref(wgs), ctypes.byref(counters), st), "grouped_plan")
+    return list(ks), wgs.value, counters.value, [bool(v) for v in st]
 
 
 def kv_quant_absmax(x: torch.Tensor, bits: int, eps: float = EPS, packed: Optional[torch.Tensor] = None,

@@ -158,9 +158,10 @@ def test_small_batch_launch_plan(L):
         ks, wgs, red, single = hbl.grouped_plan(layer(B))
         assert ks == [1, 1, 1, 4] and wgs == 96 + 32 + 256 + 128 and red == 0
         assert single == [True, True, True, True]
-    # batch > 16: shared form; only the K = 16384 problem is split, over workgroups, and needs the reduction
+    # batch > 16: shared form; only the K = 16384 problem is split, over workgroups: one arrival counter per group
+    # of four row tiles of it
     ks, wgs, red, single = hbl.grouped_plan(layer(64))
-    assert ks == [1, 1, 1, 4] and wgs == 512 and red == 64 * 4096 // 4 // 256 and single == [False] * 4
+    assert ks == [1, 1, 1, 4] and wgs == 512 and red == 4096 // 128 and single == [False] * 4
     # a single small problem is split down to 8 tiles per wave to reach more CUs
     ks, wgs, red, _ = hbl.grouped_plan([(4, 4096, 4096, True)])
     assert ks == [4] and wgs == 128 and red == 0
@@ -170,11 +171,14 @@ def test_small_batch_launch_plan(L):
     ks, wgs, red, single = hbl.grouped_plan([(16, 16384, 4096, True)])
     assert ks == [8] and wgs == 128 and red == 0 and single == [True]
     ks, wgs, red, single = hbl.grouped_plan([(32, 16384, 4096, True)])   # shared form: split over workgroups
-    assert ks == [4] and wgs == 128 and red > 0 and single == [False]
+    assert ks == [4] and wgs == 128 and red == 32 and single == [False]
     ks, wgs, red, _ = hbl.grouped_plan([(4, 128, 96, False)])        # one K block: nothing to split
     assert ks == [1] and wgs == 1 and red == 0
     ks, wgs, red, _ = hbl.grouped_plan([(40, 8192, 160, True)])      # shared form, few rows: split over workgroups
-    assert ks == [4] and wgs == 2 * 4 and red == (40 * 160 // 4 + 255) // 256
+    assert ks == [4] and wgs == 2 * 4 and red == 2
+    # more split row groups than a slot has arrival counters: the group runs without the split
+    ks, wgs, red, _ = hbl.grouped_plan([(40, 8192, 128 * 2049, True)])
+    assert ks == [1] and wgs == 2049 and red == 0
     with pytest.raises(hbl.HblError):
         hbl.grouped_plan([(65, 4096, 4096, True)])
     with pytest.raises(hbl.HblError):
