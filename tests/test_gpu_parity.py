@@ -824,15 +824,18 @@ def test_ln_bitlinear_forward_and_grouped(hbl, T, K, N, hadamard, bits):
     assert np.array_equal(host_bf16_bits(ys[1]), O.bitlinear_forward(xo, wo_ref, ao_ref, bits, True, EPS))
 
 
-def test_grouped_call_in_a_hip_graph_replays_exactly(hbl):
+@pytest.mark.parametrize("batch", [8, 40])
+def test_grouped_call_in_a_hip_graph_replays_exactly(hbl, batch):
     """The grouped call captured into a HIP graph (kernel nodes only: its argument blocks travel as
     kernel arguments) and replayed with fresh inputs between replays, eager work and
-    synchronisations in between: every replay must equal the eager result on the same inputs."""
-    note("grouped call under graph replay")
+    synchronisations in between: every replay must equal the eager result on the same inputs.
+    At batch 40 the K = 16384 problem is split over workgroups, so every replay counts its arrivals in
+    the same words of the library's counter array: they must be back at zero each time."""
+    note(f"grouped call under graph replay, batch {batch}")
     common = dict(outlier_frac=0.01, outlier_scale=30.0)
-    sites = [synth.Site("r_h", 8, 4096, 256, hadamard=True, seed=51, **common),
-             synth.Site("r_p", 8, 1536, 160, hadamard=False, seed=52, groups=1, **common),
-             synth.Site("r_big", 8, 16384, 64, hadamard=True, seed=53, **common)]
+    sites = [synth.Site("r_h", batch, 4096, 256, hadamard=True, seed=51, **common),
+             synth.Site("r_p", batch, 1536, 160, hadamard=False, seed=52, groups=1, **common),
+             synth.Site("r_big", batch, 16384, 192, hadamard=True, seed=53, **common)]
     packs = [setup_weights(hbl, s) for s in sites]
     xs = [dev_x(synth.make_x(s)) for s in sites]
     ys = [torch.empty((s.T, s.N), dtype=torch.bfloat16, device="cuda") for s in sites]
