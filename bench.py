@@ -354,11 +354,11 @@ def bench_decode(args, hbl, synth, torch, np):
                 # FETCH_SIZE + WRITE_SIZE of the layer's GEMM launch at batch <= 8 (profiles/hbm_traffic_counters.txt)
                 "traffic": measured_traffic("decode_gemm_kernel", "layer_7b_batch8"),
                 "note": "call level: both launches of the grouped call; the GEMM launch alone streams the layer's "
-                        "67.1 MB in 15 us (profiles/decode_layer_kernels_config5.txt)"}
+                        "67.1 MB in 13-14 us (profiles/decode_layer_kernels_config5.txt)"}
     return {"layers_cycled": layers, "weight_bytes_per_layer": w_bytes, "roofline": roofline,
             "launch": "one HIP graph of all layers; sequential = four forward calls per layer in model order "
-                      "(2 kernel nodes each, 3 above batch 16), grouped = one hbl_bitlinear_forward_grouped call per layer "
-                      "(one quantiser launch, one weight-streaming GEMM launch, one reduction launch for batch > 16)",
+                      "(2 kernel nodes each), grouped = one hbl_bitlinear_forward_grouped call per layer "
+                      "(one quantiser launch, one weight-streaming GEMM launch)",
             "batch": res}
 
 

@@ -447,11 +447,12 @@ int problem_wgs(const DecodeProblem& p, bool share) {
 }
 
 
-// K split of every problem, then each problem's first workgroup in the GEMM and reduction grids.
+// K split of every problem, then each problem's first workgroup in the grid and its first arrival counter.
 // About 32 weight tiles (32 KiB) per wave; while the grid is too small to occupy the chip (256 CUs x
 // 2 workgroups) split further, down to 8 tiles per wave.  The streaming form adds the slices inside a
-// workgroup, so a split is free; the shared form needs the partial buffer and a second launch, so it
-// splits further only when less than three quarters of the CUs would get a workgroup.
+// workgroup, so a split is free; the shared form needs the partial buffer and ends with the last workgroup of a
+// K range adding the others' slices, so it splits further only when less than three quarters of the CUs would get
+// a workgroup.
 void plan(DecodeArgs& a, bool share, int* wgs_out, int* counters_out) {
     const int enough = share ? 192 : 384;
     int total = 0;

@@ -206,8 +206,8 @@ int launch_ternary_gemm_f6f4(const int8_t* code_records, int64_t T, int64_t K, c
 
 // ---------------------------------------------------------------------------------------------
 // Grouped small-batch path: up to kMaxGroup independent projections (T <= 64 each) served by one
-// quantiser launch and one GEMM launch (plus one reduction launch if some K range was split over
-// workgroups).  The argument blocks travel by value as kernel arguments: no table in device memory.
+// quantiser launch and one GEMM launch (a K range split over workgroups is reduced by the last of them to
+// finish).  The argument blocks travel by value as kernel arguments: no table in device memory.
 constexpr int kMaxGroup = 8;
 
 struct QuantProblem {
