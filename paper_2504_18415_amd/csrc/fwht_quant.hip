@@ -77,6 +77,17 @@ __device__ __forceinline__ void lane_butterfly4(float (&a)[4], float c) {
 #undef HBL_F
 }
 template <int CTRL>
+__device__ __forceinline__ void lane_butterfly2(float (&a)[2], float c) {
+#define HBL_F(N, SEL) "v_fmac_f32_dpp %" #N ", %" #N ", %2 " SEL " row_mask:0xf bank_mask:0xf\n\t"
+#define HBL_LANE_FMAC2(SEL) asm("s_nop 1\n\t" HBL_F(0, SEL) HBL_F(1, SEL) : "+v"(a[0]), "+v"(a[1]) : "v"(c))
+    if constexpr (CTRL == 0xB1) HBL_LANE_FMAC2("quad_perm:[1,0,3,2]");
+    else if constexpr (CTRL == 0x4E) HBL_LANE_FMAC2("quad_perm:[2,3,0,1]");
+    else if constexpr (CTRL == 0x141) HBL_LANE_FMAC2("row_half_mirror");
+    else HBL_LANE_FMAC2("row_ror:8");
+#undef HBL_LANE_FMAC2
+#undef HBL_F
+}
+template <int CTRL>
 __device__ __forceinline__ double dpp_move(double v) {
     const uint64_t u = __builtin_bit_cast(uint64_t, v);
     const uint64_t r = (uint64_t)dpp_move<CTRL>((uint32_t)u) | ((uint64_t)dpp_move<CTRL>((uint32_t)(u >> 32)) << 32);
@@ -133,6 +144,26 @@ __device__ __forceinline__ float wave_max(float m, int few_rows) {
 #pragma unroll
     for (int sft = 1; sft < 64; sft <<= 1) m = fmaxf(m, __shfl_xor(m, sft, 64));
     return m;
+}
+
+// Butterfly between lanes in one multiply-add per element (lane_butterfly4): v <- partner * c + v, c = -1 on the
+// lane whose index bit is set.  That lane then holds the negative of the reference's a - b; see the large-row body
+// for why a lane may simply carry that sign until the values meet their 1/sqrt(K) factor.
+template <int CTRL, int R, int CH>
+__device__ __forceinline__ void lane_stage_fma(float (&v)[R][CH], bool upper) {
+    const float c = upper ? -1.0f : 1.0f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if constexpr (CH == 2) {
+            lane_butterfly2<CTRL>(v[r], c);
+        } else {
+#pragma unroll
+            for (int e = 0; e < CH; e += 4) {
+                float (&q)[4] = *reinterpret_cast<float (*)[4]>(&v[r][e]);
+                lane_butterfly4<CTRL>(q, c);
+            }
+        }
+    }
 }
 
 template <int MASK, int R, int CH>
@@ -287,10 +318,14 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int64_t row_off = row * (int64_t)K;
+    // Position of this lane's chunks inside a group of 64.  With the transform, lane ^ (3 if bit 2 is set): flipping
+    // position bit 2 then flips lane bits 0-2 together, which is the one xor-4-like permutation DPP offers inside a
+    // row of 16 lanes (the half-row mirror, lane ^ 7); bits 0, 1 and 3 flip by quad permutes and a row rotation.
+    const int pos = HADAMARD ? lane ^ (((lane >> 2) & 1) * 3) : lane;
 
     float v[R][CH];
 #pragma unroll
-    for (int r = 0; r < R; ++r) load_chunk<CH, BF16>(x, row_off + (int64_t)((wave * R + r) * 64 + lane) * CH, v[r]);
+    for (int r = 0; r < R; ++r) load_chunk<CH, BF16>(x, row_off + (int64_t)((wave * R + r) * 64 + pos) * CH, v[r]);
 
     if (rp.ln_gain) {   // uniform: RMS normalisation ahead of the transform
         __shared__ double red_n[W];
@@ -303,7 +338,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float gv[CH];
-            load_chunk<CH, false>(rp.ln_gain, (int64_t)((wave * R + r) * 64 + lane) * CH, gv);
+            load_chunk<CH, false>(rp.ln_gain, (int64_t)((wave * R + r) * 64 + pos) * CH, gv);
 #pragma unroll
             for (int e = 0; e < CH; ++e) v[r][e] = (v[r][e] * rn) * gv[e];
         }
@@ -325,11 +360,11 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
                         v[r][e + h] = a - b;
                     }
         // lane bits
-        lane_stage<1>(v, lane);
-        lane_stage<2>(v, lane);
-        lane_stage<4>(v, lane);
-        lane_stage<8>(v, lane);
-        lane_stage<16>(v, lane);
+        lane_stage_fma<0xB1>(v, pos & 1);    // lane ^ 1 (quad_perm [1,0,3,2])
+        lane_stage_fma<0x4E>(v, pos & 2);    // lane ^ 2 (quad_perm [2,3,0,1])
+        lane_stage_fma<0x141>(v, pos & 4);   // lane ^ 7 (row_half_mirror)
+        lane_stage_fma<0x128>(v, pos & 8);   // lane ^ 8 (row_ror:8)
+        lane_stage<16>(v, lane);             // (partners share position bits 0-3, hence the sign they carry)
         lane_stage<32>(v, lane);
         // r bits
 #pragma unroll
@@ -379,7 +414,8 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
                         }
                     }
         }
-        const float c_n = (float)(1.0 / sqrt((double)K));
+        // 1/sqrt(K), with the sign the lane stages left on this lane's values: (-1)^(set bits among position bits 0-3)
+        const float c_n = (__builtin_popcount(pos & 15) & 1) ? -(float)(1.0 / sqrt((double)K)) : (float)(1.0 / sqrt((double)K));
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -393,7 +429,7 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int g = exchanged ? (r % W) * R + (r / W) * W + wave : wave * R + r;
-            store_xr<CH>(codes, code_offset, row_off + (int64_t)(g * 64 + lane) * CH, v[r]);
+            store_xr<CH>(codes, code_offset, row_off + (int64_t)(g * 64 + pos) * CH, v[r]);
         }
         return;
     }
@@ -465,9 +501,9 @@ __device__ __forceinline__ void fwht_quant_body(int64_t row, int tid, const void
         } else {
             g = wave * R + r;
         }
-        int8_t* dst = codes + row_off + (int64_t)(g * 64 + lane) * CH;
+        int8_t* dst = codes + row_off + (int64_t)(g * 64 + pos) * CH;
         if constexpr (CH == 8) {
-            if (bf6) bf6_store_pair(codes, row, K, g * 64 + lane, bf6_pack4(packed[0]), bf6_pack4(packed[1]));
+            if (bf6) bf6_store_pair(codes, row, K, g * 64 + pos, bf6_pack4(packed[0]), bf6_pack4(packed[1]));
             else *reinterpret_cast<uint2*>(dst) = make_uint2(packed[0], packed[1]);
         } else if constexpr (CH == 4) {
             *reinterpret_cast<uint32_t*>(dst) = packed[0];
