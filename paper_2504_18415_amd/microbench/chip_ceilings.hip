@@ -198,6 +198,16 @@ int main() {
         printf("HBM read, 64 MiB per launch, %4d workgroups      %8.1f GB/s (%.1f us per launch)\n", wgs,
                chunk / t / 1e6, t * 1e3);
     }
+    // and one 64 MiB chunk read again and again: every launch after the first is served by the 256 MB
+    // memory-side cache, so what remains is the launch's ramp and drain and the fabric, not HBM
+    for (int wgs : {1024, 2048}) {
+        const size_t chunk = (size_t)64 << 20;
+        const float t = time_ms([&] {
+            for (int i = 0; i < 24; ++i) read_kernel<<<wgs, 256>>>(src, chunk / 16, dst);
+        }, 3) / 24;
+        printf("cached read, one 64 MiB chunk, %4d workgroups     %8.1f GB/s (%.1f us per launch)\n", wgs,
+               chunk / t / 1e6, t * 1e3);
+    }
     {   // the weight-streaming skeleton on the same 64 MiB chunks
         const int wgs = 512, tpw = (int)(((size_t)64 << 20) / 1024 / (wgs * 4));
         char* codes;
