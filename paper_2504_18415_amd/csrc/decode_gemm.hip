@@ -75,6 +75,11 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     constexpr int STAGE = XW + NW * 1024;             // + one packed weight tile per wave
     constexpr int XL = SHARE ? TT : RQ;               // code copies per wave per stage (8 rows each)
     constexpr int NACC = TT == 1 ? 2 : TT;
+    // PAIR (shared form, two token tiles, fp6 x fp4): a wave multiplies two weight tiles by one token tile instead of
+    // one weight tile by two token tiles - waves 2p and 2p + 1 share the weight tiles 2p, 2p + 1 of the stage and take
+    // token tile 0 and 1.  Same MFMAs, but 5 KiB of LDS operand reads per wave and stage instead of 7: at 33-64
+    // tokens the eight waves of a CU are bound by the LDS read rate (56 KiB per stage at 128 bytes per clock).
+    constexpr bool PAIR = SHARE && F6 && TT == 2;
     static_assert(D >= 3 && (ROWS & (ROWS - 1)) == 0, "pipeline depth / row count");
     static_assert(!SHARE || NW == 4, "the shared form is written for four waves");
     static_assert(NW * 4096 <= D * STAGE, "the in-workgroup reduction reuses the stage buffers");
@@ -96,6 +101,9 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     const int nt_max = p.N / 32 - 1;
     const bool live = nt <= nt_max;          // a wave past the last row tile streams that tile again, writes nothing
     const int ntc = live ? nt : nt_max;
+    // accumulator a of this wave: weight tile and token tile
+    auto tile_of = [&](int a) { return PAIR ? 4 * (w >> kl) + 2 * (wave >> 1) + a : nt; };
+    auto tok_tile_of = [&](int a) { return PAIR ? (wave & 1) : a; };
     const int kb0 = ks * nkb;
 
     // packed tiles are stored K-block-major (tile (nt, kb) at (kb * N/32 + nt) KiB): at any moment the waves
@@ -206,19 +214,20 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     // copies they would delay the stream.  (They return in order behind the D - 1 stages in flight, which
     // only makes the first waits below stricter than they need to be.)
     const bool write_partial = SHARE && p.ksplit > 1;
-    const bool writer = live && (SHARE || ks == 0);
+    const bool writer = (PAIR ? tile_of(0) <= nt_max : live) && (SHARE || ks == 0);
     constexpr bool TOK16 = F6 && !SHARE;     // the 16x16 accumulator layout: token = lane & 15
-    float alpha = 0.0f, sd[TT];
+    float alpha[TT], sd[TT];
     v4i wsum[4];
 #pragma unroll
-    for (int j = 0; j < TT; ++j) sd[j] = 0.0f;
+    for (int j = 0; j < TT; ++j) sd[j] = alpha[j] = 0.0f;
 #pragma unroll
     for (int g = 0; g < 4; ++g) wsum[g] = v4i{0, 0, 0, 0};
     if (writer) {   // (with a K range split over workgroups any of them may turn out to be the one that dequantises)
-        alpha = p.w_scales[(nt * 32) / p.rows_per_group];
 #pragma unroll
         for (int j = 0; j < TT; ++j) {
-            const int t = TOK16 ? (lane & 15) : j * 32 + (lane & 31);
+            const int tile = tile_of(j) <= nt_max ? tile_of(j) : nt_max;
+            alpha[j] = p.w_scales[(tile * 32) / p.rows_per_group];
+            const int t = TOK16 ? (lane & 15) : tok_tile_of(j) * 32 + (lane & 31);
             if (t < p.T) sd[j] = p.s_dequant[t];
         }
         if (!F6 && p.code_offset != 0) {
@@ -272,6 +281,26 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
             for (int hf = 0; hf < 2; ++hf)
                 facc[hf] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fp4_operand(wp[hf].x, wp[hf].y), xop, facc[hf],
                                                                             4 /*A: fp4*/, 3 /*B: bf6*/, 0, 0, 0, 0);
+        } else if constexpr (PAIR) {
+            v4i wpk[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                wpk[i] = *reinterpret_cast<const v4i*>(st + XW + (2 * (wave >> 1) + i) * 1024 + lane * 16);
+            v8i xop[2];
+            const char* rows = st + (wave & 1) * 32 * kRecordRowBytes;
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const v4i lo = *reinterpret_cast<const v4i*>(rows + xo_lo[s]);
+                const int2 hi = *reinterpret_cast<const int2*>(rows + xo_hi[s]);
+                xop[s] = v8i{lo[0], lo[1], lo[2], lo[3], hi.x, hi.y, 0, 0};
+            }
+            copies();
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    wacc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        fp4_operand((uint32_t)wpk[i][2 * s], (uint32_t)wpk[i][2 * s + 1]), xop[s], wacc[i], 4, 3, 0, 0, 0, 0);
         } else {
             const v4i wpk = *reinterpret_cast<const v4i*>(st + XW + wave * 1024 + lane * 16);
             v8i xop[2][TT];
@@ -338,11 +367,12 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
         for (int hf = 0; hf < 2; ++hf) {
             const int n = nt * 32 + 16 * hf + 4 * (lane >> 4);
             *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
-                dequant_quad_f32(facc[hf][0], facc[hf][1], facc[hf][2], facc[hf][3], sd[0], alpha);
+                dequant_quad_f32(facc[hf][0], facc[hf][1], facc[hf][2], facc[hf][3], sd[0], alpha[0]);
         }
         return;
     }
-    // lane holds token 32j + (lane & 31); register quad g holds features 8g + 4*(lane >> 5) + 0..3
+    // accumulator j (token tile j, or weight tile j of the wave's two in the pair form): lane holds token (lane & 31)
+    // of its token tile; register quad g holds features 8g + 4*(lane >> 5) + 0..3 of its weight tile
     v4i tot[TT][4];
 #pragma unroll
     for (int j = 0; j < TT; ++j)
@@ -393,16 +423,16 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     }
 #pragma unroll
     for (int j = 0; j < TT; ++j) {
-        const int t = j * 32 + (lane & 31);
-        if (t >= p.T) continue;
+        const int t = tok_tile_of(j) * 32 + (lane & 31);
+        if (t >= p.T || tile_of(j) > nt_max) continue;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int n = nt * 32 + 8 * g + 4 * (lane >> 5);
+            const int n = tile_of(j) * 32 + 8 * g + 4 * (lane >> 5);
             if constexpr (F6) {
                 *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) =
-                    dequant_quad_f32((float)tot[j][g][0], (float)tot[j][g][1], (float)tot[j][g][2], (float)tot[j][g][3], sd[j], alpha);
+                    dequant_quad_f32((float)tot[j][g][0], (float)tot[j][g][1], (float)tot[j][g][2], (float)tot[j][g][3], sd[j], alpha[j]);
             } else {
-                *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) = dequant_quad_sums(tot[j][g], sd[j], alpha, p.code_offset, wsum[g]);
+                *reinterpret_cast<uint2*>(p.y + (size_t)t * p.N + n) = dequant_quad_sums(tot[j][g], sd[j], alpha[j], p.code_offset, wsum[g]);
             }
         }
     }
