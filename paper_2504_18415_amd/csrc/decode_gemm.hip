@@ -80,6 +80,7 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     // token tile 0 and 1.  Same MFMAs, but 5 KiB of LDS operand reads per wave and stage instead of 7: at 33-64
     // tokens the eight waves of a CU are bound by the LDS read rate (56 KiB per stage at 128 bytes per clock).
     constexpr bool PAIR = SHARE && F6 && TT == 2;
+    constexpr bool PAIRED = SHARE && TT == 2;   // two stages per wait and barrier (below)
     static_assert(D >= 3 && (ROWS & (ROWS - 1)) == 0, "pipeline depth / row count");
     static_assert(!SHARE || NW == 4, "the shared form is written for four waves");
     static_assert(NW * 4096 <= D * STAGE, "the in-workgroup reduction reuses the stage buffers");
@@ -206,7 +207,7 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     static_assert(D - 2 <= 6, "wait_stage covers up to 5 later stages below the steady state");
 
 #pragma unroll
-    for (int s = 0; s < D - 1; ++s)
+    for (int s = 0; s < (PAIRED ? D - 2 : D - 1); ++s)
         if (s < nkb) issue(s, s);
 
     // Epilogue operands, requested right behind the first stages: under a saturated memory system a load
@@ -238,19 +239,10 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     }
 
 
-    int slot = 0;
-    for (int kb = 0; kb < nkb; ++kb) {
-        // stage kb has landed (for every wave, if the code stage is shared); the buffer read in the
-        // previous iteration is free for stage kb + D - 1
-        wait_stage(nkb - 1 - kb);
-        if constexpr (SHARE) asm volatile("s_barrier" ::: "memory");
-        // Order inside a stage: this stage's operand reads go out first, then the copies of stage kb + D - 1, then
-        // the MFMAs, so that the LDS latency passes while the copies are being accepted.  Worth 0.1-0.2 us per
-        // launch: the stream itself already runs at what HBM delivers, a shorter stage only lengthens the wait.
-        const char* st = lds + slot * STAGE;
-        const auto copies = [&]() {
-            if (kb + D - 1 < nkb) issue(kb + D - 1, slot == 0 ? D - 1 : slot - 1);
-        };
+    // One stage: its operand reads go out first, then `copies()` (the copies of a later stage), then the MFMAs, so
+    // that the LDS latency passes while the copies are being accepted (worth 0.1-0.2 us per launch in the streaming
+    // form: the stream itself already runs at what HBM delivers, a shorter stage only lengthens the wait).
+    auto stage_work = [&](const char* st, auto&& copies) {
         if constexpr (!F6) {
             const v4i wpk = *reinterpret_cast<const v4i*>(st + XW + wave * 1024 + lane * 16);
             v4i xop[4][TT];
@@ -322,7 +314,40 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
                     wacc[j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wop, xop[s][j], wacc[j], 4, 3, 0, 0, 0, 0);
             }
         }
-        slot = slot + 1 == D ? 0 : slot + 1;
+    };
+    if constexpr (PAIRED) {
+        // Shared form with two token tiles: one wait and one barrier per two stages (with one token tile the deeper
+        // ring this needs costs more than the barriers: 25.3 against 24.7 us per layer at batch 32).  The prologue has requested stages 0 .. D - 3; at the
+        // barrier of a pair every wave is done reading the previous pair, whose two buffers take stages kb + D - 2
+        // and kb + D - 1.
+        static_assert(D >= 6 && D % 2 == 0, "the paired loop keeps two pairs of stages in flight");
+        int slot = 0;
+        for (int kb = 0; kb < nkb; kb += 2) {
+            const int n2 = nkb - kb < 2 ? nkb - kb : 2;
+            const int issued = kb + D - 2 < nkb ? kb + D - 2 : nkb;
+            wait_stage(issued - kb - n2);
+            asm volatile("s_barrier" ::: "memory");
+            for (int u = 0; u < n2; ++u) {
+                const int ahead = kb + u + D - 2;
+                const int aslot = slot >= 2 ? slot - 2 : slot + D - 2;
+                stage_work(lds + slot * STAGE, [&]() {
+                    if (ahead < nkb) issue(ahead, aslot);
+                });
+                slot = slot + 1 == D ? 0 : slot + 1;
+            }
+        }
+    } else {
+        int slot = 0;
+        for (int kb = 0; kb < nkb; ++kb) {
+            // stage kb has landed (for every wave, if the code stage is shared); the buffer read in the previous
+            // iteration is free for stage kb + D - 1
+            wait_stage(nkb - 1 - kb);
+            if constexpr (SHARE) asm volatile("s_barrier" ::: "memory");
+            stage_work(lds + slot * STAGE, [&]() {
+                if (kb + D - 1 < nkb) issue(kb + D - 1, slot == 0 ? D - 1 : slot - 1);
+            });
+            slot = slot + 1 == D ? 0 : slot + 1;
+        }
     }
     if constexpr (!F6 && TT == 1) acc[0] += acc[1];
 
@@ -609,7 +634,7 @@ int launch_decode_gemm(DecodeArgs& a, hipStream_t stream) {
     if (max_t <= 8) return launch_form<false, 1, 1, 4>(a, wgs, 0, stream);
     if (max_t <= 16) return launch_form<false, 1, 2, 4>(a, wgs, 0, stream);
     if (max_t <= 32) return launch_form<true, 1, 1, 4>(a, wgs, counters, stream);
-    return launch_form<true, 2, 1, 4>(a, wgs, counters, stream);
+    return launch_form<true, 2, 1, 6>(a, wgs, counters, stream);
 }
 
 }  // namespace hbl
