@@ -238,7 +238,6 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
         }
     }
 
-
     // One stage: its operand reads go out first, then `copies()` (the copies of a later stage), then the MFMAs, so
     // that the LDS latency passes while the copies are being accepted (worth 0.1-0.2 us per launch in the streaming
     // form: the stream itself already runs at what HBM delivers, a shorter stage only lengthens the wait).
@@ -317,9 +316,9 @@ __device__ __forceinline__ void decode_body(const DecodeProblem& p, const int w,
     };
     if constexpr (PAIRED) {
         // Shared form with two token tiles: one wait and one barrier per two stages (with one token tile the deeper
-        // ring this needs costs more than the barriers: 25.3 against 24.7 us per layer at batch 32).  The prologue has requested stages 0 .. D - 3; at the
-        // barrier of a pair every wave is done reading the previous pair, whose two buffers take stages kb + D - 2
-        // and kb + D - 1.
+        // ring this needs costs more than the barriers: 25.3 against 24.7 us per layer at batch 32).  The prologue
+        // has requested stages 0 .. D - 3; at the barrier of a pair every wave is done reading the previous pair,
+        // whose two buffers take stages kb + D - 2 and kb + D - 1.
         static_assert(D >= 6 && D % 2 == 0, "the paired loop keeps two pairs of stages in flight");
         int slot = 0;
         for (int kb = 0; kb < nkb; kb += 2) {
