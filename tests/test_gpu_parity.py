@@ -691,6 +691,24 @@ def test_grouped_ragged_mix(hbl, bits, x_dtype):
         run_group(hbl, sites, [bits] * len(sites))
 
 
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("T", [33, 48, 64])
+def test_grouped_two_token_tiles_short_and_odd_k(hbl, bits, T):
+    """33-64 tokens take the shared form with two token tiles, which waits and synchronises once per two
+    K-blocks and, on the fp6 x fp4 path, gives a wave two row tiles of weights: K ranges of 1, 3, 4, 5 and 9
+    blocks (shorter than the copy ring, odd tails) and row-tile counts that leave a wave one or no live tile."""
+    note(f"grouped two token tiles bits={bits} T={T}")
+    common = dict(outlier_frac=0.01, outlier_scale=30.0)
+    sites = [
+        synth.Site("p_k128", T, 128, 32, hadamard=True, seed=61, **common),
+        synth.Site("p_k384", T, 384, 96, hadamard=False, seed=62, **common),
+        synth.Site("p_k512", T, 512, 160, hadamard=True, seed=63, **common),
+        synth.Site("p_k640", T - 1, 640, 224, hadamard=False, seed=64, groups=1, **common),
+        synth.Site("p_k1152", T, 1152, 288, hadamard=False, seed=65, groups=3, **common),
+    ]
+    run_group(hbl, sites, [bits] * len(sites))
+
+
 def test_grouped_single_problem_and_fallbacks(hbl):
     """A group of one; a group with a large-T member, mixed bit widths or more than 8 problems runs
     problem by problem and must give the same results."""
