@@ -55,6 +55,19 @@ __device__ __forceinline__ void store_code_quad(int8_t* codes, int64_t t, int K,
         *reinterpret_cast<uint2*>(row + record_hi_offset(r, s, h)) = make_uint2(d1, d2);
     }
 }
+
+// Store the 32 codes of features [32*rec, 32*rec + 32) of token t - a whole record, given as six dwords (feature
+// 32*rec + i at bits [6i, 6i+6)) - as its 16-byte and its 8-byte piece.  The row address is uniform over a
+// workgroup that works on one token and the rest is a 32-bit per-lane offset.
+__device__ __forceinline__ void store_code_record(int8_t* codes, int64_t t, int K, int rec, uint32_t d0, uint32_t d1,
+                                                  uint32_t d2, uint32_t d3, uint32_t d4, uint32_t d5) {
+    const int r = (int)(t & (kPanelTokens - 1));
+    const int kb = rec >> 2, s = (rec >> 1) & 1, h = rec & 1;
+    char* row = reinterpret_cast<char*>(codes) + (size_t)(t >> 7) * (size_t)(K >> 7) * kRecordBlockBytes + r * kRecordRowBytes;
+    const uint32_t blk = (uint32_t)kb * kRecordBlockBytes;
+    *reinterpret_cast<uint4*>(row + (blk + (uint32_t)record_lo_offset(r, s, h))) = make_uint4(d0, d1, d2, d3);
+    *reinterpret_cast<uint2*>(row + (blk + (uint32_t)record_hi_offset(r, s, h))) = make_uint2(d4, d5);
+}
 #endif
 
 }  // namespace hbl
