@@ -140,6 +140,68 @@ __global__ __launch_bounds__(256, 2) void stream_skeleton_kernel(const char* __r
     if (x == 0x12345678u || acc[0][0] + acc[1][1] == 1.2345f) sink[0] = make_uint4(x, 0, 0, 0);
 }
 
+// Skeleton of the small-batch kernel's shared form (17-64 tokens): per stage the four waves of a workgroup copy 4 x 1 KiB
+// of weights and XC x 4 x 768 bytes of codes (XC = 1: 32 token rows, 2: 64) into one stage buffer, meet at a barrier (every
+// stage, or every second one with PAIRB = 2), and with WORK read two weight tiles and one token tile and issue 4 MFMAs.
+template <int D, int XC, bool WORK, int PAIRB>
+__global__ __launch_bounds__(256, 2) void shared_skeleton_kernel(const char* __restrict__ src, const char* __restrict__ codes,
+                                                                 int tiles_per_wave, uint4* sink) {
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
+    constexpr int XB = XC * 4 * 768, STAGE = XB + 4096;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds;
+    const size_t wid = (size_t)blockIdx.x * 4 + wave;
+    auto issue = [&](int it, int slot) {
+        for (int m = 0; m < XC; ++m)
+            lds_dma16_first48(lds0 + slot * STAGE + (wave + 4 * m) * 768, codes + (size_t)it * 12288 + (wave + 4 * m) * 768, lane * 16);
+        lds_dma16(lds0 + slot * STAGE + XB + wave * 1024, src + (wid * tiles_per_wave + it) * 1024, lane * 16);
+    };
+    constexpr int PER = XC + 1;
+    constexpr int AHEAD = PAIRB == 2 ? D - 2 : D - 1;
+    for (int s = 0; s < AHEAD; ++s)
+        if (s < tiles_per_wave) issue(s, s);
+    v16f acc[2];
+    for (int i = 0; i < 2; ++i) for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    unsigned x = 0;
+    int slot = 0;
+    for (int it = 0; it < tiles_per_wave; it += PAIRB) {
+        // steady state only (tiles_per_wave is a multiple of PAIRB and much larger than D): the tail waits for everything
+        if (tiles_per_wave - it > AHEAD) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((AHEAD - PAIRB) * PER) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        asm volatile("s_barrier" ::: "memory");
+        for (int u = 0; u < PAIRB; ++u) {
+            const char* st = lds + slot * STAGE;
+            uint4 w0, w1, lo0, lo1; uint2 hi0, hi1;
+            if (WORK) {
+                w0 = *reinterpret_cast<const uint4*>(st + XB + (2 * (wave >> 1)) * 1024 + lane * 16);
+                w1 = *reinterpret_cast<const uint4*>(st + XB + (2 * (wave >> 1) + 1) * 1024 + lane * 16);
+                const char* rows = st + (XC == 2 ? (wave & 1) * 32 * 96 : 0) + (lane & 31) * 96;
+                lo0 = *reinterpret_cast<const uint4*>(rows + (lane >> 5) * 32);
+                hi0 = *reinterpret_cast<const uint2*>(rows + 16 + (lane >> 5) * 8);
+                lo1 = *reinterpret_cast<const uint4*>(rows + 48 + (lane >> 5) * 32 - (lane >> 5) * 16);
+                hi1 = *reinterpret_cast<const uint2*>(rows + 64 + (lane >> 5) * 8);
+            } else {
+                x ^= *reinterpret_cast<const unsigned*>(st + XB + wave * 1024 + lane * 16);
+            }
+            const int ahead = it + u + AHEAD;
+            if (ahead < tiles_per_wave) { int as = slot + AHEAD; as = as >= D ? as - D : as; issue(ahead, as); }
+            if (WORK) {
+                const v8i b0 = {(int)lo0.x, (int)lo0.y, (int)lo0.z, (int)lo0.w, (int)hi0.x, (int)hi0.y, 0, 0};
+                const v8i b1 = {(int)lo1.x, (int)lo1.y, (int)lo1.z, (int)lo1.w, (int)hi1.x, (int)hi1.y, 0, 0};
+                const uint4 ws[2] = {w0, w1};
+                for (int i = 0; i < 2; ++i) {
+                    const v8i a0 = {(int)(ws[i].x & 0xAAAAAAAAu), (int)((ws[i].x << 1) & 0xAAAAAAAAu), (int)(ws[i].y & 0xAAAAAAAAu), (int)((ws[i].y << 1) & 0xAAAAAAAAu), 0, 0, 0, 0};
+                    const v8i a1 = {(int)(ws[i].z & 0xAAAAAAAAu), (int)((ws[i].z << 1) & 0xAAAAAAAAu), (int)(ws[i].w & 0xAAAAAAAAu), (int)((ws[i].w << 1) & 0xAAAAAAAAu), 0, 0, 0, 0};
+                    acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a0, b0, acc[i], 4, 3, 0, 0, 0, 0);
+                    acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a1, b1, acc[i], 4, 3, 0, 0, 0, 0);
+                }
+            }
+            slot = slot + 1 == D ? 0 : slot + 1;
+        }
+    }
+    if (x == 0x12345678u || acc[0][0] + acc[1][1] == 1.2345f) sink[0] = make_uint4(x, 0, 0, 0);
+}
+
 template <class F>
 float time_ms(F launch, int reps) {
     hipEvent_t e0, e1;
@@ -227,6 +289,16 @@ int main() {
             stream_skeleton_kernel<4, true, true><<<wgs, 256, 4 * 4 * 2048>>>(p, codes, tpw, dst); });
         run("stream skeleton: ring D=8, + code copy, reads, MFMA", [&](const char* p) {
             stream_skeleton_kernel<8, true, true><<<wgs, 256, 4 * 8 * 2048>>>(p, codes, tpw, dst); });
+        auto shared_case = [&](const char* name, auto kern, int ldsb) {
+            CHECK(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, ldsb));
+            run(name, [&](const char* p) { kern<<<wgs, 256, ldsb>>>(p, codes, tpw, dst); });
+        };
+        shared_case("shared skeleton: 32 token rows, barrier per stage, reads + 4 MFMA", shared_skeleton_kernel<4, 1, true, 1>,
+                    4 * (1 * 4 * 768 + 4096));
+        shared_case("shared skeleton: 64 token rows, barrier per stage, reads + 4 MFMA", shared_skeleton_kernel<4, 2, true, 1>,
+                    4 * (2 * 4 * 768 + 4096));
+        shared_case("shared skeleton: 64 token rows, barrier per 2 stages, ring of 6", shared_skeleton_kernel<6, 2, true, 2>,
+                    6 * (2 * 4 * 768 + 4096));
     }
     const float c = time_ms([&] { copy_kernel<<<4096, 256>>>(src, dst, bytes / 16); }, 5);
     printf("%-48s %8.1f GB/s (read + write)\n", "HBM copy, 2 GiB -> 2 GiB", 2.0 * bytes / c / 1e6);
