@@ -1033,13 +1033,14 @@ __device__ __forceinline__ void fwht_quant_bigrow_body(int64_t row, uint32_t tid
             for (int jj = 0; jj < 8; ++jj) c24[cbase ^ LC::qj(8 * half + jj)] = piece[jj];
         }
         isum = (int)fsum;
-        // Regroup through LDS.  K <= 8192: eight consecutive chunks (32 features, 24 bytes: one record) become six
-        // dwords, stored as the record's 16-byte and 8-byte piece by every lane (56 fewer vector instructions per
-        // row than the form below, whose even and odd lanes store different pieces: 2-6 % faster).  K = 16384 keeps
-        // four chunks (16 features, 12 bytes) per lane and step: there the record form measured 8 % slower
-        // (0.125 against 0.116 ms for 8192 rows) although it executes fewer instructions.
+        // Regroup through LDS.  Eight consecutive chunks (32 features, 24 bytes: one record) become six dwords,
+        // stored as the record's 16-byte and 8-byte piece by every lane (56 fewer vector instructions per row than
+        // the form below, whose even and odd lanes store different pieces: 2-6 % faster at K <= 8192; at K = 16384
+        // with fp32 rows 5 % faster, and it needs no spill there).  K = 16384 with bf16 rows keeps four chunks (16
+        // features, 12 bytes) per lane and step: there the record form measured 8 % slower (0.125 against 0.116 ms
+        // for 8192 rows) although it executes fewer instructions.
         __syncthreads();
-        if constexpr (LOG2K < 14) {
+        if constexpr (LOG2K < 14 || !BF16) {
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 const uint32_t rec = tid + NT * i;
